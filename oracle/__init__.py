@@ -1,0 +1,86 @@
+"""CPU oracle (test infrastructure only; see the header of ppd_oracle.c).
+
+`build()` compiles ppd_oracle.c with gcc; `kv_append` / `mixed_attention` are ctypes wrappers over numpy
+arrays of bf16 bit patterns (uint16).  `dense_attention` in bruteforce.py is a second, independent
+implementation that never touches the page pool.
+"""
+import ctypes
+import os
+import subprocess
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_SRC = os.path.join(_HERE, "ppd_oracle.c")
+_LIB = os.path.join(_HERE, "libppd_oracle.so")
+_lib = None
+
+
+def build(force=False):
+    """Compile the oracle (gcc -O2 -fopenmp; no fast-math, so the arithmetic is the source's)."""
+    if force or not os.path.exists(_LIB) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC):
+        subprocess.check_call(
+            ["gcc", "-O2", "-fopenmp", "-shared", "-fPIC", "-Wall", "-Wextra", "-o", _LIB, _SRC, "-lm"])
+    return _LIB
+
+
+def _load():
+    global _lib
+    if _lib is None:
+        build()
+        lib = ctypes.CDLL(_LIB)
+        vp, i32, i64 = ctypes.c_void_p, ctypes.c_int32, ctypes.c_int64
+        lib.ppd_oracle_kv_append.argtypes = [vp, vp, vp, vp, i64, i32, i32, i32, i64]
+        lib.ppd_oracle_kv_append.restype = i32
+        lib.ppd_oracle_mixed_attention.argtypes = [vp, vp, vp, i32, vp, vp, i32, i32, i32, i32, i32, i64,
+                                                   ctypes.c_float, vp, vp]
+        lib.ppd_oracle_mixed_attention.restype = i32
+        _lib = lib
+    return _lib
+
+
+def _ptr(a):
+    return a.ctypes.data_as(ctypes.c_void_p)
+
+
+def pool_elems(num_pages, Hkv, D, P):
+    return int(num_pages) * 2 * Hkv * P * D
+
+
+def kv_append(k, v, pool, slot_mapping, Hkv, D, P, num_pages):
+    """In-place append of k, v ([T, Hkv, D] uint16) into pool (flat uint16) at slot_mapping ([T] int64)."""
+    k = np.ascontiguousarray(k, dtype=np.uint16)
+    v = np.ascontiguousarray(v, dtype=np.uint16)
+    slot_mapping = np.ascontiguousarray(slot_mapping, dtype=np.int64)
+    assert pool.dtype == np.uint16 and pool.flags.c_contiguous and pool.size == pool_elems(num_pages, Hkv, D, P)
+    T = slot_mapping.shape[0]
+    assert k.shape == (T, Hkv, D) and v.shape == (T, Hkv, D)
+    rc = _load().ppd_oracle_kv_append(_ptr(k), _ptr(v), _ptr(pool), _ptr(slot_mapping), T, Hkv, D, P, num_pages)
+    if rc != 0:
+        raise ValueError("oracle kv_append: slot outside the pool")
+
+
+def mixed_attention(q, pool, page_tables, L, n, Hq, Hkv, D, P, num_pages, scale, row_mask=None, threads=None):
+    """Returns out [T, Hq, D] float32.  q: [T, Hq, D] uint16 bf16 bits; rows masked out are left as NaN."""
+    q = np.ascontiguousarray(q, dtype=np.uint16)
+    page_tables = np.ascontiguousarray(page_tables, dtype=np.int32)
+    L = np.ascontiguousarray(L, dtype=np.int32)
+    n = np.ascontiguousarray(n, dtype=np.int32)
+    B = L.shape[0]
+    T = int(n.sum())
+    assert q.shape == (T, Hq, D) and page_tables.shape[0] == B and n.shape[0] == B
+    assert pool.dtype == np.uint16 and pool.flags.c_contiguous and pool.size == pool_elems(num_pages, Hkv, D, P)
+    out = np.full((T, Hq, D), np.nan, dtype=np.float32)
+    mask = None
+    if row_mask is not None:
+        mask = np.ascontiguousarray(row_mask, dtype=np.uint8)
+        assert mask.shape == (T,)
+    if threads is not None:
+        os.environ["OMP_NUM_THREADS"] = str(int(threads))
+    rc = _load().ppd_oracle_mixed_attention(
+        _ptr(q), _ptr(pool), _ptr(page_tables), page_tables.shape[1] if page_tables.ndim == 2 else 0,
+        _ptr(L), _ptr(n), B, Hq, Hkv, D, P, num_pages, float(scale),
+        _ptr(mask) if mask is not None else None, _ptr(out))
+    if rc != 0:
+        raise ValueError("oracle mixed_attention: page table entry outside the pool (code %d)" % rc)
+    return out

@@ -1,0 +1,135 @@
+/*
+ * CPU oracle for the mixed append-prefill + decode paged-attention step and the paged KV append.
+ *
+ * THIS IS TEST INFRASTRUCTURE, NOT THE PRODUCT.  Only the tests, the smoke check and the cpu_baseline leg
+ * of the benchmark may build, load or call it.  It shares no code with the HIP library: the page-pool
+ * index functions below are written from the layout sentence alone.
+ *
+ * What it computes (paper section 4.1, paragraph "Full Prefill vs. Append Prefill", with the renaming
+ * L = cached tokens (paper: n), n = new tokens (paper: m)):  each of the n new tokens of a sequence
+ * attends over the L cached keys and, causally, over the new tokens up to and including itself, so new
+ * row j sees keys 0 .. L+j.  Decode is n = 1 (section 2.1); full prefill is L = 0.  The method is exact:
+ * cached KV is reused with no recomputation, so the result has the plain softmax-attention definition and
+ * this file is that definition written out, in double precision, with no blocking, fusion or reordering.
+ *
+ * Declared page-pool layout (bf16 elements, P tokens per page, D a multiple of 8, P a multiple of 8):
+ *   page stride           S = 2 * Hkv * P * D
+ *   K(page,h,tok,d)   at  page*S +             h*P*D + (d/8)*(P*8) + tok*8 + d%8
+ *   V(page,h,tok,d)   at  page*S + Hkv*P*D  +  h*P*D + (tok/8)*(D*8) + d*8 + tok%8
+ * i.e. inside a (page, head) block K keeps 8 consecutive d of one token together and is token-minor over
+ * those 16-byte granules; V keeps 8 consecutive tokens of one d together.
+ *
+ * Pins (tests/test_oracle_*.py): dense brute force from the un-paged token arrays, recompute-prefill
+ * equivalence, n=1 == decode, page relabelling, chunking, closed forms, GQA replication, a library
+ * softmax-attention routine on a contiguous case, sentinel check of the append.
+ */
+#include <math.h>
+#include <stdint.h>
+#include <stdlib.h>
+#include <string.h>
+
+static double bf16_to_double(uint16_t bits) {
+    uint32_t u = ((uint32_t)bits) << 16; /* bf16 is the top half of an IEEE binary32 */
+    float f;
+    memcpy(&f, &u, sizeof f);
+    return (double)f;
+}
+
+static int64_t k_index(int64_t page, int h, int tok, int d, int Hkv, int D, int P) {
+    int64_t S = 2LL * Hkv * P * D;
+    return page * S + (int64_t)h * P * D + (int64_t)(d / 8) * (P * 8) + (int64_t)tok * 8 + d % 8;
+}
+
+static int64_t v_index(int64_t page, int h, int tok, int d, int Hkv, int D, int P) {
+    int64_t S = 2LL * Hkv * P * D;
+    return page * S + (int64_t)Hkv * P * D + (int64_t)h * P * D + (int64_t)(tok / 8) * (D * 8) + (int64_t)d * 8 +
+           tok % 8;
+}
+
+/* Paged KV append: token t goes to slot = page*P + offset; a negative slot skips the token.
+ * Raw 16-bit copies.  Returns 0, or -1 if a slot lies outside the pool (nothing is checked beyond that). */
+int ppd_oracle_kv_append(const uint16_t *k, const uint16_t *v, uint16_t *pool, const int64_t *slot_mapping,
+                         int64_t T, int Hkv, int D, int P, int64_t num_pages) {
+    for (int64_t t = 0; t < T; ++t) {
+        int64_t slot = slot_mapping[t];
+        if (slot < 0) continue;
+        int64_t page = slot / P;
+        int tok = (int)(slot % P);
+        if (page >= num_pages) return -1;
+        for (int h = 0; h < Hkv; ++h)
+            for (int d = 0; d < D; ++d) {
+                int64_t src = (t * Hkv + h) * D + d;
+                pool[k_index(page, h, tok, d, Hkv, D, P)] = k[src];
+                pool[v_index(page, h, tok, d, Hkv, D, P)] = v[src];
+            }
+    }
+    return 0;
+}
+
+/* Mixed-batch attention.  q, out: [T][Hq][D] with the rows of sequence i starting at sum_{j<i} n_j.
+ * row_mask (may be NULL): compute only rows with row_mask[r] != 0, leave the others untouched.
+ * out is fp32 (rounded once from the double result).  Returns 0, or a negative code for an invalid
+ * page-table entry. */
+int ppd_oracle_mixed_attention(const uint16_t *q, const uint16_t *pool, const int32_t *page_tables,
+                               int max_pages, const int32_t *L, const int32_t *n, int B, int Hq, int Hkv, int D,
+                               int P, int64_t num_pages, float scale, const uint8_t *row_mask, float *out) {
+    int G = Hq / Hkv;
+    int64_t T = 0;
+    for (int i = 0; i < B; ++i) T += n[i];
+    /* flat list of (sequence, row) so that the parallel loop below is a plain loop over output rows */
+    int32_t *row_seq = (int32_t *)malloc((size_t)(T > 0 ? T : 1) * sizeof(int32_t));
+    int32_t *row_j = (int32_t *)malloc((size_t)(T > 0 ? T : 1) * sizeof(int32_t));
+    int64_t r = 0;
+    for (int i = 0; i < B; ++i)
+        for (int j = 0; j < n[i]; ++j) {
+            row_seq[r] = i;
+            row_j[r] = j;
+            ++r;
+        }
+    int status = 0;
+#pragma omp parallel for collapse(2) schedule(dynamic, 1)
+    for (int64_t row = 0; row < T; ++row)
+        for (int h = 0; h < Hq; ++h) {
+            if (row_mask && !row_mask[row]) continue;
+            int i = row_seq[row];
+            int j = row_j[row];
+            int g = h / G;             /* KV head shared by this query head */
+            int64_t visible = (int64_t)L[i] + j + 1; /* keys 0 .. L+j */
+            const uint16_t *qv = q + (row * Hq + h) * D;
+            double *s = (double *)malloc((size_t)visible * sizeof(double));
+            double m = -INFINITY;
+            int bad = 0;
+            for (int64_t t = 0; t < visible; ++t) {
+                int32_t page = page_tables[(int64_t)i * max_pages + t / P];
+                if (page < 0 || page >= num_pages) { bad = 1; break; }
+                double dot = 0.0;
+                for (int d = 0; d < D; ++d)
+                    dot += bf16_to_double(qv[d]) * bf16_to_double(pool[k_index(page, g, (int)(t % P), d, Hkv, D, P)]);
+                s[t] = (double)scale * dot;
+                if (s[t] > m) m = s[t];
+            }
+            if (bad) {
+#pragma omp atomic write
+                status = -2;
+                free(s);
+                continue;
+            }
+            double l = 0.0;
+            for (int64_t t = 0; t < visible; ++t) {
+                s[t] = exp(s[t] - m);
+                l += s[t];
+            }
+            for (int d = 0; d < D; ++d) {
+                double acc = 0.0;
+                for (int64_t t = 0; t < visible; ++t) {
+                    int32_t page = page_tables[(int64_t)i * max_pages + t / P];
+                    acc += s[t] * bf16_to_double(pool[v_index(page, g, (int)(t % P), d, Hkv, D, P)]);
+                }
+                out[(row * Hq + h) * D + d] = (float)(acc / l);
+            }
+            free(s);
+        }
+    free(row_seq);
+    free(row_j);
+    return status;
+}
