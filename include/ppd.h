@@ -1,0 +1,160 @@
+/*
+ * ppd.h -- C ABI of libppd: the decode-node hot path of PPD serving on one MI355X (gfx950).
+ *
+ * One engine step on a decode node that also runs append-prefill locally (paper section 4.1, "Full
+ * Prefill vs. Append Prefill"; section 2.1 for decode): every sequence i of the batch has L_i tokens of
+ * KV already cached on the node and n_i new tokens.  n_i = 1 is a decode step, n_i > 1 with L_i > 0 is
+ * an append-prefill, L_i = 0 is a full prefill.  (The paper writes n for the cached and m for the new
+ * tokens; this interface writes L and n.)  New row j of a sequence attends to keys 0 .. L_i + j: the
+ * whole cached prefix plus the new tokens up to and including itself.
+ *
+ * The step is two calls: ppd_kv_append writes the new tokens' K/V into the page pool, then
+ * ppd_mixed_attention computes all rows of all sequences in one launch, reading every key -- cached or
+ * new -- from the pool.
+ *
+ * Conventions
+ *  - All tensor pointers are DEVICE pointers unless a parameter says HOST.  They are borrowed: the
+ *    library neither frees them nor keeps them after the enqueued work has run.
+ *  - bf16 = the upper 16 bits of an IEEE binary32.  Arithmetic: bf16 inputs, fp32 accumulation and
+ *    softmax, probabilities rounded to bf16 before the PV product, bf16 output (round to nearest even).
+ *  - Both calls are asynchronous on `stream` (a hipStream_t passed as void*; NULL = the default stream);
+ *    the caller synchronises.  Host-side argument checks are complete before anything is enqueued: a
+ *    negative return value means no device side effect.
+ *  - Values that live in device memory (page ids, slots) cannot be checked on the host; the kernels
+ *    never dereference an out-of-range id (the token or key is skipped) and raise a sticky flag that
+ *    ppd_device_error_flags reads back.
+ *  - One context serves one stream at a time.  Calls on a context are not thread-safe.
+ *
+ * Page pool layout (bf16 elements; P = 16 tokens per page; D = head_dim; Hkv = KV heads):
+ *    page stride          S = 2 * Hkv * P * D
+ *    K(page, h, tok, d)   at  page*S +            h*P*D + (d/8)*(P*8)  + tok*8 + d%8
+ *    V(page, h, tok, d)   at  page*S + Hkv*P*D +  h*P*D + (tok/8)*(D*8) + d*8   + tok%8
+ *  A (page, head) block of K or V is P*D*2 bytes contiguous (4 KiB at D = 128); K keeps 8 consecutive d of
+ *  a token in one 16-byte granule with the 16 tokens of a page adjacent, V keeps 8 consecutive tokens of
+ *  one d in a granule: the two operand shapes the matrix cores consume without a transpose.
+ */
+#ifndef PPD_H
+#define PPD_H
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct ppd_ctx ppd_ctx; /* opaque; owns only its workspace and plan buffers */
+
+typedef enum {
+    PPD_OK = 0,
+    PPD_ERR_NULL = -1,      /* a required pointer is NULL */
+    PPD_ERR_SHAPE = -2,     /* unsupported head_dim / page_size / head counts */
+    PPD_ERR_RANGE = -3,     /* n_i < 1, L_i < 0, negative or non-finite scale, sizes out of range */
+    PPD_ERR_PAGETABLE = -4, /* max_pages < ceil((L_i + n_i) / P) for some sequence */
+    PPD_ERR_WORKSPACE = -5, /* workspace allocation failed */
+    PPD_ERR_HIP = -6        /* a HIP runtime call failed (see ppd_last_error) */
+} ppd_status;
+
+/* Supported: head_dim in {64, 128}; page_size == 16; num_q_heads = G * num_kv_heads with G in {1,2,4,8};
+ * num_pages >= 1. */
+typedef struct {
+    int32_t num_q_heads;
+    int32_t num_kv_heads;
+    int32_t head_dim;
+    int32_t page_size;
+    int64_t num_pages;
+} ppd_shape;
+
+/* Work-list entry of the one-launch scheduler (host readable through ppd_plan_build). */
+typedef struct {
+    int32_t kind;     /* 0: narrow tile (rows*G <= 16 columns, HBM-bound: decode), 1: MFMA row-block tile */
+    int32_t seq;      /* sequence index */
+    int32_t kvh;      /* KV head */
+    int32_t row0;     /* first new-token row of the block, within the sequence */
+    int32_t nrows;    /* rows in the block */
+    int32_t grow0;    /* row0 as an index into q / out */
+    int32_t L;        /* cached length of the sequence */
+    int32_t kv_total; /* L + n of the sequence */
+    int32_t kv_begin; /* key range [kv_begin, kv_end) this tile covers; kv_begin is a multiple of 64 */
+    int32_t kv_end;
+    int32_t group;    /* merge group, or -1 when the tile covers the whole key range and writes `out` */
+    int32_t reserved;
+    int64_t part_off; /* float offset of this tile's partial (o, m, l) in the workspace, or -1 */
+} ppd_work_item;
+
+typedef struct {
+    int64_t n_items;        /* tiles in the work list */
+    int64_t n_narrow;       /* of which narrow (decode-like) */
+    int64_t n_mfma;         /* of which MFMA row-block tiles */
+    int64_t n_groups;       /* merge groups (row blocks whose key range was split) */
+    int64_t partial_floats; /* workspace floats for split partials */
+    int64_t kv_bytes;       /* sum over sequences of (L_i + n_i) * 2 * Hkv * D * 2: KV read at least once */
+    int64_t kv_bytes_tiles; /* KV bytes summed over tiles (row blocks re-read their key range) */
+    double flops;           /* 4 * Hq * D * sum_i n_i * (L_i + (n_i + 1) / 2) */
+    int32_t narrow_chunk;   /* split size (tokens) chosen for narrow tiles */
+    int32_t mfma_chunk;     /* split size (tokens) chosen for MFMA tiles */
+    int32_t grid;           /* workgroups launched */
+    int32_t reserved;
+} ppd_plan_stats;
+
+/* Creates a context bound to HIP device `device` for pools of the given shape. */
+ppd_status ppd_create(const ppd_shape *shape, int32_t device, ppd_ctx **out);
+ppd_status ppd_destroy(ppd_ctx *ctx);
+
+/* Message of the last failing call on this context (context-owned string; "" if none).  ctx may be NULL
+ * to read the message of a failed ppd_create. */
+const char *ppd_last_error(const ppd_ctx *ctx);
+
+/* Tuning knobs (all optional).  key: "narrow_chunk", "mfma_chunk" (tokens, multiple of 64, 0 = automatic),
+ * "grid" (workgroups, 0 = automatic), "force_kind" (-1 automatic, 1 = route every sequence through the
+ * MFMA row-block path; used to test that n = 1 append-prefill equals decode). */
+ppd_status ppd_set_option(ppd_ctx *ctx, const char *key, int64_t value);
+
+/* Paged KV append (the KV-cache write of the step; paper sections 2.1 and 4.1: prefill populates the
+ * cache, decode-side KV stays resident and grows with the context).
+ *   k, v          device bf16 [T][Hkv][D], token-major, contiguous
+ *   kv_pages      device pool in the layout above, caller-owned
+ *   slot_mapping  device int64 [T]; slot = page*P + offset; a negative slot skips the token; a slot beyond
+ *                 the pool is skipped and raises device error flag bit 0; duplicate slots in one call are
+ *                 a caller error (which copy wins is unspecified)
+ * Pure 16-bit copies: the pool afterwards is bit-identical to the definition.  T = 0 is a no-op. */
+ppd_status ppd_kv_append(ppd_ctx *ctx, const void *k, const void *v, void *kv_pages,
+                         const int64_t *slot_mapping, int64_t T, void *stream);
+
+/* Mixed-batch paged attention (paper section 4.1 for append-prefill and full prefill, section 2.1 for
+ * decode; the co-batching of the two is the interference experiment of section 4.1).
+ *   q, out        device bf16 [T][Hq][D], T = sum n_i, rows grouped by sequence in batch order
+ *   kv_pages      device pool; the n_i new tokens of every sequence must already be appended at
+ *                 positions L_i .. L_i + n_i - 1
+ *   page_tables   device int32 [B][max_pages]; entry p of row i is the page of tokens p*P .. p*P+P-1;
+ *                 entries at or beyond ceil((L_i+n_i)/P) are never read; an id outside the pool is clamped
+ *                 and raises device error flag bit 1
+ *   L, n          HOST int32 [B]
+ *   scale         softmax scale (>= 0, finite), applied to q.k before the softmax
+ * Result per row is the softmax-weighted average of the visible V rows; run-to-run bitwise deterministic
+ * for fixed arguments and options.  B = 0 is a no-op. */
+ppd_status ppd_mixed_attention(ppd_ctx *ctx, const void *q, const void *kv_pages, const int32_t *page_tables,
+                               int32_t max_pages, const int32_t *L, const int32_t *n, int32_t B, float scale,
+                               void *out, void *stream);
+
+/* Statistics of the plan built by the last ppd_mixed_attention call on this context. */
+ppd_status ppd_get_plan_stats(const ppd_ctx *ctx, ppd_plan_stats *stats);
+
+/* Host-only planner (no device needed): classifies the sequences and emits the tile list the kernel
+ * would run, in launch order.  items may be NULL to query the count; at most `capacity` entries are
+ * written and stats->n_items holds the full count.  narrow_chunk / mfma_chunk / grid: 0 = automatic;
+ * force_kind as in ppd_set_option; num_cus = compute units to balance for (256 on MI355X). */
+ppd_status ppd_plan_build(const ppd_shape *shape, const int32_t *L, const int32_t *n, int32_t B,
+                          int32_t narrow_chunk, int32_t mfma_chunk, int32_t grid, int32_t force_kind,
+                          int32_t num_cus, ppd_work_item *items, int64_t capacity, ppd_plan_stats *stats);
+
+/* Synchronises `stream`, then returns and clears the sticky device error flags (bit 0: append slot out of
+ * range, bit 1: page id out of range) in *flags. */
+ppd_status ppd_device_error_flags(ppd_ctx *ctx, void *stream, uint32_t *flags);
+
+/* Library version, "major.minor". */
+const char *ppd_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* PPD_H */

@@ -1,0 +1,302 @@
+// Host side of libppd: context, argument checks, plan upload and kernel launches behind the C ABI.
+#include <hip/hip_runtime.h>
+
+#include <cmath>
+#include <cstdio>
+#include <cstring>
+#include <string>
+
+#include "ppd_internal.h"
+
+namespace {
+
+thread_local std::string g_create_error;
+
+constexpr int kStagingSlots = 4;
+
+struct Staging {
+    void* host = nullptr;  // pinned
+    size_t bytes = 0;
+    hipEvent_t done = nullptr;
+    bool in_flight = false;
+};
+
+}  // namespace
+
+struct ppd_ctx {
+    ppd_shape shape;
+    int device = 0;
+    int num_cus = 256;
+    ppd::PlanOptions opts;
+    std::string error;
+    ppd::Plan plan;
+    // device workspace
+    void* d_items = nullptr;
+    size_t d_items_bytes = 0;
+    float* d_partials = nullptr;
+    size_t d_partials_floats = 0;
+    uint32_t* d_counters = nullptr;  // cursor, finished, error flags (+ padding)
+    Staging staging[kStagingSlots];
+    int next_slot = 0;
+};
+
+namespace {
+
+ppd_status fail(ppd_ctx* ctx, ppd_status st, const std::string& msg) {
+    if (ctx) ctx->error = msg; else g_create_error = msg;
+    return st;
+}
+
+ppd_status hip_fail(ppd_ctx* ctx, hipError_t e, const char* what) {
+    return fail(ctx, PPD_ERR_HIP, std::string(what) + ": " + hipGetErrorString(e));
+}
+
+#define PPD_HIP(ctx, call)                                         \
+    do {                                                           \
+        hipError_t e_ = (call);                                    \
+        if (e_ != hipSuccess) return hip_fail((ctx), e_, #call);   \
+    } while (0)
+
+int ilog2(int v) {
+    int l = 0;
+    while ((1 << l) < v) ++l;
+    return l;
+}
+
+// Grows a device buffer (contents are not kept).  Waits for the stream first: the old buffer may be in use.
+ppd_status grow_device(ppd_ctx* ctx, void** ptr, size_t* have, size_t need, hipStream_t st) {
+    if (need <= *have) return PPD_OK;
+    PPD_HIP(ctx, hipStreamSynchronize(st));
+    if (*ptr) PPD_HIP(ctx, hipFree(*ptr));
+    *ptr = nullptr;
+    *have = 0;
+    size_t want = need + need / 4 + 4096;
+    if (hipMalloc(ptr, want) != hipSuccess) {
+        (void)hipGetLastError();
+        *ptr = nullptr;
+        return fail(ctx, PPD_ERR_WORKSPACE, "workspace allocation of " + std::to_string(want) + " bytes failed");
+    }
+    *have = want;
+    return PPD_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+const char* ppd_version(void) { return "0.1"; }
+
+const char* ppd_last_error(const ppd_ctx* ctx) { return ctx ? ctx->error.c_str() : g_create_error.c_str(); }
+
+ppd_status ppd_create(const ppd_shape* shape, int32_t device, ppd_ctx** out) {
+    if (!out) return fail(nullptr, PPD_ERR_NULL, "out is NULL");
+    *out = nullptr;
+    const char* msg = "";
+    ppd_status st = ppd::validate_shape(shape, &msg);
+    if (st != PPD_OK) return fail(nullptr, st, msg);
+    int count = 0;
+    hipError_t e = hipGetDeviceCount(&count);
+    if (e != hipSuccess || count <= 0) {
+        (void)hipGetLastError();
+        return fail(nullptr, PPD_ERR_HIP, "no HIP device available: this library has no CPU path");
+    }
+    if (device < 0 || device >= count) return fail(nullptr, PPD_ERR_RANGE, "device index out of range");
+    ppd_ctx* ctx = new ppd_ctx();
+    ctx->shape = *shape;
+    ctx->device = device;
+    auto bail = [&](hipError_t err, const char* what) {
+        g_create_error = std::string(what) + ": " + hipGetErrorString(err);
+        ppd_destroy(ctx);
+        return PPD_ERR_HIP;
+    };
+    if ((e = hipSetDevice(device)) != hipSuccess) return bail(e, "hipSetDevice");
+    hipDeviceProp_t prop;
+    if ((e = hipGetDeviceProperties(&prop, device)) != hipSuccess) return bail(e, "hipGetDeviceProperties");
+    if (std::strncmp(prop.gcnArchName, "gfx950", 6) != 0) {
+        g_create_error = std::string("device is ") + prop.gcnArchName + ", this library is built for gfx950 only";
+        ppd_destroy(ctx);
+        return PPD_ERR_HIP;
+    }
+    ctx->num_cus = prop.multiProcessorCount > 0 ? prop.multiProcessorCount : 256;
+    ctx->opts.num_cus = ctx->num_cus;
+    if ((e = hipMalloc((void**)&ctx->d_counters, 64)) != hipSuccess) return bail(e, "hipMalloc(counters)");
+    if ((e = hipMemset(ctx->d_counters, 0, 64)) != hipSuccess) return bail(e, "hipMemset(counters)");
+    for (auto& s : ctx->staging)
+        if ((e = hipEventCreateWithFlags(&s.done, hipEventDisableTiming)) != hipSuccess) return bail(e, "hipEventCreate");
+    *out = ctx;
+    return PPD_OK;
+}
+
+ppd_status ppd_destroy(ppd_ctx* ctx) {
+    if (!ctx) return PPD_OK;
+    (void)hipSetDevice(ctx->device);
+    (void)hipDeviceSynchronize();
+    if (ctx->d_items) (void)hipFree(ctx->d_items);
+    if (ctx->d_partials) (void)hipFree(ctx->d_partials);
+    if (ctx->d_counters) (void)hipFree(ctx->d_counters);
+    for (auto& s : ctx->staging) {
+        if (s.host) (void)hipHostFree(s.host);
+        if (s.done) (void)hipEventDestroy(s.done);
+    }
+    delete ctx;
+    return PPD_OK;
+}
+
+ppd_status ppd_set_option(ppd_ctx* ctx, const char* key, int64_t value) {
+    if (!ctx || !key) return fail(ctx, PPD_ERR_NULL, "ctx / key is NULL");
+    std::string k(key);
+    if (k == "narrow_chunk" || k == "mfma_chunk") {
+        if (value < 0 || value % ppd::kTileTokens || value > (1 << 30))
+            return fail(ctx, PPD_ERR_RANGE, k + " must be 0 or a positive multiple of 64");
+        (k == "narrow_chunk" ? ctx->opts.narrow_chunk : ctx->opts.mfma_chunk) = (int32_t)value;
+    } else if (k == "grid") {
+        if (value < 0 || value > 65536) return fail(ctx, PPD_ERR_RANGE, "grid must be in [0, 65536]");
+        ctx->opts.grid = (int32_t)value;
+    } else if (k == "force_kind") {
+        if (value != -1 && value != 1) return fail(ctx, PPD_ERR_RANGE, "force_kind must be -1 or 1");
+        ctx->opts.force_kind = (int32_t)value;
+    } else {
+        return fail(ctx, PPD_ERR_RANGE, "unknown option " + k);
+    }
+    return PPD_OK;
+}
+
+ppd_status ppd_kv_append(ppd_ctx* ctx, const void* k, const void* v, void* kv_pages, const int64_t* slot_mapping,
+                         int64_t T, void* stream) {
+    if (!ctx) return PPD_ERR_NULL;
+    if (T < 0 || T >= (int64_t(1) << 31)) return fail(ctx, PPD_ERR_RANGE, "T out of range");
+    if (T == 0) return PPD_OK;
+    if (!k || !v || !kv_pages || !slot_mapping) return fail(ctx, PPD_ERR_NULL, "k / v / kv_pages / slot_mapping is NULL");
+    PPD_HIP(ctx, hipSetDevice(ctx->device));
+    int rc = ppd::launch_kv_append(static_cast<const uint16_t*>(k), static_cast<const uint16_t*>(v),
+                                   static_cast<uint16_t*>(kv_pages), slot_mapping, T, ctx->shape.num_kv_heads,
+                                   ctx->shape.head_dim, ctx->shape.num_pages, ctx->d_counters + 2, stream);
+    if (rc != 0) return hip_fail(ctx, (hipError_t)rc, "launch kv_append");
+    return PPD_OK;
+}
+
+ppd_status ppd_mixed_attention(ppd_ctx* ctx, const void* q, const void* kv_pages, const int32_t* page_tables,
+                               int32_t max_pages, const int32_t* L, const int32_t* n, int32_t B, float scale,
+                               void* out, void* stream) {
+    if (!ctx) return PPD_ERR_NULL;
+    if (B < 0) return fail(ctx, PPD_ERR_RANGE, "B < 0");
+    if (B == 0) {
+        ctx->plan.items.clear();
+        ctx->plan.groups.clear();
+        std::memset(&ctx->plan.stats, 0, sizeof ctx->plan.stats);
+        return PPD_OK;
+    }
+    if (!q || !kv_pages || !page_tables || !L || !n || !out)
+        return fail(ctx, PPD_ERR_NULL, "q / kv_pages / page_tables / L / n / out is NULL");
+    if (!(scale >= 0.f) || !std::isfinite(scale)) return fail(ctx, PPD_ERR_RANGE, "scale must be finite and >= 0");
+    const char* msg = "";
+    ppd_status st = ppd::build_plan(ctx->shape, L, n, B, ctx->opts, &ctx->plan, &msg);
+    if (st != PPD_OK) return fail(ctx, st, msg);
+    for (int i = 0; i < B; ++i) {
+        const int64_t need = ((int64_t)L[i] + n[i] + ppd::kPage - 1) / ppd::kPage;
+        if (need > max_pages)
+            return fail(ctx, PPD_ERR_PAGETABLE, "sequence " + std::to_string(i) + " needs " + std::to_string(need) +
+                                                    " pages, max_pages is " + std::to_string(max_pages));
+    }
+    hipStream_t hs = static_cast<hipStream_t>(stream);
+    PPD_HIP(ctx, hipSetDevice(ctx->device));
+
+    // upload: [items][groups] through one pinned staging slot
+    const ppd::Plan& plan = ctx->plan;
+    const size_t items_bytes = plan.items.size() * sizeof(ppd_work_item);
+    const size_t groups_bytes = plan.groups.size() * sizeof(ppd::MergeGroup);
+    const size_t total = items_bytes + groups_bytes;
+    Staging& sg = ctx->staging[ctx->next_slot];
+    ctx->next_slot = (ctx->next_slot + 1) % kStagingSlots;
+    if (sg.in_flight) {
+        PPD_HIP(ctx, hipEventSynchronize(sg.done));
+        sg.in_flight = false;
+    }
+    if (sg.bytes < total) {
+        if (sg.host) PPD_HIP(ctx, hipHostFree(sg.host));
+        sg.host = nullptr;
+        sg.bytes = 0;
+        const size_t want = total + total / 4 + 4096;
+        if (hipHostMalloc(&sg.host, want, hipHostMallocDefault) != hipSuccess) {
+            (void)hipGetLastError();
+            sg.host = nullptr;
+            return fail(ctx, PPD_ERR_WORKSPACE, "pinned staging allocation failed");
+        }
+        sg.bytes = want;
+    }
+    st = grow_device(ctx, &ctx->d_items, &ctx->d_items_bytes, total, hs);
+    if (st != PPD_OK) return st;
+    {
+        void* p = ctx->d_partials;
+        size_t have = ctx->d_partials_floats * sizeof(float);
+        st = grow_device(ctx, &p, &have, (size_t)plan.stats.partial_floats * sizeof(float), hs);
+        ctx->d_partials = static_cast<float*>(p);
+        ctx->d_partials_floats = have / sizeof(float);
+        if (st != PPD_OK) return st;
+    }
+    std::memcpy(sg.host, plan.items.data(), items_bytes);
+    if (groups_bytes) std::memcpy(static_cast<char*>(sg.host) + items_bytes, plan.groups.data(), groups_bytes);
+    PPD_HIP(ctx, hipMemcpyAsync(ctx->d_items, sg.host, total, hipMemcpyHostToDevice, hs));
+    PPD_HIP(ctx, hipEventRecord(sg.done, hs));
+    sg.in_flight = true;
+
+    const int G = ctx->shape.num_q_heads / ctx->shape.num_kv_heads;
+    // Masked scores are -inf and enter the exponent as s*c: keep c strictly positive so that scale = 0 gives
+    // 2^(-inf) = 0 for masked keys and 2^(~0) = 1 for visible ones (identical to the exact result in fp32).
+    float scale_log2e = scale * 1.4426950408889634f;
+    if (scale_log2e < 1e-30f) scale_log2e = 1e-30f;
+    ppd::KParams kp;
+    kp.q = static_cast<const uint16_t*>(q);
+    kp.out = static_cast<uint16_t*>(out);
+    kp.pool = static_cast<const uint16_t*>(kv_pages);
+    kp.page_tables = page_tables;
+    kp.items = static_cast<const ppd_work_item*>(ctx->d_items);
+    kp.partials = ctx->d_partials;
+    kp.counters = ctx->d_counters;
+    kp.num_pages = ctx->shape.num_pages;
+    kp.page_stride = 2LL * ctx->shape.num_kv_heads * ppd::kPage * ctx->shape.head_dim;
+    kp.n_items = (int32_t)plan.items.size();
+    kp.max_pages = max_pages;
+    kp.Hq = ctx->shape.num_q_heads;
+    kp.Hkv = ctx->shape.num_kv_heads;
+    kp.G = G;
+    kp.lgG = ilog2(G);
+    kp.scale_log2e = scale_log2e;
+    int rc = ppd::launch_mixed(kp, ctx->shape.head_dim, plan.stats.grid, stream);
+    if (rc != 0) return hip_fail(ctx, (hipError_t)rc, "launch mixed attention");
+    if (!plan.groups.empty()) {
+        ppd::MergeParams mp;
+        mp.groups = reinterpret_cast<const ppd::MergeGroup*>(static_cast<const char*>(ctx->d_items) + items_bytes);
+        mp.partials = ctx->d_partials;
+        mp.out = static_cast<uint16_t*>(out);
+        mp.n_groups = (int32_t)plan.groups.size();
+        mp.Hq = kp.Hq;
+        mp.G = G;
+        mp.lgG = kp.lgG;
+        mp.D = ctx->shape.head_dim;
+        mp.scale_log2e = scale_log2e;
+        rc = ppd::launch_merge(mp, stream);
+        if (rc != 0) return hip_fail(ctx, (hipError_t)rc, "launch merge");
+    }
+    return PPD_OK;
+}
+
+ppd_status ppd_get_plan_stats(const ppd_ctx* ctx, ppd_plan_stats* stats) {
+    if (!ctx || !stats) return PPD_ERR_NULL;
+    *stats = ctx->plan.stats;
+    return PPD_OK;
+}
+
+ppd_status ppd_device_error_flags(ppd_ctx* ctx, void* stream, uint32_t* flags) {
+    if (!ctx || !flags) return fail(ctx, PPD_ERR_NULL, "ctx / flags is NULL");
+    hipStream_t hs = static_cast<hipStream_t>(stream);
+    PPD_HIP(ctx, hipSetDevice(ctx->device));
+    PPD_HIP(ctx, hipStreamSynchronize(hs));
+    uint32_t v = 0;
+    PPD_HIP(ctx, hipMemcpy(&v, ctx->d_counters + 2, sizeof v, hipMemcpyDeviceToHost));
+    PPD_HIP(ctx, hipMemset(ctx->d_counters + 2, 0, sizeof v));
+    *flags = v;
+    return PPD_OK;
+}
+
+}  // extern "C"

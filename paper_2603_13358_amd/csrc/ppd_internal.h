@@ -1,0 +1,78 @@
+// Internal declarations shared by the host planner, the host API and the kernels of libppd.
+#pragma once
+#include <stdint.h>
+
+#include <vector>
+
+#include "../../include/ppd.h"
+
+namespace ppd {
+
+constexpr int kPage = 16;            // tokens per page
+constexpr int kNarrowCols = 16;      // a narrow tile holds rows*G <= 16 query columns
+constexpr int kMfmaCols = 128;       // an MFMA row-block tile holds up to 128 query columns (4 waves x 32)
+constexpr int kTileTokens = 64;      // key tile of the MFMA path; every split boundary is a multiple of it
+constexpr int kThreads = 256;
+
+// One merge group: a row block whose key range was split over `nsplit` tiles with consecutive partials.
+struct MergeGroup {
+    int32_t grow0;
+    int32_t nrows;
+    int32_t kvh;
+    int32_t nsplit;
+    int64_t part_off;     // float offset of split 0
+    int64_t part_stride;  // floats per split = cols * (D + 2)
+};
+
+struct Plan {
+    std::vector<ppd_work_item> items;
+    std::vector<MergeGroup> groups;
+    ppd_plan_stats stats;
+};
+
+struct PlanOptions {
+    int32_t narrow_chunk = 0;
+    int32_t mfma_chunk = 0;
+    int32_t grid = 0;
+    int32_t force_kind = -1;
+    int32_t num_cus = 256;
+};
+
+// Returns PPD_OK or an error code with a message in `err` (may be null).
+ppd_status validate_shape(const ppd_shape* s, const char** err);
+ppd_status build_plan(const ppd_shape& s, const int32_t* L, const int32_t* n, int32_t B, const PlanOptions& o,
+                      Plan* plan, const char** err);
+
+// Kernel arguments (passed by value).
+struct KParams {
+    const uint16_t* q;
+    uint16_t* out;
+    const uint16_t* pool;
+    const int32_t* page_tables;
+    const ppd_work_item* items;
+    float* partials;
+    uint32_t* counters;   // [0] work cursor, [1] finished workgroups, [2] sticky error flags
+    int64_t num_pages;
+    int64_t page_stride;  // elements per page = 2 * Hkv * 16 * D
+    int32_t n_items;
+    int32_t max_pages;
+    int32_t Hq, Hkv, G, lgG;
+    float scale_log2e;
+};
+
+struct MergeParams {
+    const MergeGroup* groups;
+    const float* partials;
+    uint16_t* out;
+    int32_t n_groups;
+    int32_t Hq, G, lgG, D;
+    float scale_log2e;
+};
+
+// Launchers (defined in ppd_kernels.hip); stream is a hipStream_t.
+int launch_mixed(const KParams& p, int head_dim, int grid, void* stream);
+int launch_merge(const MergeParams& p, void* stream);
+int launch_kv_append(const uint16_t* k, const uint16_t* v, uint16_t* pool, const int64_t* slots, int64_t T,
+                     int Hkv, int D, int64_t num_pages, uint32_t* err_flags, void* stream);
+
+}  // namespace ppd

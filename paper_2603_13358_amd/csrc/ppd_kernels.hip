@@ -1,0 +1,635 @@
+// gfx950 kernels of libppd: paged KV append, the one-launch mixed attention kernel (narrow tiles for
+// decode-like rows, MFMA row-block tiles for append-prefill / full prefill) and the log-sum-exp merge of
+// split partials.
+//
+// Operation (paper section 4.1, "Full Prefill vs. Append Prefill"; L = cached, n = new): new row j of a
+// sequence attends to keys 0 .. L + j, all read from the page pool.  Both tile kinds compute the
+// transposed products  S^T = K Q^T  and  O^T = V^T P^T  so that the accumulator layout of the first
+// product is already the operand layout of the second, and every per-row softmax quantity lives in the
+// lane that owns the row's column.
+#include <hip/hip_runtime.h>
+
+#include "ppd_internal.h"
+
+namespace ppd {
+
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+typedef float f32x2 __attribute__((ext_vector_type(2)));
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+typedef float f32x16 __attribute__((ext_vector_type(16)));
+typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+
+#define NEG_INF (-__builtin_inff())
+
+__device__ __forceinline__ uint32_t pack_bf16(float a, float b) {
+    f32x2 f = {a, b};
+    bf16x2 r = __builtin_convertvector(f, bf16x2);  // round to nearest even
+    return __builtin_bit_cast(uint32_t, r);
+}
+
+__device__ __forceinline__ bf16x8 as_bf16x8(u32x4 v) { return __builtin_bit_cast(bf16x8, v); }
+
+__device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
+
+__device__ __forceinline__ float xor_shuffle(float v, int mask) { return __shfl_xor(v, mask, 64); }
+
+// Page id of logical page `pi` of a sequence, clamped so that no access leaves the page table row or the pool.
+__device__ __forceinline__ int64_t fetch_page(const KParams& P, const int32_t* pt_row, int pi, int last_page) {
+    pi = pi < last_page ? pi : last_page;
+    int64_t page = pt_row[pi];
+    if (page < 0 || page >= P.num_pages) {
+        atomicOr(&P.counters[2], 2u);
+        page = 0;
+    }
+    return page;
+}
+
+// Zeroes the bf16 elements e of a granule of 8 tokens whose position first + e is >= kv_total (never written).
+__device__ __forceinline__ u32x4 zero_unwritten(u32x4 v, int first, int kv_total) {
+#pragma unroll
+    for (int e = 0; e < 8; ++e)
+        if (first + e >= kv_total) v[e >> 1] &= (e & 1) ? 0x0000FFFFu : 0xFFFF0000u;
+    return v;
+}
+
+// ---------------------------------------------------------------------------------------------------
+// MFMA row-block tile: up to 128 query columns (rows x G heads of one KV head) against keys
+// [kv_begin, kv_end).  4 waves x 32 columns; key tiles of 64 tokens (4 pages) staged through LDS, double
+// buffered; v_mfma_f32_32x32x16_bf16 for both products.
+// ---------------------------------------------------------------------------------------------------
+template <int HD>
+__device__ __forceinline__ void mfma_item(const KParams& P, const ppd_work_item& it, char* smem) {
+    constexpr int PB = kPage * HD * 2;         // bytes of one (page, head) block of K or of V
+    constexpr int GPP = PB / 16;               // 16-byte granules per block
+    constexpr int KBYTES = 4 * PB;             // K (or V) part of one stage: 4 pages
+    constexpr int STAGE = 2 * KBYTES;
+    constexpr int ROUNDS = 4 * GPP / kThreads; // granules of K (and of V) each thread moves per tile
+    constexpr int KS = HD / 16;                // k-steps of S^T = K Q^T
+    constexpr int DB = HD / 32;                // 32-row d blocks of O^T
+
+    const int tid = threadIdx.x;
+    const int lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int h = lane >> 5;
+    const int l32 = lane & 31;
+    const int G = P.G, lg = P.lgG;
+    const int ncols = it.nrows * G;
+    const int col = wave * 32 + l32;
+    const int colc = col < ncols ? col : ncols - 1;
+    const int jrow = colc >> lg;
+    const int head = it.kvh * G + (colc & (G - 1));
+    const int limit = it.L + it.row0 + jrow;  // last key position this column may see
+    const bool wave_active = wave * 32 < ncols;
+    const int wmin_limit = it.L + it.row0 + (((wave * 32) < ncols ? wave * 32 : ncols - 1) >> lg);
+
+    // Q^T operand: column = lane % 32, d = ks*16 + (lane/32)*8 .. +8
+    bf16x8 qreg[KS];
+    {
+        const uint16_t* qp = P.q + ((int64_t)(it.grow0 + jrow) * P.Hq + head) * HD + h * 8;
+#pragma unroll
+        for (int ks = 0; ks < KS; ++ks) qreg[ks] = as_bf16x8(*reinterpret_cast<const u32x4*>(qp + ks * 16));
+    }
+
+    const int32_t* pt_row = P.page_tables + (int64_t)it.seq * P.max_pages;
+    const int last_page = (it.kv_total - 1) >> 4;
+    const int first_page = it.kv_begin >> 4;
+    const int ntiles = (it.kv_end - it.kv_begin + kTileTokens - 1) / kTileTokens;
+    const int64_t head_off = (int64_t)it.kvh * (kPage * HD);
+    const int64_t v_off = (int64_t)P.Hkv * (kPage * HD);
+
+    // staging assignment: granule gid = r*256 + tid of the tile's 4 page blocks
+    int64_t pages_next[ROUNDS];
+    u32x4 kst[ROUNDS], vst[ROUNDS];
+    auto fetch_pages = [&](int ti) {
+#pragma unroll
+        for (int r = 0; r < ROUNDS; ++r) {
+            const int s = (r * kThreads + tid) / GPP;
+            pages_next[r] = fetch_page(P, pt_row, first_page + ti * 4 + s, last_page);
+        }
+    };
+    auto issue_loads = [&](int ti) {
+        const int tile_base = it.kv_begin + ti * kTileTokens;
+#pragma unroll
+        for (int r = 0; r < ROUNDS; ++r) {
+            const int gid = r * kThreads + tid;
+            const int within = gid % GPP;
+            const uint16_t* src = P.pool + pages_next[r] * P.page_stride + head_off + within * 8;
+            kst[r] = *reinterpret_cast<const u32x4*>(src);
+            vst[r] = *reinterpret_cast<const u32x4*>(src + v_off);
+        }
+        if (tile_base + kTileTokens > it.kv_total) {  // the sequence's last tile: pool rows never written
+#pragma unroll
+            for (int r = 0; r < ROUNDS; ++r) {
+                const int gid = r * kThreads + tid;
+                const int s = gid / GPP, within = gid % GPP;
+                vst[r] = zero_unwritten(vst[r], tile_base + s * 16 + (within / HD) * 8, it.kv_total);
+            }
+        }
+    };
+    auto store_stage = [&](int buf) {
+        char* base = smem + buf * STAGE;
+#pragma unroll
+        for (int r = 0; r < ROUNDS; ++r) {
+            const int gid = r * kThreads + tid;
+            *reinterpret_cast<u32x4*>(base + gid * 16) = kst[r];
+            *reinterpret_cast<u32x4*>(base + KBYTES + gid * 16) = vst[r];
+        }
+    };
+
+    f32x16 oacc[DB];
+#pragma unroll
+    for (int db = 0; db < DB; ++db)
+#pragma unroll
+        for (int i = 0; i < 16; ++i) oacc[db][i] = 0.f;
+    float m_run = NEG_INF, l_run = 0.f;
+    const float c = P.scale_log2e;
+
+    // K operand row of this lane inside a 32-token block: MFMA row r holds token
+    //   page = bit4(r), token-in-page = 8*bit2(r) + 4*bit3(r) + (r & 3)
+    // so that accumulator registers 8*s2 .. 8*s2+7 of a lane are 8 consecutive tokens of one page.
+    const int k_tok = ((l32 >> 2) & 1) * 8 + ((l32 >> 3) & 1) * 4 + (l32 & 3);
+    const int k_lane_off = (l32 >> 4) * PB + k_tok * 16 + h * 256;  // + tb*2*PB + ks*512
+    const int v_lane_off = (h * HD + l32) * 16;                     // + s*PB + db*512
+
+    fetch_pages(0);
+    issue_loads(0);
+    if (ntiles > 1) fetch_pages(1);
+    store_stage(0);
+    __syncthreads();
+
+    for (int ti = 0; ti < ntiles; ++ti) {
+        const int buf = ti & 1;
+        if (ti + 1 < ntiles) {
+            issue_loads(ti + 1);
+            if (ti + 2 < ntiles) fetch_pages(ti + 2);
+        }
+        if (wave_active) {
+            const char* kb = smem + buf * STAGE + k_lane_off;
+            const char* vb = smem + buf * STAGE + KBYTES + v_lane_off;
+            f32x16 sacc[2];
+#pragma unroll
+            for (int tb = 0; tb < 2; ++tb)
+#pragma unroll
+                for (int i = 0; i < 16; ++i) sacc[tb][i] = 0.f;
+#pragma unroll
+            for (int ks = 0; ks < KS; ++ks)
+#pragma unroll
+                for (int tb = 0; tb < 2; ++tb) {
+                    bf16x8 a = as_bf16x8(*reinterpret_cast<const u32x4*>(kb + tb * 2 * PB + ks * 512));
+                    sacc[tb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, qreg[ks], sacc[tb], 0, 0, 0);
+                }
+            const int tile_base = it.kv_begin + ti * kTileTokens;
+            if (tile_base + kTileTokens - 1 > wmin_limit) {  // causal boundary crosses this tile
+#pragma unroll
+                for (int tb = 0; tb < 2; ++tb)
+#pragma unroll
+                    for (int i = 0; i < 16; ++i) {
+                        const int pos = tile_base + (tb * 2 + (i >> 3)) * 16 + h * 8 + (i & 7);
+                        if (pos > limit) sacc[tb][i] = NEG_INF;
+                    }
+            }
+            float mx = sacc[0][0];
+#pragma unroll
+            for (int tb = 0; tb < 2; ++tb)
+#pragma unroll
+                for (int i = 0; i < 16; ++i) mx = fmaxf(mx, sacc[tb][i]);
+            mx = fmaxf(mx, xor_shuffle(mx, 32));
+            const float m_new = fmaxf(m_run, mx);
+            const float m_use = m_new == NEG_INF ? 0.f : m_new;
+            const float mc = m_use * c;
+            if (__any(m_new != m_run)) {
+                const float alpha = fast_exp2(m_run * c - mc);  // m_run = -inf gives 0
+                l_run *= alpha;
+#pragma unroll
+                for (int db = 0; db < DB; ++db)
+#pragma unroll
+                    for (int i = 0; i < 16; ++i) oacc[db][i] *= alpha;
+                m_run = m_new;
+            }
+            float psum = 0.f;
+#pragma unroll
+            for (int tb = 0; tb < 2; ++tb)
+#pragma unroll
+                for (int i = 0; i < 16; ++i) {
+                    const float p = fast_exp2(__builtin_fmaf(sacc[tb][i], c, -mc));
+                    sacc[tb][i] = p;
+                    psum += p;
+                }
+            l_run += psum;
+#pragma unroll
+            for (int s = 0; s < 4; ++s) {
+                u32x4 pw;
+#pragma unroll
+                for (int e = 0; e < 4; ++e)
+                    pw[e] = pack_bf16(sacc[s >> 1][(s & 1) * 8 + 2 * e], sacc[s >> 1][(s & 1) * 8 + 2 * e + 1]);
+                const bf16x8 pb = as_bf16x8(pw);
+#pragma unroll
+                for (int db = 0; db < DB; ++db) {
+                    bf16x8 a = as_bf16x8(*reinterpret_cast<const u32x4*>(vb + s * PB + db * 512));
+                    oacc[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, pb, oacc[db], 0, 0, 0);
+                }
+            }
+        }
+        if (ti + 1 < ntiles) store_stage(buf ^ 1);
+        __syncthreads();
+    }
+
+    // epilogue: O^T register i of block db is d = db*32 + (i/4)*8 + h*4 + i%4 of column `col`
+    const float l_tot = l_run + xor_shuffle(l_run, 32);
+    if (col < ncols) {
+        if (it.part_off < 0) {
+            const float inv = 1.f / l_tot;
+            uint16_t* op = P.out + ((int64_t)(it.grow0 + jrow) * P.Hq + head) * HD + h * 4;
+#pragma unroll
+            for (int db = 0; db < DB; ++db)
+#pragma unroll
+                for (int i4 = 0; i4 < 4; ++i4) {
+                    u32x2 w;
+                    w[0] = pack_bf16(oacc[db][i4 * 4 + 0] * inv, oacc[db][i4 * 4 + 1] * inv);
+                    w[1] = pack_bf16(oacc[db][i4 * 4 + 2] * inv, oacc[db][i4 * 4 + 3] * inv);
+                    *reinterpret_cast<u32x2*>(op + db * 32 + i4 * 8) = w;
+                }
+        } else {
+            float* pp = P.partials + it.part_off;
+            float* po = pp + (int64_t)col * HD + h * 4;
+#pragma unroll
+            for (int db = 0; db < DB; ++db)
+#pragma unroll
+                for (int i4 = 0; i4 < 4; ++i4) {
+                    f32x4 w = {oacc[db][i4 * 4 + 0], oacc[db][i4 * 4 + 1], oacc[db][i4 * 4 + 2], oacc[db][i4 * 4 + 3]};
+                    *reinterpret_cast<f32x4*>(po + db * 32 + i4 * 8) = w;
+                }
+            if (h == 0) {
+                float* ml = pp + (int64_t)ncols * HD + col * 2;
+                ml[0] = m_run;
+                ml[1] = l_tot;
+            }
+        }
+    }
+}
+
+// ---------------------------------------------------------------------------------------------------
+// Narrow tile: rows*G <= 16 query columns (decode: 1 row x G heads).  HBM-bound: each of the 4 waves
+// streams its own quarter of the key range straight from the pool into MFMA operand registers
+// (v_mfma_f32_16x16x32_bf16; 32 tokens = 2 pages per step, one step prefetched), then the four
+// (o, m, l) are combined through LDS.
+// ---------------------------------------------------------------------------------------------------
+template <int HD>
+__device__ __forceinline__ void narrow_item(const KParams& P, const ppd_work_item& it, char* smem) {
+    constexpr int KS = HD / 32;   // k-steps of S^T
+    constexpr int DBN = HD / 16;  // 16-row d blocks of O^T
+    constexpr int WSTRIDE = kNarrowCols * (HD + 2);  // floats per wave in the combine buffer
+
+    const int tid = threadIdx.x;
+    const int lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int c16 = lane & 15;
+    const int g4 = lane >> 4;
+    const int G = P.G, lg = P.lgG;
+    const int ncols = it.nrows * G;
+    const int colc = c16 < ncols ? c16 : ncols - 1;
+    const int jrow = colc >> lg;
+    const int head = it.kvh * G + (colc & (G - 1));
+    const int limit = it.L + it.row0 + jrow;
+    const int min_limit = it.L + it.row0;
+
+    bf16x8 qreg[KS];
+    {
+        const uint16_t* qp = P.q + ((int64_t)(it.grow0 + jrow) * P.Hq + head) * HD + g4 * 8;
+#pragma unroll
+        for (int ks = 0; ks < KS; ++ks) {
+            u32x4 w = *reinterpret_cast<const u32x4*>(qp + ks * 32);
+            if (c16 >= ncols) w = u32x4{0, 0, 0, 0};
+            qreg[ks] = as_bf16x8(w);
+        }
+    }
+
+    const int32_t* pt_row = P.page_tables + (int64_t)it.seq * P.max_pages;
+    const int last_page = (it.kv_total - 1) >> 4;
+    const int nsteps = (it.kv_end - it.kv_begin + 31) >> 5;
+    const int s_lo = wave * nsteps / 4, s_hi = (wave + 1) * nsteps / 4;
+    const int wave_first_page = (it.kv_begin >> 4) + s_lo * 2;
+    const int64_t head_off = (int64_t)it.kvh * (kPage * HD);
+    const int64_t v_off = (int64_t)P.Hkv * (kPage * HD);
+
+    f32x4 oacc[DBN];
+#pragma unroll
+    for (int db = 0; db < DBN; ++db) oacc[db] = f32x4{0.f, 0.f, 0.f, 0.f};
+    float m_run = NEG_INF, l_run = 0.f;
+    const float c = P.scale_log2e;
+
+    // lane i of `ids` holds the page of logical page (batch*64 + i) of this wave's range
+    int ids_cur = 0, ids_nxt = 0;
+    auto load_ids = [&](int batch) {
+        return (int)fetch_page(P, pt_row, wave_first_page + batch * 64 + lane, last_page);
+    };
+    struct StepRegs {
+        u32x4 k[2][KS];  // K operand of the step's two pages
+        u32x4 v[DBN];    // V^T operand, one per 16-row d block
+    };
+    StepRegs ra, rb;
+    const int my_steps = s_hi - s_lo;
+    auto issue_step = [&](int k, StepRegs& r) {  // k = step index relative to s_lo
+        if ((k & 31) == 0 && k > 0) {
+            ids_cur = ids_nxt;
+            if (k + 32 < my_steps) ids_nxt = load_ids(k / 32 + 1);
+        }
+        const int li = (2 * k) & 63;
+        const int64_t pa = __builtin_amdgcn_readlane(ids_cur, li);
+        const int64_t pb = __builtin_amdgcn_readlane(ids_cur, li + 1);
+        const uint16_t* ka = P.pool + pa * P.page_stride + head_off;
+        const uint16_t* kb = P.pool + pb * P.page_stride + head_off;
+#pragma unroll
+        for (int ks = 0; ks < KS; ++ks) {
+            r.k[0][ks] = *reinterpret_cast<const u32x4*>(ka + (ks * 4 + g4) * 128 + c16 * 8);
+            r.k[1][ks] = *reinterpret_cast<const u32x4*>(kb + (ks * 4 + g4) * 128 + c16 * 8);
+        }
+        const int voff = ((g4 >> 1) * HD + c16) * 8 + (g4 & 1) * 4;
+#pragma unroll
+        for (int db = 0; db < DBN; ++db) {
+            const u32x2 a = *reinterpret_cast<const u32x2*>(ka + v_off + voff + db * 128);
+            const u32x2 b = *reinterpret_cast<const u32x2*>(kb + v_off + voff + db * 128);
+            r.v[db] = u32x4{a[0], a[1], b[0], b[1]};
+        }
+    };
+    auto compute_step = [&](int k, StepRegs& r) {
+        f32x4 sa = {0.f, 0.f, 0.f, 0.f}, sb = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+        for (int ks = 0; ks < KS; ++ks) {
+            sa = __builtin_amdgcn_mfma_f32_16x16x32_bf16(as_bf16x8(r.k[0][ks]), qreg[ks], sa, 0, 0, 0);
+            sb = __builtin_amdgcn_mfma_f32_16x16x32_bf16(as_bf16x8(r.k[1][ks]), qreg[ks], sb, 0, 0, 0);
+        }
+        // sa[i]: token 4*g4 + i of the step's first page; sb[i]: same of its second page
+        const int t0 = it.kv_begin + (s_lo + k) * 32;
+        const bool masked = t0 + 31 > min_limit || t0 + 32 > it.kv_end;
+        if (masked) {
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                const int pa = t0 + 4 * g4 + i, pb = pa + 16;
+                if (pa > limit || pa >= it.kv_end) sa[i] = NEG_INF;
+                if (pb > limit || pb >= it.kv_end) sb[i] = NEG_INF;
+            }
+            if (t0 + 32 > it.kv_total) {  // rows of the last page that were never written
+#pragma unroll
+                for (int db = 0; db < DBN; ++db) {
+#pragma unroll
+                    for (int e = 0; e < 8; ++e) {
+                        const int pos = t0 + (e >> 2) * 16 + 4 * g4 + (e & 3);
+                        if (pos >= it.kv_total) r.v[db][e >> 1] &= (e & 1) ? 0x0000FFFFu : 0xFFFF0000u;
+                    }
+                }
+            }
+        }
+        float mx = fmaxf(fmaxf(fmaxf(sa[0], sa[1]), fmaxf(sa[2], sa[3])), fmaxf(fmaxf(sb[0], sb[1]), fmaxf(sb[2], sb[3])));
+        mx = fmaxf(mx, xor_shuffle(mx, 16));
+        mx = fmaxf(mx, xor_shuffle(mx, 32));
+        const float m_new = fmaxf(m_run, mx);
+        const float m_use = m_new == NEG_INF ? 0.f : m_new;
+        const float mc = m_use * c;
+        if (__any(m_new != m_run)) {
+            const float alpha = fast_exp2(m_run * c - mc);
+            l_run *= alpha;
+#pragma unroll
+            for (int db = 0; db < DBN; ++db) oacc[db] *= alpha;
+            m_run = m_new;
+        }
+        float p[8];
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            p[i] = fast_exp2(__builtin_fmaf(sa[i], c, -mc));
+            p[4 + i] = fast_exp2(__builtin_fmaf(sb[i], c, -mc));
+        }
+        l_run += ((p[0] + p[1]) + (p[2] + p[3])) + ((p[4] + p[5]) + (p[6] + p[7]));
+        const u32x4 pw = {pack_bf16(p[0], p[1]), pack_bf16(p[2], p[3]), pack_bf16(p[4], p[5]), pack_bf16(p[6], p[7])};
+        const bf16x8 pb8 = as_bf16x8(pw);
+#pragma unroll
+        for (int db = 0; db < DBN; ++db)
+            oacc[db] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(as_bf16x8(r.v[db]), pb8, oacc[db], 0, 0, 0);
+    };
+
+    if (my_steps > 0) {
+        ids_cur = load_ids(0);
+        if (my_steps > 32) ids_nxt = load_ids(1);
+        issue_step(0, ra);
+    }
+    for (int k = 0; k < my_steps; k += 2) {  // one step always in flight; registers alternate ra / rb
+        if (k + 1 < my_steps) issue_step(k + 1, rb);
+        compute_step(k, ra);
+        if (k + 1 < my_steps) {
+            if (k + 2 < my_steps) issue_step(k + 2, ra);
+            compute_step(k + 1, rb);
+        }
+    }
+    l_run += xor_shuffle(l_run, 16);
+    l_run += xor_shuffle(l_run, 32);
+
+    // combine the four waves: O^T register i of block db is d = db*16 + 4*g4 + i of column c16
+    float* wbuf = reinterpret_cast<float*>(smem) + wave * WSTRIDE;
+#pragma unroll
+    for (int db = 0; db < DBN; ++db)
+        *reinterpret_cast<f32x4*>(wbuf + c16 * HD + db * 16 + 4 * g4) = oacc[db];
+    if (g4 == 0) {
+        wbuf[kNarrowCols * HD + c16 * 2] = m_run;
+        wbuf[kNarrowCols * HD + c16 * 2 + 1] = l_run;
+    }
+    __syncthreads();
+    const float* all = reinterpret_cast<const float*>(smem);
+    for (int idx = tid; idx < ncols * HD; idx += kThreads) {
+        const int col = idx / HD, d = idx % HD;
+        float mw[4], mm = NEG_INF;
+#pragma unroll
+        for (int w = 0; w < 4; ++w) {
+            mw[w] = all[w * WSTRIDE + kNarrowCols * HD + col * 2];
+            mm = fmaxf(mm, mw[w]);
+        }
+        float o = 0.f, l = 0.f;
+#pragma unroll
+        for (int w = 0; w < 4; ++w) {
+            const float f = mw[w] == NEG_INF ? 0.f : fast_exp2((mw[w] - mm) * c);
+            o += f * all[w * WSTRIDE + col * HD + d];
+            l += f * all[w * WSTRIDE + kNarrowCols * HD + col * 2 + 1];
+        }
+        if (it.part_off < 0) {
+            const int64_t orow = (int64_t)(it.grow0 + (col >> lg)) * P.Hq + it.kvh * G + (col & (G - 1));
+            const float val = o / l;
+            const float other = __shfl_xor(val, 1, 64);  // d and d^1 sit in neighbouring lanes
+            if ((d & 1) == 0) *reinterpret_cast<uint32_t*>(P.out + orow * HD + d) = pack_bf16(val, other);
+        } else {
+            float* pp = P.partials + it.part_off;
+            pp[(int64_t)col * HD + d] = o;
+            if (d == 0) {
+                pp[(int64_t)ncols * HD + col * 2] = mm;
+                pp[(int64_t)ncols * HD + col * 2 + 1] = l;
+            }
+        }
+    }
+}
+
+template <int HD>
+__global__ __launch_bounds__(kThreads, 2) void ppd_mixed_kernel(const KParams P) {
+    // Two stages of (4 pages of K + 4 pages of V) for the MFMA path = 512*HD bytes (64 KiB at HD = 128, the
+    // static limit).  The narrow path's combine buffer uses the first 256*(HD+2) bytes.  The next-tile index
+    // is broadcast through the last word: the MFMA path ends on a barrier and the narrow path never
+    // touches that word, so it is free whenever a tile has finished.
+    __shared__ __attribute__((aligned(16))) char smem[512 * HD];
+    volatile int* s_next = reinterpret_cast<volatile int*>(smem + 512 * HD - 4);
+    const int tid = threadIdx.x;
+    for (;;) {
+        if (tid == 0) *s_next = (int)atomicAdd(&P.counters[0], 1u);
+        __syncthreads();
+        const int idx = __builtin_amdgcn_readfirstlane(*s_next);
+        __syncthreads();  // everyone has read s_next, and the previous tile's LDS use is over
+        if (idx >= P.n_items) break;
+        const ppd_work_item it = P.items[idx];
+        if (it.kind == 0)
+            narrow_item<HD>(P, it, smem);
+        else
+            mfma_item<HD>(P, it, smem);
+    }
+    if (tid == 0) {
+        // the last workgroup to run out of work re-arms the cursor for the next launch
+        const unsigned done = atomicAdd(&P.counters[1], 1u);
+        if (done == gridDim.x - 1) {
+            __hip_atomic_store(&P.counters[0], 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            __hip_atomic_store(&P.counters[1], 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        }
+    }
+}
+
+// ---------------------------------------------------------------------------------------------------
+// Log-sum-exp merge of split partials: out = sum_j o_j 2^{(m_j - m*) c} / sum_j l_j 2^{(m_j - m*) c},
+// splits taken in index order (deterministic).  One workgroup per merge group, one wave per column.
+// ---------------------------------------------------------------------------------------------------
+__global__ __launch_bounds__(kThreads) void ppd_merge_kernel(const MergeParams M) {
+    const MergeGroup g = M.groups[blockIdx.x];
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int ncols = g.nrows * M.G;
+    const int D = M.D;
+    for (int col = wave; col < ncols; col += kThreads / 64) {
+        float mm = NEG_INF;
+        for (int j = 0; j < g.nsplit; ++j)
+            mm = fmaxf(mm, M.partials[g.part_off + g.part_stride * j + (int64_t)ncols * D + col * 2]);
+        float o0 = 0.f, o1 = 0.f, l = 0.f;
+        for (int j = 0; j < g.nsplit; ++j) {
+            const float* pp = M.partials + g.part_off + g.part_stride * j;
+            const float mj = pp[(int64_t)ncols * D + col * 2];
+            const float f = mj == NEG_INF ? 0.f : fast_exp2((mj - mm) * M.scale_log2e);
+            l += f * pp[(int64_t)ncols * D + col * 2 + 1];
+            const int d = lane * 2;
+            if (d < D) {
+                const f32x2 v = *reinterpret_cast<const f32x2*>(pp + (int64_t)col * D + d);
+                o0 += f * v[0];
+                o1 += f * v[1];
+            }
+        }
+        const int d = lane * 2;
+        if (d < D) {
+            const int64_t orow = (int64_t)(g.grow0 + (col >> M.lgG)) * M.Hq + g.kvh * M.G + (col & (M.G - 1));
+            *reinterpret_cast<uint32_t*>(M.out + orow * D + d) = pack_bf16(o0 / l, o1 / l);
+        }
+    }
+}
+
+// ---------------------------------------------------------------------------------------------------
+// Paged KV append.  One workgroup moves 8 consecutive tokens of the batch for all KV heads.
+// K: 16-byte granules (8 d of one token), lanes ordered token-minor so that tokens in consecutive slots
+//    write 128 contiguous bytes.  V: a granule is 8 tokens of one d; when the 8 tokens fill one aligned
+//    granule (the common case for prefill) each thread writes it whole, otherwise element by element.
+// ---------------------------------------------------------------------------------------------------
+__global__ __launch_bounds__(kThreads) void ppd_kv_append_kernel(const uint16_t* __restrict__ k,
+                                                                 const uint16_t* __restrict__ v,
+                                                                 uint16_t* __restrict__ pool,
+                                                                 const int64_t* __restrict__ slots, int64_t T,
+                                                                 int Hkv, int D, int64_t num_pages,
+                                                                 uint32_t* err_flags) {
+    __shared__ int64_t s_slot[8];
+    __shared__ int s_aligned;
+    const int tid = threadIdx.x;
+    const int64_t t0 = (int64_t)blockIdx.x * 8;
+    const int nt = (int)((T - t0) < 8 ? (T - t0) : 8);
+    if (tid < 8) {
+        int64_t s = tid < nt ? slots[t0 + tid] : -1;
+        if (s >= num_pages * kPage) {
+            atomicOr(err_flags, 1u);
+            s = -1;
+        }
+        s_slot[tid] = s;
+    }
+    __syncthreads();
+    if (tid == 0) {
+        int ok = nt == 8 && s_slot[0] >= 0 && (s_slot[0] & 7) == 0;
+        for (int i = 1; i < 8 && ok; ++i) ok = s_slot[i] == s_slot[0] + i;
+        s_aligned = ok;
+    }
+    __syncthreads();
+    const int64_t S = 2LL * Hkv * kPage * D;
+    const int HD = Hkv * D;
+    // K: work unit = (h, granule c, token), token fastest
+    const int kunits = Hkv * (D / 8) * 8;
+    for (int u = tid; u < kunits; u += kThreads) {
+        const int tok = u & 7;
+        const int hc = u >> 3;
+        const int c = hc % (D / 8), hh = hc / (D / 8);
+        const int64_t s = s_slot[tok];
+        if (s < 0) continue;
+        const u32x4 val = *reinterpret_cast<const u32x4*>(k + (t0 + tok) * HD + hh * D + c * 8);
+        const int64_t page = s >> 4;
+        const int off = (int)(s & 15);
+        *reinterpret_cast<u32x4*>(pool + page * S + (int64_t)hh * kPage * D + c * (kPage * 8) + off * 8) = val;
+    }
+    // V: work unit = (h, d)
+    if (s_aligned) {
+        const int64_t page = s_slot[0] >> 4;
+        const int half = (int)((s_slot[0] & 15) >> 3);
+        for (int u = tid; u < HD; u += kThreads) {
+            const int hh = u / D, d = u % D;
+            uint32_t w[4];
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                const uint32_t lo = v[(t0 + 2 * e) * HD + u];
+                const uint32_t hi = v[(t0 + 2 * e + 1) * HD + u];
+                w[e] = lo | (hi << 16);
+            }
+            *reinterpret_cast<u32x4*>(pool + page * S + (int64_t)Hkv * kPage * D + (int64_t)hh * kPage * D +
+                                      half * (D * 8) + d * 8) = u32x4{w[0], w[1], w[2], w[3]};
+        }
+    } else {
+        for (int u = tid; u < HD * 8; u += kThreads) {
+            const int tok = u / HD, e = u % HD;
+            const int64_t s = s_slot[tok];
+            if (s < 0) continue;
+            const int hh = e / D, d = e % D;
+            const int64_t page = s >> 4;
+            const int off = (int)(s & 15);
+            pool[page * S + (int64_t)Hkv * kPage * D + (int64_t)hh * kPage * D + (off >> 3) * (D * 8) + d * 8 +
+                 (off & 7)] = v[(t0 + tok) * HD + e];
+        }
+    }
+}
+
+// ---------------------------------------------------------------------------------------------------
+int launch_mixed(const KParams& p, int head_dim, int grid, void* stream) {
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    if (head_dim == 128)
+        hipLaunchKernelGGL(ppd_mixed_kernel<128>, dim3(grid), dim3(kThreads), 0, st, p);
+    else
+        hipLaunchKernelGGL(ppd_mixed_kernel<64>, dim3(grid), dim3(kThreads), 0, st, p);
+    return (int)hipGetLastError();
+}
+
+int launch_merge(const MergeParams& p, void* stream) {
+    hipLaunchKernelGGL(ppd_merge_kernel, dim3(p.n_groups), dim3(kThreads), 0, static_cast<hipStream_t>(stream), p);
+    return (int)hipGetLastError();
+}
+
+int launch_kv_append(const uint16_t* k, const uint16_t* v, uint16_t* pool, const int64_t* slots, int64_t T, int Hkv,
+                     int D, int64_t num_pages, uint32_t* err_flags, void* stream) {
+    const int64_t blocks = (T + 7) / 8;
+    hipLaunchKernelGGL(ppd_kv_append_kernel, dim3((unsigned)blocks), dim3(kThreads), 0,
+                       static_cast<hipStream_t>(stream), k, v, pool, slots, T, Hkv, D, num_pages, err_flags);
+    return (int)hipGetLastError();
+}
+
+}  // namespace ppd

@@ -1,0 +1,191 @@
+// Host planner of the one-launch mixed step: classifies sequences, splits key ranges, orders tiles.
+//
+// Per sequence (L cached, n new; paper section 4.1 with L = the paper's n and n = its m): n*G <= 16 query
+// columns -> narrow tiles (decode is n = 1), else row blocks of 128/G rows on the MFMA path.  A tile is
+// (sequence, KV head, row block, key range); key ranges are split so that the launch has several tiles per
+// resident workgroup, and tiles run longest-first from one queue so that HBM-bound narrow tiles and
+// MFMA-bound row-block tiles share the compute units.
+#include <algorithm>
+#include <cmath>
+#include <cstring>
+
+#include "ppd_internal.h"
+
+namespace ppd {
+
+ppd_status validate_shape(const ppd_shape* s, const char** err) {
+    static const char* kNull = "shape is NULL";
+    static const char* kDim = "head_dim must be 64 or 128";
+    static const char* kPageSz = "page_size must be 16";
+    static const char* kHeads = "num_q_heads must be G * num_kv_heads with G in {1,2,4,8}, num_kv_heads >= 1";
+    static const char* kPages = "num_pages must be >= 1 and the pool below 2^40 elements";
+    const char* dummy;
+    if (!err) err = &dummy;
+    if (!s) { *err = kNull; return PPD_ERR_NULL; }
+    if (s->head_dim != 64 && s->head_dim != 128) { *err = kDim; return PPD_ERR_SHAPE; }
+    if (s->page_size != kPage) { *err = kPageSz; return PPD_ERR_SHAPE; }
+    if (s->num_kv_heads < 1 || s->num_q_heads < 1 || s->num_q_heads % s->num_kv_heads != 0) {
+        *err = kHeads; return PPD_ERR_SHAPE;
+    }
+    int G = s->num_q_heads / s->num_kv_heads;
+    if (G != 1 && G != 2 && G != 4 && G != 8) { *err = kHeads; return PPD_ERR_SHAPE; }
+    if (s->num_kv_heads > 1024) { *err = kHeads; return PPD_ERR_SHAPE; }
+    if (s->num_pages < 1 || s->num_pages > (int64_t(1) << 40) / (2LL * s->num_kv_heads * kPage * s->head_dim)) {
+        *err = kPages; return PPD_ERR_SHAPE;
+    }
+    return PPD_OK;
+}
+
+static inline int64_t round_up(int64_t x, int64_t m) { return (x + m - 1) / m * m; }
+
+// Splits [0, len) into pieces of at most ~chunk tokens with boundaries on multiples of kTileTokens.
+static void split_range(int64_t len, int64_t chunk, std::vector<int32_t>* bounds) {
+    bounds->clear();
+    int64_t nsplit = std::max<int64_t>(1, (len + chunk - 1) / chunk);
+    int64_t per = round_up((len + nsplit - 1) / nsplit, kTileTokens);
+    for (int64_t b = 0; b < len; b += per) bounds->push_back((int32_t)b);
+    bounds->push_back((int32_t)len);
+}
+
+ppd_status build_plan(const ppd_shape& s, const int32_t* L, const int32_t* n, int32_t B, const PlanOptions& o,
+                      Plan* plan, const char** err) {
+    static const char* kNull = "L / n is NULL";
+    static const char* kNeg = "n_i must be >= 1 and L_i >= 0";
+    static const char* kBig = "L_i + n_i and the total row count must stay below 2^30";
+    static const char* kChunk = "chunk options must be 0 or a positive multiple of 64; grid >= 0";
+    const char* dummy;
+    if (!err) err = &dummy;
+    plan->items.clear();
+    plan->groups.clear();
+    std::memset(&plan->stats, 0, sizeof plan->stats);
+    if (B < 0) { *err = kNeg; return PPD_ERR_RANGE; }
+    if (B > 0 && (!L || !n)) { *err = kNull; return PPD_ERR_NULL; }
+    if (o.narrow_chunk < 0 || o.narrow_chunk % kTileTokens || o.mfma_chunk < 0 || o.mfma_chunk % kTileTokens ||
+        o.grid < 0 || o.num_cus < 1) {
+        *err = kChunk; return PPD_ERR_RANGE;
+    }
+    const int D = s.head_dim, Hq = s.num_q_heads, Hkv = s.num_kv_heads, G = Hq / Hkv;
+    const int64_t kv_tok_bytes_head = 2LL * D * 2;  // K and V of one token of one KV head
+    int64_t rows = 0;
+    double flops = 0;
+    int64_t kv_tokens = 0;
+    for (int i = 0; i < B; ++i) {
+        if (n[i] < 1 || L[i] < 0) { *err = kNeg; return PPD_ERR_RANGE; }
+        if ((int64_t)L[i] + n[i] >= (1 << 30)) { *err = kBig; return PPD_ERR_RANGE; }
+        rows += n[i];
+        kv_tokens += (int64_t)L[i] + n[i];
+        flops += 4.0 * Hq * D * ((double)n[i] * L[i] + (double)n[i] * ((double)n[i] + 1) / 2);
+    }
+    if (rows >= (1 << 30)) { *err = kBig; return PPD_ERR_RANGE; }
+
+    auto is_narrow = [&](int i) { return o.force_kind != 1 && (int64_t)n[i] * G <= kNarrowCols; };
+    const int rows_per_block = kMfmaCols / G;
+
+    // Total cost in "token units": a narrow tile costs its tokens, an MFMA tile twice its tokens (rough
+    // ratio of time per key at the rates the two paths reach; only the order of tiles depends on it).
+    double cost_total = 0;
+    for (int i = 0; i < B; ++i) {
+        if (is_narrow(i)) {
+            cost_total += (double)Hkv * (L[i] + n[i]);
+        } else {
+            for (int r0 = 0; r0 < n[i]; r0 += rows_per_block)
+                cost_total += 2.0 * Hkv * (L[i] + std::min<int64_t>(n[i], r0 + rows_per_block));
+        }
+    }
+    const int slots = o.grid > 0 ? o.grid : 2 * o.num_cus;  // two workgroups are resident per compute unit
+    const double per_item = cost_total / (4.0 * slots);     // aim for ~4 tiles per resident workgroup
+    int64_t narrow_chunk = o.narrow_chunk > 0
+                               ? o.narrow_chunk
+                               : std::min<int64_t>(8192, std::max<int64_t>(256, round_up((int64_t)per_item, kTileTokens)));
+    int64_t mfma_chunk = o.mfma_chunk > 0
+                             ? o.mfma_chunk
+                             : std::min<int64_t>(8192, std::max<int64_t>(512, round_up((int64_t)(per_item / 2), kTileTokens)));
+
+    struct Keyed { double cost; ppd_work_item it; };
+    std::vector<Keyed> keyed;
+    std::vector<int32_t> bounds;
+    int64_t part_floats = 0;
+    int64_t grow = 0;
+    int64_t n_narrow = 0, n_mfma = 0, bytes_tiles = 0;
+    for (int i = 0; i < B; ++i) {
+        const bool narrow = is_narrow(i);
+        const int blk = narrow ? n[i] : rows_per_block;
+        for (int r0 = 0; r0 < n[i]; r0 += blk) {
+            const int nrows = std::min(blk, n[i] - r0);
+            const int64_t vis_end = (int64_t)L[i] + r0 + nrows;  // keys 0 .. L + last row of the block
+            split_range(vis_end, narrow ? narrow_chunk : mfma_chunk, &bounds);
+            const int nsplit = (int)bounds.size() - 1;
+            const int64_t stride = (int64_t)nrows * G * (D + 2);
+            for (int h = 0; h < Hkv; ++h) {
+                int group = -1;
+                int64_t base = -1;
+                if (nsplit > 1) {
+                    group = (int)plan->groups.size();
+                    base = part_floats;
+                    plan->groups.push_back(MergeGroup{(int32_t)(grow + r0), nrows, h, nsplit, base, stride});
+                    part_floats += stride * nsplit;
+                }
+                for (int sp = 0; sp < nsplit; ++sp) {
+                    ppd_work_item it;
+                    std::memset(&it, 0, sizeof it);
+                    it.kind = narrow ? 0 : 1;
+                    it.seq = i;
+                    it.kvh = h;
+                    it.row0 = r0;
+                    it.nrows = nrows;
+                    it.grow0 = (int32_t)(grow + r0);
+                    it.L = L[i];
+                    it.kv_total = L[i] + n[i];
+                    it.kv_begin = bounds[sp];
+                    it.kv_end = bounds[sp + 1];
+                    it.group = group;
+                    it.part_off = nsplit > 1 ? base + stride * sp : -1;
+                    const int64_t toks = it.kv_end - it.kv_begin;
+                    keyed.push_back(Keyed{(narrow ? 1.0 : 2.0) * toks, it});
+                    (narrow ? n_narrow : n_mfma) += 1;
+                    bytes_tiles += toks * kv_tok_bytes_head;
+                }
+            }
+        }
+        grow += n[i];
+    }
+    std::stable_sort(keyed.begin(), keyed.end(), [](const Keyed& a, const Keyed& b) { return a.cost > b.cost; });
+    plan->items.reserve(keyed.size());
+    for (auto& k : keyed) plan->items.push_back(k.it);
+
+    ppd_plan_stats& st = plan->stats;
+    st.n_items = (int64_t)plan->items.size();
+    st.n_narrow = n_narrow;
+    st.n_mfma = n_mfma;
+    st.n_groups = (int64_t)plan->groups.size();
+    st.partial_floats = part_floats;
+    st.kv_bytes = kv_tokens * kv_tok_bytes_head * Hkv;
+    st.kv_bytes_tiles = bytes_tiles;
+    st.flops = flops;
+    st.narrow_chunk = (int32_t)narrow_chunk;
+    st.mfma_chunk = (int32_t)mfma_chunk;
+    st.grid = (int32_t)std::max<int64_t>(1, std::min<int64_t>(slots, st.n_items));
+    return PPD_OK;
+}
+
+}  // namespace ppd
+
+extern "C" ppd_status ppd_plan_build(const ppd_shape* shape, const int32_t* L, const int32_t* n, int32_t B,
+                                     int32_t narrow_chunk, int32_t mfma_chunk, int32_t grid, int32_t force_kind,
+                                     int32_t num_cus, ppd_work_item* items, int64_t capacity, ppd_plan_stats* stats) {
+    ppd_status st = ppd::validate_shape(shape, nullptr);
+    if (st != PPD_OK) return st;
+    ppd::PlanOptions o;
+    o.narrow_chunk = narrow_chunk;
+    o.mfma_chunk = mfma_chunk;
+    o.grid = grid;
+    o.force_kind = force_kind;
+    o.num_cus = num_cus > 0 ? num_cus : 256;
+    ppd::Plan plan;
+    st = ppd::build_plan(*shape, L, n, B, o, &plan, nullptr);
+    if (st != PPD_OK) return st;
+    if (items)
+        for (int64_t i = 0; i < std::min<int64_t>(capacity, (int64_t)plan.items.size()); ++i) items[i] = plan.items[i];
+    if (stats) *stats = plan.stats;
+    return PPD_OK;
+}

@@ -1,0 +1,204 @@
+"""Parity of the HIP path against the CPU oracle, element by element, through the C ABI (needs an MI355X).
+
+Bar: KV append bit-exact; attention max-abs <= 2e-2 and per-(row, head) relative L2 <= 1e-2 against the
+double-precision oracle (bf16 inputs, fp32 accumulation, bf16 probabilities and output on the GPU side).
+"""
+import numpy as np
+import pytest
+
+import synthetic_inputs as si
+from helpers import bits_to_f32, check_close, oracle_out, oracle_pool
+
+pytestmark = pytest.mark.gpu
+
+
+def _step(b, **kw):
+    from gpu_helpers import gpu_step
+    return gpu_step(b, **kw)
+
+
+def _compare(b, **kw):
+    print("case", b.name, "L", b.L.tolist()[:8], "n", b.n.tolist()[:8], kw, flush=True)
+    ref_pool = oracle_pool(b)
+    pool, out, stats = _step(b, **kw)
+    assert np.array_equal(pool, ref_pool), "KV append is not bit-exact"
+    ref = oracle_out(b, ref_pool)
+    worst = check_close(bits_to_f32(out), ref)
+    print("  max-abs %.3e  items %d (narrow %d, mfma %d, groups %d)" %
+          (worst, stats["n_items"], stats["n_narrow"], stats["n_mfma"], stats["n_groups"]), flush=True)
+    return out, stats
+
+
+@pytest.mark.parametrize("seed", [0, 1, 2])
+def test_cfg1_tiny_mixed(seed):
+    _compare(si.cfg1_tiny(seed))
+
+
+def test_cfg1_peaky_queries():
+    """q scaled x4: outputs are O(1) so the absolute bound bites."""
+    _compare(si.cfg1_tiny(0, q_std=4.0))
+
+
+@pytest.mark.parametrize("Hq,Hkv,D", [(32, 8, 128), (8, 8, 128), (8, 4, 64), (8, 1, 128), (16, 2, 64)])
+def test_shapes_and_ragged_lengths(Hq, Hkv, D):
+    L = [0, 0, 1, 15, 16, 17, 63, 64, 65, 300, 1000, 129]
+    n = [1, 130, 1, 1, 3, 40, 2, 1, 70, 5, 1, 260]
+    _compare(si.make_batch("ragged", L=L, n=n, Hq=Hq, Hkv=Hkv, D=D, seed=21, slack_pages=7))
+
+
+def test_split_chunks_and_merge():
+    """Small forced split sizes: many partials per row block, several tiles per split, ragged tails."""
+    b = si.make_batch("splits", L=[700, 0, 1500, 333], n=[1, 200, 90, 2], Hq=32, Hkv=8, D=128, seed=22, slack_pages=3)
+    _compare(b, options={"narrow_chunk": 64, "mfma_chunk": 64})
+    _compare(b, options={"narrow_chunk": 256, "mfma_chunk": 128, "grid": 3})
+
+
+def test_decode_batch_scaled():
+    _compare(si.cfg2_decode(0, B=12, Lmin=100, Lmax=3000))
+
+
+def test_append_prefill_batch_scaled():
+    _compare(si.cfg3_append_prefill(0, B=4, Lmin=200, Lmax=1500, n_median=60, n_lo=16, n_hi=200))
+
+
+def test_mixed_batch_scaled_and_full_prefill_variant():
+    kw = dict(n_decode=10, n_ap=2, dec_L=(100, 2000), ap_L=(300, 1500), ap_n=(40, 150))
+    _compare(si.cfg4_mixed(0, **kw))
+    _compare(si.cfg4_mixed(0, full_prefill=True, **kw))
+
+
+def test_n1_append_prefill_equals_decode():
+    """The same decode rows through the narrow path and through the MFMA row-block path."""
+    b = si.cfg2_decode(3, B=6, Lmin=50, Lmax=900)
+    out_a, st_a = _compare(b)
+    out_b, st_b = _compare(b, options={"force_kind": 1})
+    assert st_a["n_mfma"] == 0 and st_b["n_narrow"] == 0
+    check_close(bits_to_f32(out_b), bits_to_f32(out_a).astype(np.float64), max_abs=2e-2, rel=1e-2)
+
+
+def test_append_prefill_equals_tail_of_recompute_on_gpu():
+    b = si.make_batch("ap", L=[500, 77], n=[100, 30], Hq=32, Hkv=8, D=128, seed=23)
+    _, out_ap, _ = _step(b)
+    tot = (b.L + b.n).astype(np.int32)
+    rng = np.random.default_rng(5)
+    qf = si.normal_bf16(rng, (int(tot.sum()), b.Hq, b.D))
+    at = 0
+    for i in range(b.B):
+        qf[at + int(b.L[i]):at + int(tot[i])] = b.q[int(b.row_off[i]):int(b.row_off[i + 1])]
+        at += int(tot[i])
+    full = si.MixedBatch(name="full", Hq=b.Hq, Hkv=b.Hkv, D=b.D, P=b.P, num_pages=b.num_pages, scale=b.scale,
+                         L=np.zeros(b.B, np.int32), n=tot, page_tables=b.page_tables, q=qf, k=b.k, v=b.v)
+    _, out_full, _ = _step(full)
+    at = 0
+    for i in range(b.B):
+        tail = bits_to_f32(out_full[at + int(b.L[i]):at + int(tot[i])])
+        mine = bits_to_f32(out_ap[int(b.row_off[i]):int(b.row_off[i + 1])])
+        check_close(mine, tail.astype(np.float64))
+        at += int(tot[i])
+
+
+def test_page_relabelling_and_determinism():
+    b = si.cfg1_tiny(1)
+    _, out1, _ = _step(b)
+    _, out2, _ = _step(b)
+    assert np.array_equal(out1, out2), "not run-to-run deterministic"
+    rng = np.random.default_rng(99)
+    relabel = rng.permutation(b.num_pages).astype(np.int32)
+    pt = np.where(b.page_tables >= 0, relabel[np.maximum(b.page_tables, 0)], -1).astype(np.int32)
+    b2 = si.MixedBatch(name="perm", Hq=b.Hq, Hkv=b.Hkv, D=b.D, P=b.P, num_pages=b.num_pages, scale=b.scale,
+                       L=b.L, n=b.n, page_tables=pt, q=b.q, k=b.k, v=b.v)
+    _, out3, _ = _step(b2)
+    assert np.array_equal(out1, out3), "page order changed the result"
+
+
+def test_single_key_is_exact_and_scale_zero():
+    b = si.make_batch("one", L=[0, 0], n=[1, 1], Hq=8, Hkv=2, D=64, seed=24)
+    _, out, _ = _step(b)
+    for i in range(2):
+        _, v = b.seq_kv(i)
+        for h in range(8):
+            assert np.array_equal(out[i, h], v[0, h // 4])
+    bz = si.make_batch("z", L=[40, 0], n=[1, 20], Hq=8, Hkv=2, D=64, seed=25)
+    bz.scale = 0.0
+    _compare(bz)
+
+
+def test_append_in_one_call_and_skipped_slots():
+    import torch
+    import paper_2603_13358_amd as ppd
+    from gpu_helpers import from_dev_u16, to_dev_u16
+    b = si.cfg1_tiny(2)
+    pool_a, _, _ = _step(b)
+    pool_b, _, _ = _step(b, append_in_one_call=True)
+    assert np.array_equal(pool_a, pool_b)
+    # negative slots are skipped; slots beyond the pool are skipped and flagged
+    dev = torch.device("cuda:0")
+    ctx = ppd.Context(b.Hq, b.Hkv, b.D, b.num_pages)
+    pool = torch.zeros((ctx.pool_elems(),), dtype=torch.int16, device=dev)
+    k, v, slots = b.new_part()
+    slots = slots.copy()
+    slots[3] = -1
+    slots[10] = b.num_pages * b.P + 5
+    ctx.kv_append(to_dev_u16(k, torch, dev), to_dev_u16(v, torch, dev), pool, torch.from_numpy(slots).to(dev))
+    assert ctx.device_error_flags() == 1
+    assert ctx.device_error_flags() == 0
+    import oracle
+    ref = np.zeros(ctx.pool_elems(), np.uint16)
+    slots[10] = -1
+    oracle.kv_append(k, v, ref, slots, b.Hkv, b.D, b.P, b.num_pages)
+    assert np.array_equal(from_dev_u16(pool), ref)
+    ctx.close()
+
+
+def test_bad_page_id_is_flagged_not_dereferenced():
+    import torch
+    import paper_2603_13358_amd as ppd
+    from gpu_helpers import to_dev_u16
+    b = si.make_batch("bad", L=[40], n=[1], Hq=8, Hkv=2, D=64, seed=26)
+    dev = torch.device("cuda:0")
+    ctx = ppd.Context(b.Hq, b.Hkv, b.D, b.num_pages)
+    pool = torch.zeros((ctx.pool_elems(),), dtype=torch.int16, device=dev)
+    pt = b.page_tables.copy()
+    pt[0, 1] = b.num_pages + 1000
+    out = torch.zeros((b.T, b.Hq, b.D), dtype=torch.int16, device=dev)
+    ctx.mixed_attention(to_dev_u16(b.q, torch, dev), pool, torch.from_numpy(pt).to(dev), b.L, b.n, b.scale, out)
+    assert ctx.device_error_flags() == 2
+    ctx.close()
+
+
+def test_host_argument_errors_enqueue_nothing():
+    import torch
+    import paper_2603_13358_amd as ppd
+    from gpu_helpers import to_dev_u16
+    b = si.cfg1_tiny(0)
+    dev = torch.device("cuda:0")
+    ctx = ppd.Context(b.Hq, b.Hkv, b.D, b.num_pages)
+    pool = torch.zeros((ctx.pool_elems(),), dtype=torch.int16, device=dev)
+    out = torch.full((b.T, b.Hq, b.D), 7, dtype=torch.int16, device=dev)
+    q = to_dev_u16(b.q, torch, dev)
+    pt = torch.from_numpy(b.page_tables).to(dev)
+    cases = [
+        (dict(n=[64, 0, 12, 1]), -3), (dict(L=[0, -1, 100, 256]), -3), (dict(scale=-1.0), -3),
+        (dict(scale=float("nan")), -3), (dict(max_pages=3), -4),
+    ]
+    for kw, code in cases:
+        args = dict(L=b.L, n=b.n, scale=b.scale, max_pages=None)
+        args.update(kw)
+        with pytest.raises(ppd.PPDError) as e:
+            ppd.ppd_mixed_attention(ctx.handle, q, pool, pt, args["L"], args["n"], args["scale"], out,
+                                    max_pages=args["max_pages"])
+        assert e.value.status == code, (kw, e.value)
+    with pytest.raises(ppd.PPDError) as e:
+        ppd.ppd_mixed_attention(ctx.handle, None, pool, pt, b.L, b.n, b.scale, out)
+    assert e.value.status == -1
+    torch.cuda.synchronize()
+    assert bool((out == 7).all()), "a rejected call touched the output"
+    # empty batch and empty append are no-ops
+    ppd.ppd_mixed_attention(ctx.handle, q, pool, pt, np.zeros(0, np.int32), np.zeros(0, np.int32), b.scale, out)
+    ppd.ppd_kv_append(ctx.handle, None, None, pool, None, T=0)
+    ctx.close()
+    for shape, code in [((8, 2, 96, 16, 4), -2), ((8, 2, 64, 32, 4), -2), ((8, 3, 64, 16, 4), -2),
+                        ((32, 2, 64, 16, 4), -2), ((8, 2, 64, 16, 0), -2)]:
+        with pytest.raises(ppd.PPDError) as e:
+            ppd.ppd_create(*shape)
+        assert e.value.status == code
