@@ -1,0 +1,216 @@
+#!/usr/bin/env python3
+"""Benchmark of the decode-node mixed step on one MI355X.
+
+A step = one pass of the whole hot path over one synthetic batch: ppd_kv_append of the new tokens'
+K/V, then ppd_mixed_attention (plan on the host, one launch of the mixed kernel, LSE merge).  Inputs are
+resident in HBM before the timed region.  Default workload: the decode-node mixed batch (128 decode
+sequences co-batched with 4 append-prefills on a Llama-3-8B-shaped layer); the same run also times the
+decode-only and full-prefill variants (decode-step slowdown), the decode-only batch (HBM fraction) and
+the append-prefill-only batch (MFMA fraction), and the CPU oracle on a bounded sample.
+
+Prints ONE JSON line.
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+for p in (ROOT, os.path.join(ROOT, "tests")):
+    if p not in sys.path:
+        sys.path.insert(0, p)
+
+import numpy as np
+
+HBM_PEAK_GBS = 8000.0       # MI355X HBM3E, published
+MFMA_BF16_PEAK_TFLOPS = 2500.0  # MI355X dense bf16 MFMA, published
+
+
+def make_shapes(name, seed):
+    import synthetic_inputs as si
+    if name == "cfg4_mixed_ap":
+        return si.cfg4_mixed(seed, with_data=False)
+    if name == "cfg4_mixed_full":
+        return si.cfg4_mixed(seed, full_prefill=True, with_data=False)
+    if name == "cfg4_decode_only":
+        return si.cfg4_mixed(seed, with_ap=False, with_data=False)
+    if name == "cfg2_decode":
+        return si.cfg2_decode(seed, with_data=False)
+    if name == "cfg3_ap":
+        return si.cfg3_append_prefill(seed, with_data=False)
+    raise SystemExit("unknown workload " + name)
+
+
+class Runner:
+    def __init__(self, b, torch, seed=0, options=None):
+        import paper_2603_13358_amd as ppd
+        import synthetic_inputs as si
+        self.torch, self.b = torch, b
+        self.dev = torch.device("cuda:0")
+        self.ctx = ppd.Context(b.Hq, b.Hkv, b.D, b.num_pages)
+        for k, v in (options or {}).items():
+            self.ctx.set_option(k, v)
+        self.w = si.device_workload(b, torch, self.dev, seed)
+        self.stream = torch.cuda.current_stream().cuda_stream
+
+    def step(self):
+        w, b = self.w, self.b
+        self.ctx.kv_append(w["k_new"], w["v_new"], w["pool"], w["slots"], stream=self.stream)
+        self.ctx.mixed_attention(w["q"], w["pool"], w["page_tables"], b.L, b.n, b.scale, w["out"], stream=self.stream)
+
+    def time_steps(self, steps, warmup):
+        torch = self.torch
+        for _ in range(warmup):
+            self.step()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(steps):
+            self.step()
+        torch.cuda.synchronize()
+        return (time.perf_counter() - t0) * 1e3 / steps
+
+    def kernel_ms(self, steps):
+        """Average duration of the mixed kernel alone (HIP events recorded by the library around its launch)."""
+        self.ctx.set_option("timing", 1)
+        tot = 0.0
+        for _ in range(steps):
+            self.step()
+            tot += self.ctx.last_kernel_ms()
+        self.ctx.set_option("timing", 0)
+        return tot / steps
+
+    def close(self):
+        self.ctx.close()
+        self.w = None
+        self.torch.cuda.empty_cache()
+
+
+def cpu_baseline(runner, budget_s=20.0):
+    """Times the oracle, as it stands, on a bounded sample of the workload and scales to one step."""
+    import oracle
+    import synthetic_inputs as si
+    b, torch = runner.b, runner.torch
+    runner.step()
+    torch.cuda.synchronize()
+    # sample: the shortest decode sequences first, then a slice of rows of one append-prefill
+    order = np.argsort(b.L.astype(np.int64) + b.n)
+    dec = [int(i) for i in order if b.n[i] == 1][:2]
+    ap = [int(i) for i in order if b.n[i] > 1][:1]
+    seqs = dec + ap
+    sub, pool, rows = si.compact_subbatch(b, seqs, runner.w["pool"], runner.w["q"], torch)
+    mask = np.zeros(sub.T, np.uint8)
+    mask[:len(dec)] = 1
+    ap_rows = 0
+    if ap:
+        ap_rows = int(min(4, b.n[ap[0]]))
+        mask[len(dec):len(dec) + ap_rows] = 1
+    pairs_sample = float(sum(int(b.L[i]) + 1 for i in dec))
+    if ap:
+        pairs_sample += sum(int(b.L[ap[0]]) + j + 1 for j in range(ap_rows))
+    cores = len(os.sched_getaffinity(0))
+    t0 = time.perf_counter()
+    ref = oracle.mixed_attention(sub.q, pool, sub.page_tables, sub.L, sub.n, sub.Hq, sub.Hkv, sub.D, sub.P,
+                                 sub.num_pages, sub.scale, row_mask=mask, threads=cores)
+    dt = time.perf_counter() - t0
+    pairs_total = float(np.sum(b.n.astype(np.float64) * b.L + b.n.astype(np.float64) * (b.n + 1) / 2))
+    est_step_us = dt * 1e6 * pairs_total / pairs_sample
+    # the same rows must agree with what the GPU just wrote
+    got = runner.w["out"].float().cpu().numpy()[rows]
+    sel = mask.astype(bool)
+    err = float(np.abs(got[sel] - ref[sel]).max())
+    return {"value": est_step_us, "unit": "us/step (extrapolated by visible (row,key) pairs)", "cores": cores,
+            "kind": "oracle", "sample": "%d decode rows + %d append-prefill rows, all heads: %.3g of %.3g (row,key) "
+            "pairs, %.2f s measured" % (len(dec), ap_rows, pairs_sample, pairs_total, dt),
+            "max_abs_err_vs_gpu": err}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--workload", default="cfg4_mixed_ap",
+                    choices=["cfg4_mixed_ap", "cfg4_mixed_full", "cfg4_decode_only", "cfg2_decode", "cfg3_ap"])
+    ap.add_argument("--seed", type=int, default=0)
+    ap.add_argument("--no-extras", action="store_true", help="time the chosen workload only")
+    ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle leg")
+    ap.add_argument("--opt", action="append", default=[], help="library option key=value (tuning sweeps)")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        raise SystemExit("bench.py measures one GPU: the step has no multi-GPU part in this build (--gpus 1 only)")
+    import torch
+    if not torch.cuda.is_available():
+        raise SystemExit("bench.py needs an MI355X: the library has no CPU path")
+    options = {kv.split("=")[0]: int(kv.split("=")[1]) for kv in args.opt}
+
+    def run(name, steps, warmup, want_cpu=False):
+        b = make_shapes(name, args.seed)
+        r = Runner(b, torch, args.seed, options)
+        ms = r.time_steps(steps, warmup)
+        kms = r.kernel_ms(max(3, min(steps, 10)))
+        st = r.ctx.plan_stats().as_dict()
+        res = {"workload": name, "ms_per_step": ms, "mixed_kernel_ms": kms, "plan": st,
+               "kv_bytes": b.kv_read_bytes(), "flops": b.attention_flops(), "rows": b.T, "sequences": b.B}
+        if want_cpu:
+            res["cpu"] = cpu_baseline(r)
+        r.close()
+        return res
+
+    main_res = run(args.workload, args.steps, args.warmup, want_cpu=not args.no_cpu)
+    b_bytes, b_flops = main_res["kv_bytes"], main_res["flops"]
+    t_hbm = b_bytes / (HBM_PEAK_GBS * 1e9)
+    t_mfma = b_flops / (MFMA_BF16_PEAK_TFLOPS * 1e12)
+    kernel_s = main_res["mixed_kernel_ms"] * 1e-3
+    if t_hbm >= t_mfma:
+        roofline = {"bound": "hbm", "achieved": b_bytes / kernel_s / 1e9, "peak": HBM_PEAK_GBS, "unit": "GB/s"}
+    else:
+        roofline = {"bound": "mfma", "achieved": b_flops / kernel_s / 1e12, "peak": MFMA_BF16_PEAK_TFLOPS,
+                    "unit": "TFLOP/s"}
+    roofline["frac"] = roofline["achieved"] / roofline["peak"]
+    roofline["traffic"] = None
+    roofline["kernel"] = "ppd_mixed_kernel<128>"
+    roofline["kernel_ms"] = main_res["mixed_kernel_ms"]
+
+    extras = {}
+    if not args.no_extras:
+        few, fw = max(5, args.steps // 2), 3
+        for name in ["cfg4_decode_only", "cfg4_mixed_full", "cfg2_decode", "cfg3_ap", "cfg4_mixed_ap"]:
+            if name == args.workload:
+                continue
+            steps = 3 if name == "cfg4_mixed_full" else few
+            r = run(name, steps, 2 if name == "cfg4_mixed_full" else fw)
+            ks = r["mixed_kernel_ms"] * 1e-3
+            extras[name] = {"us_per_step": r["ms_per_step"] * 1e3, "mixed_kernel_us": r["mixed_kernel_ms"] * 1e3,
+                            "hbm_GBs": r["kv_bytes"] / ks / 1e9, "hbm_frac": r["kv_bytes"] / ks / 1e9 / HBM_PEAK_GBS,
+                            "mfma_TFLOPs": r["flops"] / ks / 1e12,
+                            "mfma_frac": r["flops"] / ks / 1e12 / MFMA_BF16_PEAK_TFLOPS,
+                            "tiles": r["plan"]["n_items"]}
+        extras[args.workload] = {"us_per_step": main_res["ms_per_step"] * 1e3,
+                                 "mixed_kernel_us": main_res["mixed_kernel_ms"] * 1e3}
+        if "cfg4_decode_only" in extras and "cfg4_mixed_ap" in extras and "cfg4_mixed_full" in extras:
+            base = extras["cfg4_decode_only"]["us_per_step"]
+            extras["decode_step_slowdown"] = {
+                "with_append_prefill": extras["cfg4_mixed_ap"]["us_per_step"] / base - 1.0,
+                "with_full_prefill_of_equal_context": extras["cfg4_mixed_full"]["us_per_step"] / base - 1.0,
+                "paper_context": "whole-model vLLM on 1xH100, Llama-3.1-8B, batch 200, one 1024-token prefill: "
+                                 "+2% append vs +48% full (section 4.1)"}
+
+    line = {
+        "metric": "mixed AP+decode paged-attn step us; decode HBM TB/s & AP MFMA util vs peak",
+        "value": main_res["ms_per_step"] * 1e3, "unit": "us/step", "n_gpus": 1, "steps": args.steps,
+        "warmup": args.warmup, "ms_per_step": main_res["ms_per_step"], "higher_is_better": False,
+        "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": args.workload, "sequences": main_res["sequences"], "new_token_rows": main_res["rows"],
+                   "heads": "32q/8kv", "head_dim": 128, "page_size": 16, "seed": args.seed,
+                   "kv_bytes_per_step": b_bytes, "attention_flops_per_step": b_flops,
+                   "tiles": main_res["plan"]["n_items"], "grid": main_res["plan"]["grid"]},
+        "roofline": roofline,
+        "cpu_baseline": main_res.get("cpu"),
+        "extras": extras,
+    }
+    print(json.dumps(line))
+
+
+if __name__ == "__main__":
+    main()

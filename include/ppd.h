@@ -106,7 +106,8 @@ const char *ppd_last_error(const ppd_ctx *ctx);
 
 /* Tuning knobs (all optional).  key: "narrow_chunk", "mfma_chunk" (tokens, multiple of 64, 0 = automatic),
  * "grid" (workgroups, 0 = automatic), "force_kind" (-1 automatic, 1 = route every sequence through the
- * MFMA row-block path; used to test that n = 1 append-prefill equals decode). */
+ * MFMA row-block path; used to test that n = 1 append-prefill equals decode), "timing" (1 = record HIP
+ * events on the call's stream right before and after the mixed-attention kernel, see ppd_last_kernel_ms). */
 ppd_status ppd_set_option(ppd_ctx *ctx, const char *key, int64_t value);
 
 /* Paged KV append (the KV-cache write of the step; paper sections 2.1 and 4.1: prefill populates the
@@ -150,6 +151,11 @@ ppd_status ppd_plan_build(const ppd_shape *shape, const int32_t *L, const int32_
 /* Synchronises `stream`, then returns and clears the sticky device error flags (bit 0: append slot out of
  * range, bit 1: page id out of range) in *flags. */
 ppd_status ppd_device_error_flags(ppd_ctx *ctx, void *stream, uint32_t *flags);
+
+/* With option "timing" set: waits for the mixed-attention kernel of the last ppd_mixed_attention call and
+ * returns its duration in milliseconds (HIP events on the stream it was launched on; the plan upload and
+ * the merge kernel are outside the bracket). */
+ppd_status ppd_last_kernel_ms(ppd_ctx *ctx, float *ms);
 
 /* Library version, "major.minor". */
 const char *ppd_version(void);

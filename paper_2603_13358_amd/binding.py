@@ -40,7 +40,7 @@ class PlanStats(ctypes.Structure):
 
 
 EXPORTS = ["ppd_create", "ppd_destroy", "ppd_last_error", "ppd_set_option", "ppd_kv_append", "ppd_mixed_attention",
-           "ppd_get_plan_stats", "ppd_plan_build", "ppd_device_error_flags", "ppd_version"]
+           "ppd_get_plan_stats", "ppd_plan_build", "ppd_device_error_flags", "ppd_last_kernel_ms", "ppd_version"]
 
 
 def lib_path():
@@ -68,6 +68,7 @@ def load_library():
     lib.ppd_plan_build.argtypes = [ctypes.POINTER(Shape), vp, vp, i32, i32, i32, i32, i32, i32,
                                    ctypes.POINTER(WorkItem), i64, ctypes.POINTER(PlanStats)]
     lib.ppd_device_error_flags.argtypes = [vp, vp, ctypes.POINTER(ctypes.c_uint32)]
+    lib.ppd_last_kernel_ms.argtypes = [vp, ctypes.POINTER(ctypes.c_float)]
     lib.ppd_version.argtypes = []
     lib.ppd_version.restype = ctypes.c_char_p
     for name in EXPORTS:
@@ -147,6 +148,12 @@ def ppd_device_error_flags(ctx, stream=None):
     return int(flags.value)
 
 
+def ppd_last_kernel_ms(ctx):
+    ms = ctypes.c_float(0)
+    _check(load_library().ppd_last_kernel_ms(ctx, ctypes.byref(ms)), ctx)
+    return float(ms.value)
+
+
 def ppd_plan_build(num_q_heads, num_kv_heads, head_dim, page_size, num_pages, L, n, narrow_chunk=0, mfma_chunk=0,
                    grid=0, force_kind=-1, num_cus=256):
     """Host-only planner.  Returns (list of WorkItem, PlanStats)."""
@@ -189,6 +196,9 @@ class Context:
 
     def plan_stats(self):
         return ppd_get_plan_stats(self.handle)
+
+    def last_kernel_ms(self):
+        return ppd_last_kernel_ms(self.handle)
 
     def device_error_flags(self, stream=None):
         return ppd_device_error_flags(self.handle, stream)

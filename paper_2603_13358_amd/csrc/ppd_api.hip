@@ -38,6 +38,10 @@ struct ppd_ctx {
     uint32_t* d_counters = nullptr;  // cursor, finished, error flags (+ padding)
     Staging staging[kStagingSlots];
     int next_slot = 0;
+    // optional timing of the mixed kernel alone (option "timing")
+    bool timing = false;
+    bool timed = false;
+    hipEvent_t ev_begin = nullptr, ev_end = nullptr;
 };
 
 namespace {
@@ -123,6 +127,8 @@ ppd_status ppd_create(const ppd_shape* shape, int32_t device, ppd_ctx** out) {
     if ((e = hipMemset(ctx->d_counters, 0, 64)) != hipSuccess) return bail(e, "hipMemset(counters)");
     for (auto& s : ctx->staging)
         if ((e = hipEventCreateWithFlags(&s.done, hipEventDisableTiming)) != hipSuccess) return bail(e, "hipEventCreate");
+    if ((e = hipEventCreate(&ctx->ev_begin)) != hipSuccess) return bail(e, "hipEventCreate");
+    if ((e = hipEventCreate(&ctx->ev_end)) != hipSuccess) return bail(e, "hipEventCreate");
     *out = ctx;
     return PPD_OK;
 }
@@ -138,6 +144,8 @@ ppd_status ppd_destroy(ppd_ctx* ctx) {
         if (s.host) (void)hipHostFree(s.host);
         if (s.done) (void)hipEventDestroy(s.done);
     }
+    if (ctx->ev_begin) (void)hipEventDestroy(ctx->ev_begin);
+    if (ctx->ev_end) (void)hipEventDestroy(ctx->ev_end);
     delete ctx;
     return PPD_OK;
 }
@@ -155,6 +163,9 @@ ppd_status ppd_set_option(ppd_ctx* ctx, const char* key, int64_t value) {
     } else if (k == "force_kind") {
         if (value != -1 && value != 1) return fail(ctx, PPD_ERR_RANGE, "force_kind must be -1 or 1");
         ctx->opts.force_kind = (int32_t)value;
+    } else if (k == "timing") {
+        ctx->timing = value != 0;
+        ctx->timed = false;
     } else {
         return fail(ctx, PPD_ERR_RANGE, "unknown option " + k);
     }
@@ -262,8 +273,13 @@ ppd_status ppd_mixed_attention(ppd_ctx* ctx, const void* q, const void* kv_pages
     kp.G = G;
     kp.lgG = ilog2(G);
     kp.scale_log2e = scale_log2e;
+    if (ctx->timing) PPD_HIP(ctx, hipEventRecord(ctx->ev_begin, hs));
     int rc = ppd::launch_mixed(kp, ctx->shape.head_dim, plan.stats.grid, stream);
     if (rc != 0) return hip_fail(ctx, (hipError_t)rc, "launch mixed attention");
+    if (ctx->timing) {
+        PPD_HIP(ctx, hipEventRecord(ctx->ev_end, hs));
+        ctx->timed = true;
+    }
     if (!plan.groups.empty()) {
         ppd::MergeParams mp;
         mp.groups = reinterpret_cast<const ppd::MergeGroup*>(static_cast<const char*>(ctx->d_items) + items_bytes);
@@ -284,6 +300,15 @@ ppd_status ppd_mixed_attention(ppd_ctx* ctx, const void* q, const void* kv_pages
 ppd_status ppd_get_plan_stats(const ppd_ctx* ctx, ppd_plan_stats* stats) {
     if (!ctx || !stats) return PPD_ERR_NULL;
     *stats = ctx->plan.stats;
+    return PPD_OK;
+}
+
+ppd_status ppd_last_kernel_ms(ppd_ctx* ctx, float* ms) {
+    if (!ctx || !ms) return fail(ctx, PPD_ERR_NULL, "ctx / ms is NULL");
+    if (!ctx->timed) return fail(ctx, PPD_ERR_RANGE, "no timed launch: set option \"timing\" to 1 and run a step");
+    PPD_HIP(ctx, hipSetDevice(ctx->device));
+    PPD_HIP(ctx, hipEventSynchronize(ctx->ev_end));
+    PPD_HIP(ctx, hipEventElapsedTime(ms, ctx->ev_begin, ctx->ev_end));
     return PPD_OK;
 }
 

@@ -257,3 +257,57 @@ def cfg5_trace(seed=0, n_conv=256, turns=5, prompt_mean=200.0, response_mean=300
         step += 1
     max_tokens = (prompts.sum(1) + resps.sum(1)).astype(np.int64)
     return steps, max_tokens
+
+
+# ---------------------------------------------------------------------------------------------------
+# Full-size workloads: the data is drawn on the GPU (torch is used for device memory only).  The pool is
+# filled with iid N(0,1) bf16 in place -- iid values are iid in any layout, so no layout arithmetic is
+# needed here -- and the new tokens' K/V go in through the library's own append.
+# ---------------------------------------------------------------------------------------------------
+
+def new_token_slots(b):
+    return b.new_part()[2]
+
+
+def device_workload(b, torch, device, seed=0):
+    """Device tensors of a shapes-only batch b (made with with_data=False)."""
+    gen = torch.Generator(device=device)
+    gen.manual_seed(10_000 + seed)
+    page_elems = 2 * b.Hkv * b.P * b.D
+    pool = torch.empty((b.num_pages * page_elems,), dtype=torch.bfloat16, device=device)
+    step = 1 << 28
+    for a in range(0, pool.numel(), step):
+        pool[a:a + step].normal_(generator=gen)
+    q = torch.empty((b.T, b.Hq, b.D), dtype=torch.bfloat16, device=device).normal_(generator=gen)
+    k_new = torch.empty((b.T, b.Hkv, b.D), dtype=torch.bfloat16, device=device).normal_(generator=gen)
+    v_new = torch.empty((b.T, b.Hkv, b.D), dtype=torch.bfloat16, device=device).normal_(generator=gen)
+    return dict(pool=pool, q=q, k_new=k_new, v_new=v_new,
+                slots=torch.from_numpy(new_token_slots(b)).to(device),
+                page_tables=torch.from_numpy(b.page_tables).to(device),
+                out=torch.zeros((b.T, b.Hq, b.D), dtype=torch.bfloat16, device=device))
+
+
+def compact_subbatch(b, seq_ids, pool_dev, q_dev, torch):
+    """Host copy of the pages of the sequences seq_ids only, with page ids renumbered 0..k-1, as a
+    MixedBatch carrying q but no dense K/V (the pool bytes are the data).  Returns (sub_batch, pool_u16)."""
+    seq_ids = [int(s) for s in seq_ids]
+    page_elems = 2 * b.Hkv * b.P * b.D
+    pts, pages = [], []
+    at = 0
+    need = (b.L.astype(np.int64) + b.n + b.P - 1) // b.P
+    for s in seq_ids:
+        c = int(need[s])
+        pages.append(b.page_tables[s, :c].astype(np.int64))
+        pts.append(np.arange(at, at + c, dtype=np.int32))
+        at += c
+    maxp = max(len(p) for p in pts)
+    pt = np.full((len(seq_ids), maxp), -1, np.int32)
+    for i, p in enumerate(pts):
+        pt[i, :len(p)] = p
+    idx = torch.from_numpy(np.concatenate(pages)).to(pool_dev.device)
+    sub_pool = pool_dev.view(torch.int16).view(b.num_pages, page_elems).index_select(0, idx).cpu().numpy()
+    rows = np.concatenate([np.arange(b.row_off[s], b.row_off[s + 1]) for s in seq_ids])
+    q = q_dev.view(torch.int16)[torch.from_numpy(rows).to(q_dev.device)].cpu().numpy().view(np.uint16)
+    sub = MixedBatch(name=b.name + "_sub", Hq=b.Hq, Hkv=b.Hkv, D=b.D, P=b.P, num_pages=at, scale=b.scale,
+                     L=b.L[seq_ids], n=b.n[seq_ids], page_tables=pt, q=q)
+    return sub, sub_pool.view(np.uint16).reshape(-1), rows
