@@ -86,42 +86,59 @@ class Runner:
         self.torch.cuda.empty_cache()
 
 
-def cpu_baseline(runner, budget_s=20.0):
-    """Times the oracle, as it stands, on a bounded sample of the workload and scales to one step."""
+def cpu_baseline(runner, budget_s=15.0):
+    """Times the oracle, as it stands, on a bounded sample of the workload and scales to one step.
+
+    The sample is whole decode sequences (shortest first) plus the first rows of one append-prefill, sized
+    from a short calibration run so that the measured part takes about budget_s seconds."""
     import oracle
     import synthetic_inputs as si
     b, torch = runner.b, runner.torch
     runner.step()
     torch.cuda.synchronize()
-    # sample: the shortest decode sequences first, then a slice of rows of one append-prefill
-    order = np.argsort(b.L.astype(np.int64) + b.n)
-    dec = [int(i) for i in order if b.n[i] == 1][:2]
-    ap = [int(i) for i in order if b.n[i] > 1][:1]
-    seqs = dec + ap
-    sub, pool, rows = si.compact_subbatch(b, seqs, runner.w["pool"], runner.w["q"], torch)
-    mask = np.zeros(sub.T, np.uint8)
-    mask[:len(dec)] = 1
-    ap_rows = 0
-    if ap:
-        ap_rows = int(min(4, b.n[ap[0]]))
-        mask[len(dec):len(dec) + ap_rows] = 1
-    pairs_sample = float(sum(int(b.L[i]) + 1 for i in dec))
-    if ap:
-        pairs_sample += sum(int(b.L[ap[0]]) + j + 1 for j in range(ap_rows))
     cores = len(os.sched_getaffinity(0))
-    t0 = time.perf_counter()
-    ref = oracle.mixed_attention(sub.q, pool, sub.page_tables, sub.L, sub.n, sub.Hq, sub.Hkv, sub.D, sub.P,
-                                 sub.num_pages, sub.scale, row_mask=mask, threads=cores)
-    dt = time.perf_counter() - t0
+    order = np.argsort(b.L.astype(np.int64) + b.n)
+    dec_all = [int(i) for i in order if b.n[i] == 1]
+    ap_all = [int(i) for i in order if b.n[i] > 1]
+
+    def run_sample(n_dec, n_ap_rows):
+        dec = dec_all[:n_dec]
+        ap = ap_all[:1] if n_ap_rows > 0 else []
+        seqs = dec + ap
+        sub, pool, rows = si.compact_subbatch(b, seqs, runner.w["pool"], runner.w["q"], torch)
+        mask = np.zeros(sub.T, np.uint8)
+        mask[:len(dec)] = 1
+        ap_rows = int(min(n_ap_rows, b.n[ap[0]])) if ap else 0
+        mask[len(dec):len(dec) + ap_rows] = 1
+        pairs = float(sum(int(b.L[i]) + 1 for i in dec))
+        if ap:
+            pairs += sum(int(b.L[ap[0]]) + j + 1 for j in range(ap_rows))
+        t0 = time.perf_counter()
+        ref = oracle.mixed_attention(sub.q, pool, sub.page_tables, sub.L, sub.n, sub.Hq, sub.Hkv, sub.D, sub.P,
+                                     sub.num_pages, sub.scale, row_mask=mask, threads=cores)
+        dt = time.perf_counter() - t0
+        got = runner.w["out"].float().cpu().numpy()[rows]
+        sel = mask.astype(bool)
+        err = float(np.abs(got[sel] - ref[sel]).max()) if sel.any() else 0.0
+        return dt, pairs, len(dec), ap_rows, err
+
+    dt, pairs, _, _, _ = run_sample(min(2, len(dec_all)), 4 if ap_all else 0)
+    rate = pairs / max(dt, 1e-6)                       # (row, key) pairs per second, all heads
+    want = rate * budget_s
+    n_dec, acc = 0, 0.0
+    while n_dec < len(dec_all) and acc < want / (2 if ap_all else 1):
+        acc += int(b.L[dec_all[n_dec]]) + 1
+        n_dec += 1
+    n_ap_rows = 0
+    if ap_all:
+        per_row = int(b.L[ap_all[0]]) + 1
+        n_ap_rows = int(max(4, min(b.n[ap_all[0]], (want - acc) / per_row)))
+    dt, pairs, nd, nr, err = run_sample(n_dec, n_ap_rows)
     pairs_total = float(np.sum(b.n.astype(np.float64) * b.L + b.n.astype(np.float64) * (b.n + 1) / 2))
-    est_step_us = dt * 1e6 * pairs_total / pairs_sample
-    # the same rows must agree with what the GPU just wrote
-    got = runner.w["out"].float().cpu().numpy()[rows]
-    sel = mask.astype(bool)
-    err = float(np.abs(got[sel] - ref[sel]).max())
-    return {"value": est_step_us, "unit": "us/step (extrapolated by visible (row,key) pairs)", "cores": cores,
-            "kind": "oracle", "sample": "%d decode rows + %d append-prefill rows, all heads: %.3g of %.3g (row,key) "
-            "pairs, %.2f s measured" % (len(dec), ap_rows, pairs_sample, pairs_total, dt),
+    return {"value": dt * 1e6 * pairs_total / pairs, "unit": "us/step (extrapolated by visible (row,key) pairs)",
+            "cores": cores, "kind": "oracle",
+            "sample": "%d whole decode sequences + first %d rows of one append-prefill, all heads: %.3g of %.3g "
+                      "(row,key) pairs, %.2f s measured" % (nd, nr, pairs, pairs_total, dt),
             "max_abs_err_vs_gpu": err}
 
 

@@ -40,7 +40,8 @@ class PlanStats(ctypes.Structure):
 
 
 EXPORTS = ["ppd_create", "ppd_destroy", "ppd_last_error", "ppd_set_option", "ppd_kv_append", "ppd_mixed_attention",
-           "ppd_get_plan_stats", "ppd_plan_build", "ppd_device_error_flags", "ppd_last_kernel_ms", "ppd_version"]
+           "ppd_get_plan_stats", "ppd_plan_build", "ppd_device_error_flags", "ppd_last_kernel_ms", "ppd_debug_counters",
+           "ppd_version"]
 
 
 def lib_path():
@@ -69,6 +70,7 @@ def load_library():
                                    ctypes.POINTER(WorkItem), i64, ctypes.POINTER(PlanStats)]
     lib.ppd_device_error_flags.argtypes = [vp, vp, ctypes.POINTER(ctypes.c_uint32)]
     lib.ppd_last_kernel_ms.argtypes = [vp, ctypes.POINTER(ctypes.c_float)]
+    lib.ppd_debug_counters.argtypes = [vp, vp, ctypes.POINTER(ctypes.c_uint32), i32]
     lib.ppd_version.argtypes = []
     lib.ppd_version.restype = ctypes.c_char_p
     for name in EXPORTS:
@@ -152,6 +154,12 @@ def ppd_last_kernel_ms(ctx):
     ms = ctypes.c_float(0)
     _check(load_library().ppd_last_kernel_ms(ctx, ctypes.byref(ms)), ctx)
     return float(ms.value)
+
+
+def ppd_debug_counters(ctx, stream=None, clear=False):
+    buf = (ctypes.c_uint32 * 16)()
+    _check(load_library().ppd_debug_counters(ctx, stream, buf, 1 if clear else 0), ctx)
+    return [int(x) for x in buf]
 
 
 def ppd_plan_build(num_q_heads, num_kv_heads, head_dim, page_size, num_pages, L, n, narrow_chunk=0, mfma_chunk=0,

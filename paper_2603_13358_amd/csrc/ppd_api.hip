@@ -163,6 +163,9 @@ ppd_status ppd_set_option(ppd_ctx* ctx, const char* key, int64_t value) {
     } else if (k == "force_kind") {
         if (value != -1 && value != 1) return fail(ctx, PPD_ERR_RANGE, "force_kind must be -1 or 1");
         ctx->opts.force_kind = (int32_t)value;
+    } else if (k == "pref_mode") {
+        if (value < 0 || value > 3) return fail(ctx, PPD_ERR_RANGE, "pref_mode must be in [0, 3]");
+        ctx->opts.pref_mode = (int32_t)value;
     } else if (k == "timing") {
         ctx->timing = value != 0;
         ctx->timed = false;
@@ -194,6 +197,7 @@ ppd_status ppd_mixed_attention(ppd_ctx* ctx, const void* q, const void* kv_pages
     if (B == 0) {
         ctx->plan.items.clear();
         ctx->plan.groups.clear();
+        ctx->plan.units.clear();
         std::memset(&ctx->plan.stats, 0, sizeof ctx->plan.stats);
         return PPD_OK;
     }
@@ -216,7 +220,8 @@ ppd_status ppd_mixed_attention(ppd_ctx* ctx, const void* q, const void* kv_pages
     const ppd::Plan& plan = ctx->plan;
     const size_t items_bytes = plan.items.size() * sizeof(ppd_work_item);
     const size_t groups_bytes = plan.groups.size() * sizeof(ppd::MergeGroup);
-    const size_t total = items_bytes + groups_bytes;
+    const size_t units_bytes = plan.units.size() * sizeof(ppd::MergeUnit);
+    const size_t total = items_bytes + groups_bytes + units_bytes;
     Staging& sg = ctx->staging[ctx->next_slot];
     ctx->next_slot = (ctx->next_slot + 1) % kStagingSlots;
     if (sg.in_flight) {
@@ -246,7 +251,10 @@ ppd_status ppd_mixed_attention(ppd_ctx* ctx, const void* q, const void* kv_pages
         if (st != PPD_OK) return st;
     }
     std::memcpy(sg.host, plan.items.data(), items_bytes);
-    if (groups_bytes) std::memcpy(static_cast<char*>(sg.host) + items_bytes, plan.groups.data(), groups_bytes);
+    if (groups_bytes) {
+        std::memcpy(static_cast<char*>(sg.host) + items_bytes, plan.groups.data(), groups_bytes);
+        std::memcpy(static_cast<char*>(sg.host) + items_bytes + groups_bytes, plan.units.data(), units_bytes);
+    }
     PPD_HIP(ctx, hipMemcpyAsync(ctx->d_items, sg.host, total, hipMemcpyHostToDevice, hs));
     PPD_HIP(ctx, hipEventRecord(sg.done, hs));
     sg.in_flight = true;
@@ -267,6 +275,8 @@ ppd_status ppd_mixed_attention(ppd_ctx* ctx, const void* q, const void* kv_pages
     kp.num_pages = ctx->shape.num_pages;
     kp.page_stride = 2LL * ctx->shape.num_kv_heads * ppd::kPage * ctx->shape.head_dim;
     kp.n_items = (int32_t)plan.items.size();
+    kp.n_mfma = (int32_t)plan.stats.n_mfma;
+    kp.pref_mode = ctx->opts.pref_mode;
     kp.max_pages = max_pages;
     kp.Hq = ctx->shape.num_q_heads;
     kp.Hkv = ctx->shape.num_kv_heads;
@@ -286,6 +296,9 @@ ppd_status ppd_mixed_attention(ppd_ctx* ctx, const void* q, const void* kv_pages
         mp.partials = ctx->d_partials;
         mp.out = static_cast<uint16_t*>(out);
         mp.n_groups = (int32_t)plan.groups.size();
+        mp.units = reinterpret_cast<const ppd::MergeUnit*>(static_cast<const char*>(ctx->d_items) + items_bytes +
+                                                          groups_bytes);
+        mp.n_units = (int32_t)plan.units.size();
         mp.Hq = kp.Hq;
         mp.G = G;
         mp.lgG = kp.lgG;
@@ -309,6 +322,16 @@ ppd_status ppd_last_kernel_ms(ppd_ctx* ctx, float* ms) {
     PPD_HIP(ctx, hipSetDevice(ctx->device));
     PPD_HIP(ctx, hipEventSynchronize(ctx->ev_end));
     PPD_HIP(ctx, hipEventElapsedTime(ms, ctx->ev_begin, ctx->ev_end));
+    return PPD_OK;
+}
+
+ppd_status ppd_debug_counters(ppd_ctx* ctx, void* stream, uint32_t* out16, int32_t clear) {
+    if (!ctx || !out16) return fail(ctx, PPD_ERR_NULL, "ctx / out16 is NULL");
+    hipStream_t hs = static_cast<hipStream_t>(stream);
+    PPD_HIP(ctx, hipSetDevice(ctx->device));
+    PPD_HIP(ctx, hipStreamSynchronize(hs));
+    PPD_HIP(ctx, hipMemcpy(out16, ctx->d_counters, 64, hipMemcpyDeviceToHost));
+    if (clear) PPD_HIP(ctx, hipMemset(ctx->d_counters + 4, 0, 48));
     return PPD_OK;
 }
 

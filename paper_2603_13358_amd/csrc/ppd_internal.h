@@ -24,9 +24,16 @@ struct MergeGroup {
     int64_t part_stride;  // floats per split = cols * (D + 2)
 };
 
+// One workgroup of the merge kernel: 4 consecutive columns of a group (one wave each).
+struct MergeUnit {
+    int32_t group;
+    int32_t col0;
+};
+
 struct Plan {
     std::vector<ppd_work_item> items;
     std::vector<MergeGroup> groups;
+    std::vector<MergeUnit> units;
     ppd_plan_stats stats;
 };
 
@@ -36,6 +43,7 @@ struct PlanOptions {
     int32_t grid = 0;
     int32_t force_kind = -1;
     int32_t num_cus = 256;
+    int32_t pref_mode = 2;
 };
 
 // Returns PPD_OK or an error code with a message in `err` (may be null).
@@ -51,10 +59,12 @@ struct KParams {
     const int32_t* page_tables;
     const ppd_work_item* items;
     float* partials;
-    uint32_t* counters;   // [0] work cursor, [1] finished workgroups, [2] sticky error flags
+    uint32_t* counters;   // [0] MFMA-queue cursor, [1] narrow-queue cursor, [2] sticky error flags, [3] finished workgroups
     int64_t num_pages;
     int64_t page_stride;  // elements per page = 2 * Hkv * 16 * D
     int32_t n_items;
+    int32_t n_mfma;       // items [0, n_mfma) are MFMA row-block tiles, the rest narrow tiles
+    int32_t pref_mode;    // how a workgroup picks its preferred queue (see ppd_mixed_kernel)
     int32_t max_pages;
     int32_t Hq, Hkv, G, lgG;
     float scale_log2e;
@@ -62,6 +72,8 @@ struct KParams {
 
 struct MergeParams {
     const MergeGroup* groups;
+    const MergeUnit* units;
+    int32_t n_units;
     const float* partials;
     uint16_t* out;
     int32_t n_groups;

@@ -23,6 +23,28 @@ typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 
 #define NEG_INF (-__builtin_inff())
 
+// Optional phase timing of the MFMA tile loop (build with -DPPD_PHASE_TIMING): shader-clock cycles of wave 0
+// of every workgroup, summed per phase into counters[4..15] as six 64-bit sums.  Off in the product build.
+#ifdef PPD_PHASE_TIMING
+#define PPD_TICK_DECL() long long tick_last_ = clock64(); long long tick_sum_[6] = {0, 0, 0, 0, 0, 0}
+#define PPD_TICK(k)                              \
+    do {                                         \
+        const long long now_ = clock64();        \
+        tick_sum_[k] += now_ - tick_last_;       \
+        tick_last_ = now_;                       \
+    } while (0)
+#define PPD_TICK_FLUSH(P)                                                                                  \
+    do {                                                                                                   \
+        if (threadIdx.x == 0)                                                                              \
+            for (int k_ = 0; k_ < 6; ++k_)                                                                 \
+                atomicAdd(reinterpret_cast<unsigned long long*>((P).counters + 4) + k_, (unsigned long long)tick_sum_[k_]); \
+    } while (0)
+#else
+#define PPD_TICK_DECL() do {} while (0)
+#define PPD_TICK(k) do {} while (0)
+#define PPD_TICK_FLUSH(P) do {} while (0)
+#endif
+
 __device__ __forceinline__ uint32_t pack_bf16(float a, float b) {
     f32x2 f = {a, b};
     bf16x2 r = __builtin_convertvector(f, bf16x2);  // round to nearest even
@@ -35,10 +57,25 @@ __device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_ex
 
 __device__ __forceinline__ float xor_shuffle(float v, int mask) { return __shfl_xor(v, mask, 64); }
 
-// Page id of logical page `pi` of a sequence, clamped so that no access leaves the page table row or the pool.
-__device__ __forceinline__ int64_t fetch_page(const KParams& P, const int32_t* pt_row, int pi, int last_page) {
+// Raw page-table entry of logical page `pi` of a sequence; pi is clamped so that no access leaves the page
+// table row.  The value is NOT inspected here: a caller that prefetches it must not wait for the load.
+__device__ __forceinline__ int load_page_id(const int32_t* pt_row, int pi, int last_page) {
     pi = pi < last_page ? pi : last_page;
-    int64_t page = pt_row[pi];
+    return pt_row[pi];
+}
+
+// Same for a wave-uniform pi: the page table is not written while the kernel runs, so it is read through the
+// constant address space, which lets a uniform address become a scalar load that nobody has to wait for
+// until the value is used.
+typedef const int32_t __attribute__((address_space(4))) * const_i32_ptr;
+__device__ __forceinline__ int load_page_id_uniform(const int32_t* pt_row, int pi, int last_page) {
+    pi = pi < last_page ? pi : last_page;
+    return reinterpret_cast<const_i32_ptr>(reinterpret_cast<uintptr_t>(pt_row))[pi];
+}
+
+// Checks a page id at the point of use: an id outside the pool raises the sticky flag and is replaced by
+// page 0, so that no access leaves the pool.
+__device__ __forceinline__ int64_t checked_page(const KParams& P, int page) {
     if (page < 0 || page >= P.num_pages) {
         atomicOr(&P.counters[2], 2u);
         page = 0;
@@ -99,15 +136,14 @@ __device__ __forceinline__ void mfma_item(const KParams& P, const ppd_work_item&
     const int64_t head_off = (int64_t)it.kvh * (kPage * HD);
     const int64_t v_off = (int64_t)P.Hkv * (kPage * HD);
 
-    // staging assignment: granule gid = r*256 + tid of the tile's 4 page blocks
-    int64_t pages_next[ROUNDS];
+    // staging assignment: granule gid = r*256 + tid of the tile's 4 page blocks.  The page a thread reads in
+    // round r is the same for its whole wave (s = r at HD = 128, s = 2r + wave/2 at HD = 64), so the ids are
+    // wave-uniform scalar loads, prefetched one tile ahead of the loads that use them.
+    int pages_next[4];
     u32x4 kst[ROUNDS], vst[ROUNDS];
     auto fetch_pages = [&](int ti) {
 #pragma unroll
-        for (int r = 0; r < ROUNDS; ++r) {
-            const int s = (r * kThreads + tid) / GPP;
-            pages_next[r] = fetch_page(P, pt_row, first_page + ti * 4 + s, last_page);
-        }
+        for (int s = 0; s < 4; ++s) pages_next[s] = load_page_id_uniform(pt_row, first_page + ti * 4 + s, last_page);
     };
     auto issue_loads = [&](int ti) {
         const int tile_base = it.kv_begin + ti * kTileTokens;
@@ -115,7 +151,12 @@ __device__ __forceinline__ void mfma_item(const KParams& P, const ppd_work_item&
         for (int r = 0; r < ROUNDS; ++r) {
             const int gid = r * kThreads + tid;
             const int within = gid % GPP;
-            const uint16_t* src = P.pool + pages_next[r] * P.page_stride + head_off + within * 8;
+            int page;
+            if (ROUNDS == 4)
+                page = pages_next[r];
+            else
+                page = (wave >> 1) ? pages_next[2 * r + 1] : pages_next[2 * r];
+            const uint16_t* src = P.pool + checked_page(P, page) * P.page_stride + head_off + within * 8;
             kst[r] = *reinterpret_cast<const u32x4*>(src);
             vst[r] = *reinterpret_cast<const u32x4*>(src + v_off);
         }
@@ -159,12 +200,14 @@ __device__ __forceinline__ void mfma_item(const KParams& P, const ppd_work_item&
     store_stage(0);
     __syncthreads();
 
+    PPD_TICK_DECL();
     for (int ti = 0; ti < ntiles; ++ti) {
         const int buf = ti & 1;
         if (ti + 1 < ntiles) {
             issue_loads(ti + 1);
             if (ti + 2 < ntiles) fetch_pages(ti + 2);
         }
+        PPD_TICK(0);
         if (wave_active) {
             const char* kb = smem + buf * STAGE + k_lane_off;
             const char* vb = smem + buf * STAGE + KBYTES + v_lane_off;
@@ -180,6 +223,7 @@ __device__ __forceinline__ void mfma_item(const KParams& P, const ppd_work_item&
                     bf16x8 a = as_bf16x8(*reinterpret_cast<const u32x4*>(kb + tb * 2 * PB + ks * 512));
                     sacc[tb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, qreg[ks], sacc[tb], 0, 0, 0);
                 }
+            PPD_TICK(1);
             const int tile_base = it.kv_begin + ti * kTileTokens;
             if (tile_base + kTileTokens - 1 > wmin_limit) {  // causal boundary crosses this tile
 #pragma unroll
@@ -208,6 +252,7 @@ __device__ __forceinline__ void mfma_item(const KParams& P, const ppd_work_item&
                     for (int i = 0; i < 16; ++i) oacc[db][i] *= alpha;
                 m_run = m_new;
             }
+            PPD_TICK(2);
             float psum = 0.f;
 #pragma unroll
             for (int tb = 0; tb < 2; ++tb)
@@ -232,9 +277,13 @@ __device__ __forceinline__ void mfma_item(const KParams& P, const ppd_work_item&
                 }
             }
         }
+        PPD_TICK(3);
         if (ti + 1 < ntiles) store_stage(buf ^ 1);
+        PPD_TICK(4);
         __syncthreads();
+        PPD_TICK(5);
     }
+    PPD_TICK_FLUSH(P);
 
     // epilogue: O^T register i of block db is d = db*32 + (i/4)*8 + h*4 + i%4 of column `col`
     const float l_tot = l_run + xor_shuffle(l_run, 32);
@@ -322,9 +371,7 @@ __device__ __forceinline__ void narrow_item(const KParams& P, const ppd_work_ite
 
     // lane i of `ids` holds the page of logical page (batch*64 + i) of this wave's range
     int ids_cur = 0, ids_nxt = 0;
-    auto load_ids = [&](int batch) {
-        return (int)fetch_page(P, pt_row, wave_first_page + batch * 64 + lane, last_page);
-    };
+    auto load_ids = [&](int batch) { return load_page_id(pt_row, wave_first_page + batch * 64 + lane, last_page); };
     struct StepRegs {
         u32x4 k[2][KS];  // K operand of the step's two pages
         u32x4 v[DBN];    // V^T operand, one per 16-row d block
@@ -337,8 +384,8 @@ __device__ __forceinline__ void narrow_item(const KParams& P, const ppd_work_ite
             if (k + 32 < my_steps) ids_nxt = load_ids(k / 32 + 1);
         }
         const int li = (2 * k) & 63;
-        const int64_t pa = __builtin_amdgcn_readlane(ids_cur, li);
-        const int64_t pb = __builtin_amdgcn_readlane(ids_cur, li + 1);
+        const int64_t pa = checked_page(P, __builtin_amdgcn_readlane(ids_cur, li));
+        const int64_t pb = checked_page(P, __builtin_amdgcn_readlane(ids_cur, li + 1));
         const uint16_t* ka = P.pool + pa * P.page_stride + head_off;
         const uint16_t* kb = P.pool + pb * P.page_stride + head_off;
 #pragma unroll
@@ -476,12 +523,38 @@ __global__ __launch_bounds__(kThreads, 2) void ppd_mixed_kernel(const KParams P)
     __shared__ __attribute__((aligned(16))) char smem[512 * HD];
     volatile int* s_next = reinterpret_cast<volatile int*>(smem + 512 * HD - 4);
     const int tid = threadIdx.x;
+    // Two queues in one list: MFMA row-block tiles [0, n_mfma) and narrow tiles [n_mfma, n_items), each
+    // longest-first.  A workgroup prefers one kind and steals from the other when its own runs dry, so that
+    // the two workgroups resident on a compute unit tend to run one HBM-bound and one MFMA-bound tile.
+    int pref;
+    switch (P.pref_mode) {
+        case 1: pref = blockIdx.x & 1; break;
+        case 2: pref = blockIdx.x >= (gridDim.x >> 1) ? 1 : 0; break;
+        case 3: pref = (blockIdx.x >> 3) & 1; break;
+        default: pref = 0; break;
+    }
+    bool dry0 = false, dry1 = false;  // only thread 0 uses these
     for (;;) {
-        if (tid == 0) *s_next = (int)atomicAdd(&P.counters[0], 1u);
+        if (tid == 0) {
+            int idx = -1;
+#pragma unroll
+            for (int attempt = 0; attempt < 2 && idx < 0; ++attempt) {
+                const int kind = attempt == 0 ? pref : 1 - pref;  // 0: MFMA queue, 1: narrow queue
+                bool& dry = kind == 0 ? dry0 : dry1;
+                if (dry) continue;
+                const int count = kind == 0 ? P.n_mfma : P.n_items - P.n_mfma;
+                const int got = (int)atomicAdd(&P.counters[kind], 1u);
+                if (got < count)
+                    idx = (kind == 0 ? 0 : P.n_mfma) + got;
+                else
+                    dry = true;
+            }
+            *s_next = idx;
+        }
         __syncthreads();
         const int idx = __builtin_amdgcn_readfirstlane(*s_next);
         __syncthreads();  // everyone has read s_next, and the previous tile's LDS use is over
-        if (idx >= P.n_items) break;
+        if (idx < 0) break;
         const ppd_work_item it = P.items[idx];
         if (it.kind == 0)
             narrow_item<HD>(P, it, smem);
@@ -489,51 +562,54 @@ __global__ __launch_bounds__(kThreads, 2) void ppd_mixed_kernel(const KParams P)
             mfma_item<HD>(P, it, smem);
     }
     if (tid == 0) {
-        // the last workgroup to run out of work re-arms the cursor for the next launch
-        const unsigned done = atomicAdd(&P.counters[1], 1u);
+        // the last workgroup to run out of work re-arms the cursors for the next launch
+        const unsigned done = atomicAdd(&P.counters[3], 1u);
         if (done == gridDim.x - 1) {
             __hip_atomic_store(&P.counters[0], 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
             __hip_atomic_store(&P.counters[1], 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            __hip_atomic_store(&P.counters[3], 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
         }
     }
 }
 
 // ---------------------------------------------------------------------------------------------------
 // Log-sum-exp merge of split partials: out = sum_j o_j 2^{(m_j - m*) c} / sum_j l_j 2^{(m_j - m*) c},
-// splits taken in index order (deterministic).  One workgroup per merge group, one wave per column.
+// splits taken in index order (deterministic).  One wave per (merge group, column): block b takes the 4
+// columns starting at units[b].col0 of group units[b].group.
 // ---------------------------------------------------------------------------------------------------
 __global__ __launch_bounds__(kThreads) void ppd_merge_kernel(const MergeParams M) {
-    const MergeGroup g = M.groups[blockIdx.x];
+    const MergeUnit u = M.units[blockIdx.x];
+    const MergeGroup g = M.groups[u.group];
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int ncols = g.nrows * M.G;
     const int D = M.D;
-    for (int col = wave; col < ncols; col += kThreads / 64) {
-        float mm = NEG_INF;
-        for (int j = 0; j < g.nsplit; ++j)
-            mm = fmaxf(mm, M.partials[g.part_off + g.part_stride * j + (int64_t)ncols * D + col * 2]);
-        float o0 = 0.f, o1 = 0.f, l = 0.f;
-        for (int j = 0; j < g.nsplit; ++j) {
-            const float* pp = M.partials + g.part_off + g.part_stride * j;
-            const float mj = pp[(int64_t)ncols * D + col * 2];
-            const float f = mj == NEG_INF ? 0.f : fast_exp2((mj - mm) * M.scale_log2e);
-            l += f * pp[(int64_t)ncols * D + col * 2 + 1];
-            const int d = lane * 2;
-            if (d < D) {
-                const f32x2 v = *reinterpret_cast<const f32x2*>(pp + (int64_t)col * D + d);
-                o0 += f * v[0];
-                o1 += f * v[1];
-            }
-        }
-        const int d = lane * 2;
+    const int col = u.col0 + wave;
+    if (col >= ncols) return;
+    const float* base = M.partials + g.part_off;
+    const int64_t ml_off = (int64_t)ncols * D + col * 2;
+    float mm = NEG_INF;
+    for (int j = 0; j < g.nsplit; ++j) mm = fmaxf(mm, base[g.part_stride * j + ml_off]);
+    float o0 = 0.f, o1 = 0.f, l = 0.f;
+    const int d = lane * 2;
+    for (int j = 0; j < g.nsplit; ++j) {
+        const float* pp = base + g.part_stride * j;
+        const float mj = pp[ml_off];
+        const float f = mj == NEG_INF ? 0.f : fast_exp2((mj - mm) * M.scale_log2e);
+        l += f * pp[ml_off + 1];
         if (d < D) {
-            const int64_t orow = (int64_t)(g.grow0 + (col >> M.lgG)) * M.Hq + g.kvh * M.G + (col & (M.G - 1));
-            *reinterpret_cast<uint32_t*>(M.out + orow * D + d) = pack_bf16(o0 / l, o1 / l);
+            const f32x2 v = *reinterpret_cast<const f32x2*>(pp + (int64_t)col * D + d);
+            o0 += f * v[0];
+            o1 += f * v[1];
         }
+    }
+    if (d < D) {
+        const int64_t orow = (int64_t)(g.grow0 + (col >> M.lgG)) * M.Hq + g.kvh * M.G + (col & (M.G - 1));
+        *reinterpret_cast<uint32_t*>(M.out + orow * D + d) = pack_bf16(o0 / l, o1 / l);
     }
 }
 
 // ---------------------------------------------------------------------------------------------------
-// Paged KV append.  One workgroup moves 8 consecutive tokens of the batch for all KV heads.
+// Paged KV append.  One workgroup moves 8 consecutive tokens of the batch for one KV head.
 // K: 16-byte granules (8 d of one token), lanes ordered token-minor so that tokens in consecutive slots
 //    write 128 contiguous bytes.  V: a granule is 8 tokens of one d; when the 8 tokens fill one aligned
 //    granule (the common case for prefill) each thread writes it whole, otherwise element by element.
@@ -544,67 +620,63 @@ __global__ __launch_bounds__(kThreads) void ppd_kv_append_kernel(const uint16_t*
                                                                  const int64_t* __restrict__ slots, int64_t T,
                                                                  int Hkv, int D, int64_t num_pages,
                                                                  uint32_t* err_flags) {
-    __shared__ int64_t s_slot[8];
-    __shared__ int s_aligned;
     const int tid = threadIdx.x;
+    const int hh = blockIdx.y;
     const int64_t t0 = (int64_t)blockIdx.x * 8;
     const int nt = (int)((T - t0) < 8 ? (T - t0) : 8);
-    if (tid < 8) {
-        int64_t s = tid < nt ? slots[t0 + tid] : -1;
+    // every thread reads the (at most) 8 slots itself: no LDS round trip, the loads are broadcast
+    int64_t sl[8];
+    bool aligned = nt == 8;
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+        int64_t s = i < nt ? slots[t0 + i] : -1;
         if (s >= num_pages * kPage) {
-            atomicOr(err_flags, 1u);
+            if (tid == 0 && hh == 0) atomicOr(err_flags, 1u);
             s = -1;
         }
-        s_slot[tid] = s;
+        sl[i] = s;
     }
-    __syncthreads();
-    if (tid == 0) {
-        int ok = nt == 8 && s_slot[0] >= 0 && (s_slot[0] & 7) == 0;
-        for (int i = 1; i < 8 && ok; ++i) ok = s_slot[i] == s_slot[0] + i;
-        s_aligned = ok;
-    }
-    __syncthreads();
+    aligned = aligned && sl[0] >= 0 && (sl[0] & 7) == 0;
+#pragma unroll
+    for (int i = 1; i < 8; ++i) aligned = aligned && sl[i] == sl[0] + i;
     const int64_t S = 2LL * Hkv * kPage * D;
     const int HD = Hkv * D;
-    // K: work unit = (h, granule c, token), token fastest
-    const int kunits = Hkv * (D / 8) * 8;
+    const int64_t koff = (int64_t)hh * kPage * D;
+    const int64_t voff = (int64_t)Hkv * kPage * D + koff;
+    // K: work unit = (granule c, token), token fastest
+    const int kunits = (D / 8) * 8;
     for (int u = tid; u < kunits; u += kThreads) {
-        const int tok = u & 7;
-        const int hc = u >> 3;
-        const int c = hc % (D / 8), hh = hc / (D / 8);
-        const int64_t s = s_slot[tok];
+        const int tok = u & 7, c = u >> 3;
+        int64_t s = sl[0];
+#pragma unroll
+        for (int i = 1; i < 8; ++i) s = tok == i ? sl[i] : s;
         if (s < 0) continue;
         const u32x4 val = *reinterpret_cast<const u32x4*>(k + (t0 + tok) * HD + hh * D + c * 8);
-        const int64_t page = s >> 4;
-        const int off = (int)(s & 15);
-        *reinterpret_cast<u32x4*>(pool + page * S + (int64_t)hh * kPage * D + c * (kPage * 8) + off * 8) = val;
+        *reinterpret_cast<u32x4*>(pool + (s >> 4) * S + koff + c * (kPage * 8) + (int)(s & 15) * 8) = val;
     }
-    // V: work unit = (h, d)
-    if (s_aligned) {
-        const int64_t page = s_slot[0] >> 4;
-        const int half = (int)((s_slot[0] & 15) >> 3);
-        for (int u = tid; u < HD; u += kThreads) {
-            const int hh = u / D, d = u % D;
+    // V: work unit = d
+    if (aligned) {
+        const int64_t page = sl[0] >> 4;
+        const int half = (int)((sl[0] & 15) >> 3);
+        for (int d = tid; d < D; d += kThreads) {
             uint32_t w[4];
 #pragma unroll
             for (int e = 0; e < 4; ++e) {
-                const uint32_t lo = v[(t0 + 2 * e) * HD + u];
-                const uint32_t hi = v[(t0 + 2 * e + 1) * HD + u];
+                const uint32_t lo = v[(t0 + 2 * e) * HD + hh * D + d];
+                const uint32_t hi = v[(t0 + 2 * e + 1) * HD + hh * D + d];
                 w[e] = lo | (hi << 16);
             }
-            *reinterpret_cast<u32x4*>(pool + page * S + (int64_t)Hkv * kPage * D + (int64_t)hh * kPage * D +
-                                      half * (D * 8) + d * 8) = u32x4{w[0], w[1], w[2], w[3]};
+            *reinterpret_cast<u32x4*>(pool + page * S + voff + half * (D * 8) + d * 8) = u32x4{w[0], w[1], w[2], w[3]};
         }
     } else {
-        for (int u = tid; u < HD * 8; u += kThreads) {
-            const int tok = u / HD, e = u % HD;
-            const int64_t s = s_slot[tok];
+        for (int u = tid; u < D * 8; u += kThreads) {
+            const int tok = u / D, d = u % D;
+            int64_t s = sl[0];
+#pragma unroll
+            for (int i = 1; i < 8; ++i) s = tok == i ? sl[i] : s;
             if (s < 0) continue;
-            const int hh = e / D, d = e % D;
-            const int64_t page = s >> 4;
             const int off = (int)(s & 15);
-            pool[page * S + (int64_t)Hkv * kPage * D + (int64_t)hh * kPage * D + (off >> 3) * (D * 8) + d * 8 +
-                 (off & 7)] = v[(t0 + tok) * HD + e];
+            pool[(s >> 4) * S + voff + (off >> 3) * (D * 8) + d * 8 + (off & 7)] = v[(t0 + tok) * HD + hh * D + d];
         }
     }
 }
@@ -620,14 +692,14 @@ int launch_mixed(const KParams& p, int head_dim, int grid, void* stream) {
 }
 
 int launch_merge(const MergeParams& p, void* stream) {
-    hipLaunchKernelGGL(ppd_merge_kernel, dim3(p.n_groups), dim3(kThreads), 0, static_cast<hipStream_t>(stream), p);
+    hipLaunchKernelGGL(ppd_merge_kernel, dim3(p.n_units), dim3(kThreads), 0, static_cast<hipStream_t>(stream), p);
     return (int)hipGetLastError();
 }
 
 int launch_kv_append(const uint16_t* k, const uint16_t* v, uint16_t* pool, const int64_t* slots, int64_t T, int Hkv,
                      int D, int64_t num_pages, uint32_t* err_flags, void* stream) {
     const int64_t blocks = (T + 7) / 8;
-    hipLaunchKernelGGL(ppd_kv_append_kernel, dim3((unsigned)blocks), dim3(kThreads), 0,
+    hipLaunchKernelGGL(ppd_kv_append_kernel, dim3((unsigned)blocks, (unsigned)Hkv), dim3(kThreads), 0,
                        static_cast<hipStream_t>(stream), k, v, pool, slots, T, Hkv, D, num_pages, err_flags);
     return (int)hipGetLastError();
 }

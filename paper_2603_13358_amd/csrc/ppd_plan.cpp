@@ -57,6 +57,7 @@ ppd_status build_plan(const ppd_shape& s, const int32_t* L, const int32_t* n, in
     if (!err) err = &dummy;
     plan->items.clear();
     plan->groups.clear();
+    plan->units.clear();
     std::memset(&plan->stats, 0, sizeof plan->stats);
     if (B < 0) { *err = kNeg; return PPD_ERR_RANGE; }
     if (B > 0 && (!L || !n)) { *err = kNull; return PPD_ERR_NULL; }
@@ -123,6 +124,7 @@ ppd_status build_plan(const ppd_shape& s, const int32_t* L, const int32_t* n, in
                     group = (int)plan->groups.size();
                     base = part_floats;
                     plan->groups.push_back(MergeGroup{(int32_t)(grow + r0), nrows, h, nsplit, base, stride});
+                    for (int c0 = 0; c0 < nrows * G; c0 += kThreads / 64) plan->units.push_back(MergeUnit{group, c0});
                     part_floats += stride * nsplit;
                 }
                 for (int sp = 0; sp < nsplit; ++sp) {
@@ -149,7 +151,12 @@ ppd_status build_plan(const ppd_shape& s, const int32_t* L, const int32_t* n, in
         }
         grow += n[i];
     }
-    std::stable_sort(keyed.begin(), keyed.end(), [](const Keyed& a, const Keyed& b) { return a.cost > b.cost; });
+    // two queues in one list: MFMA tiles first, then narrow tiles; each longest-first (stable, so the row
+    // blocks that share a key range stay adjacent and run at about the same time)
+    std::stable_sort(keyed.begin(), keyed.end(), [](const Keyed& a, const Keyed& b) {
+        if (a.it.kind != b.it.kind) return a.it.kind > b.it.kind;
+        return a.cost > b.cost;
+    });
     plan->items.reserve(keyed.size());
     for (auto& k : keyed) plan->items.push_back(k.it);
 
