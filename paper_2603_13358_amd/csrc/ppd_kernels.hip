@@ -57,6 +57,33 @@ __device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_ex
 
 __device__ __forceinline__ float xor_shuffle(float v, int mask) { return __shfl_xor(v, mask, 64); }
 
+// max / sum of v over lanes l and l^32 (v_permlane32_swap: no LDS round trip).  The instruction exchanges
+// the upper half of its first register with the lower half of its second.  It is written as inline asm on
+// two copies of v (the builtin's second result was folded into the first by the compiler when both inputs
+// hold the same value); the s_nop cover the VALU-write -> permlane-read wait states on both sides.
+__device__ __forceinline__ void swap_halves(float v, float* lo, float* hi) {
+    float a = v, b = v;
+    asm volatile("s_nop 1\n\tv_permlane32_swap_b32 %0, %1\n\ts_nop 1" : "+v"(a), "+v"(b));
+    *lo = a;  // {v[0..31], v[0..31]}
+    *hi = b;  // {v[32..63], v[32..63]}
+}
+__device__ __forceinline__ float max_halves(float v) {
+    float lo, hi;
+    swap_halves(v, &lo, &hi);
+    return fmaxf(lo, hi);
+}
+__device__ __forceinline__ float sum_halves(float v) {
+    float lo, hi;
+    swap_halves(v, &lo, &hi);
+    return lo + hi;
+}
+
+// The running maximum is only raised (and the accumulators rescaled) when it would grow by more than this many
+// powers of two; until then probabilities may exceed 1, by at most 2^kLazyRescale.  The final o / l is unchanged.
+#ifndef kLazyRescale
+#define kLazyRescale 8.0f
+#endif
+
 // Raw page-table entry of logical page `pi` of a sequence; pi is clamped so that no access leaves the page
 // table row.  The value is NOT inspected here: a caller that prefetches it must not wait for the load.
 __device__ __forceinline__ int load_page_id(const int32_t* pt_row, int pi, int last_page) {
@@ -239,12 +266,11 @@ __device__ __forceinline__ void mfma_item(const KParams& P, const ppd_work_item&
             for (int tb = 0; tb < 2; ++tb)
 #pragma unroll
                 for (int i = 0; i < 16; ++i) mx = fmaxf(mx, sacc[tb][i]);
-            mx = fmaxf(mx, xor_shuffle(mx, 32));
+            mx = max_halves(mx);
             const float m_new = fmaxf(m_run, mx);
-            const float m_use = m_new == NEG_INF ? 0.f : m_new;
-            const float mc = m_use * c;
-            if (__any(m_new != m_run)) {
-                const float alpha = fast_exp2(m_run * c - mc);  // m_run = -inf gives 0
+            if (__any((m_new - m_run) * c > kLazyRescale)) {  // -inf -> finite counts; -inf -> -inf does not
+                const float m_use = m_new == NEG_INF ? 0.f : m_new;
+                const float alpha = fast_exp2(m_run * c - m_use * c);  // m_run = -inf gives 0
                 l_run *= alpha;
 #pragma unroll
                 for (int db = 0; db < DB; ++db)
@@ -252,6 +278,7 @@ __device__ __forceinline__ void mfma_item(const KParams& P, const ppd_work_item&
                     for (int i = 0; i < 16; ++i) oacc[db][i] *= alpha;
                 m_run = m_new;
             }
+            const float mc = m_run == NEG_INF ? 0.f : m_run * c;
             PPD_TICK(2);
             float psum = 0.f;
 #pragma unroll
@@ -286,7 +313,7 @@ __device__ __forceinline__ void mfma_item(const KParams& P, const ppd_work_item&
     PPD_TICK_FLUSH(P);
 
     // epilogue: O^T register i of block db is d = db*32 + (i/4)*8 + h*4 + i%4 of column `col`
-    const float l_tot = l_run + xor_shuffle(l_run, 32);
+    const float l_tot = sum_halves(l_run);
     if (col < ncols) {
         if (it.part_off < 0) {
             const float inv = 1.f / l_tot;
@@ -431,17 +458,17 @@ __device__ __forceinline__ void narrow_item(const KParams& P, const ppd_work_ite
         }
         float mx = fmaxf(fmaxf(fmaxf(sa[0], sa[1]), fmaxf(sa[2], sa[3])), fmaxf(fmaxf(sb[0], sb[1]), fmaxf(sb[2], sb[3])));
         mx = fmaxf(mx, xor_shuffle(mx, 16));
-        mx = fmaxf(mx, xor_shuffle(mx, 32));
+        mx = max_halves(mx);
         const float m_new = fmaxf(m_run, mx);
-        const float m_use = m_new == NEG_INF ? 0.f : m_new;
-        const float mc = m_use * c;
-        if (__any(m_new != m_run)) {
-            const float alpha = fast_exp2(m_run * c - mc);
+        if (__any((m_new - m_run) * c > kLazyRescale)) {
+            const float m_use = m_new == NEG_INF ? 0.f : m_new;
+            const float alpha = fast_exp2(m_run * c - m_use * c);
             l_run *= alpha;
 #pragma unroll
             for (int db = 0; db < DBN; ++db) oacc[db] *= alpha;
             m_run = m_new;
         }
+        const float mc = m_run == NEG_INF ? 0.f : m_run * c;
         float p[8];
 #pragma unroll
         for (int i = 0; i < 4; ++i) {
@@ -470,7 +497,7 @@ __device__ __forceinline__ void narrow_item(const KParams& P, const ppd_work_ite
         }
     }
     l_run += xor_shuffle(l_run, 16);
-    l_run += xor_shuffle(l_run, 32);
+    l_run = sum_halves(l_run);
 
     // combine the four waves: O^T register i of block db is d = db*16 + 4*g4 + i of column c16
     float* wbuf = reinterpret_cast<float*>(smem) + wave * WSTRIDE;
