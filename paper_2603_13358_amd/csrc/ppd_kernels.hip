@@ -120,15 +120,24 @@ __device__ __forceinline__ u32x4 zero_unwritten(u32x4 v, int first, int kv_total
 
 // ---------------------------------------------------------------------------------------------------
 // MFMA row-block tile: up to 128 query columns (rows x G heads of one KV head) against keys
-// [kv_begin, kv_end).  4 waves x 32 columns; key tiles of 64 tokens (4 pages) staged through LDS, double
-// buffered; v_mfma_f32_32x32x16_bf16 for both products.
+// [kv_begin, kv_end).  4 waves x 32 columns; key tiles of 64 tokens (4 pages); v_mfma_f32_32x32x16_bf16 for
+// both products.  K and V tiles go from the pool straight into LDS (global_load_lds, 16 bytes per lane, no
+// staging registers), each in a ring of two stages.  The loop is software-pipelined: iteration i computes
+// S^T of tile i+1 while it runs the softmax and the PV product of tile i, so that matrix and vector
+// instructions of one wave are independent of each other and can overlap.
+//   iteration i:  loads K(i+2) -> Kring[i&1], V(i+1) -> Vring[(i+1)&1]
+//                 reads K(i+1) from Kring[(i+1)&1], V(i) from Vring[i&1]
+//   one barrier per iteration (after the loads of the iteration have landed).
 // ---------------------------------------------------------------------------------------------------
+typedef const void __attribute__((address_space(1))) * global_cptr;
+typedef void __attribute__((address_space(3))) * lds_ptr;
+
 template <int HD>
 __device__ __forceinline__ void mfma_item(const KParams& P, const ppd_work_item& it, char* smem) {
     constexpr int PB = kPage * HD * 2;         // bytes of one (page, head) block of K or of V
     constexpr int GPP = PB / 16;               // 16-byte granules per block
-    constexpr int KBYTES = 4 * PB;             // K (or V) part of one stage: 4 pages
-    constexpr int STAGE = 2 * KBYTES;
+    constexpr int KBYTES = 4 * PB;             // one stage: 4 pages of K (or of V)
+    constexpr int VRING = 2 * KBYTES;          // LDS: K ring at 0, V ring behind it
     constexpr int ROUNDS = 4 * GPP / kThreads; // granules of K (and of V) each thread moves per tile
     constexpr int KS = HD / 16;                // k-steps of S^T = K Q^T
     constexpr int DB = HD / 32;                // 32-row d blocks of O^T
@@ -163,48 +172,55 @@ __device__ __forceinline__ void mfma_item(const KParams& P, const ppd_work_item&
     const int64_t head_off = (int64_t)it.kvh * (kPage * HD);
     const int64_t v_off = (int64_t)P.Hkv * (kPage * HD);
 
-    // staging assignment: granule gid = r*256 + tid of the tile's 4 page blocks.  The page a thread reads in
-    // round r is the same for its whole wave (s = r at HD = 128, s = 2r + wave/2 at HD = 64), so the ids are
-    // wave-uniform scalar loads, prefetched one tile ahead of the loads that use them.
-    int pages_next[4];
-    u32x4 kst[ROUNDS], vst[ROUNDS];
-    auto fetch_pages = [&](int ti) {
-#pragma unroll
-        for (int s = 0; s < 4; ++s) pages_next[s] = load_page_id_uniform(pt_row, first_page + ti * 4 + s, last_page);
+    // Page ids: lane i of `ids_cur` holds the id of the item's logical page cur_batch*64 + i (16 tiles per
+    // batch), `ids_nxt` the batch after it, loaded a whole batch ahead; a tile's four ids are read out of the
+    // register with v_readlane, so no tile waits on a page-table load.
+    struct TilePages { int p[4]; };
+    int cur_batch = 0;
+    int ids_cur = load_page_id(pt_row, first_page + lane, last_page);
+    int ids_nxt = load_page_id(pt_row, first_page + 64 + lane, last_page);
+    auto advance_pages = [&](int ti) {  // makes tile ti addressable (ti never goes back)
+        if ((ti >> 4) > cur_batch) {
+            ids_cur = ids_nxt;
+            ++cur_batch;
+            ids_nxt = load_page_id(pt_row, first_page + (cur_batch + 1) * 64 + lane, last_page);
+        }
     };
-    auto issue_loads = [&](int ti) {
-        const int tile_base = it.kv_begin + ti * kTileTokens;
+    auto tile_pages = [&](int ti) {  // ti in batch cur_batch or cur_batch + 1
+        TilePages t;
+        const int src = (ti >> 4) == cur_batch ? ids_cur : ids_nxt;
+#pragma unroll
+        for (int s = 0; s < 4; ++s) t.p[s] = __builtin_amdgcn_readlane(src, ((ti & 15) << 2) + s);
+        return t;
+    };
+    // Granule gid = r*256 + tid of the tile's 4 page blocks goes to LDS byte gid*16 of the stage: a wave
+    // writes 1 KiB contiguous per round, which is what a wave-wide LDS-direct load does.  The page a thread
+    // reads in round r is the same for its whole wave (s = r at HD = 128, s = 2r + wave/2 at HD = 64).
+    auto load_block = [&](const TilePages& t, int lds_byte, int64_t kv_off) {
 #pragma unroll
         for (int r = 0; r < ROUNDS; ++r) {
-            const int gid = r * kThreads + tid;
-            const int within = gid % GPP;
-            int page;
-            if (ROUNDS == 4)
-                page = pages_next[r];
-            else
-                page = (wave >> 1) ? pages_next[2 * r + 1] : pages_next[2 * r];
-            const uint16_t* src = P.pool + checked_page(P, page) * P.page_stride + head_off + within * 8;
-            kst[r] = *reinterpret_cast<const u32x4*>(src);
-            vst[r] = *reinterpret_cast<const u32x4*>(src + v_off);
+            const int within = (r * kThreads + tid) % GPP;
+            const int page = ROUNDS == 4 ? t.p[r] : ((wave >> 1) ? t.p[2 * r + 1] : t.p[2 * r]);
+            const uint16_t* src = P.pool + checked_page(P, page) * P.page_stride + head_off + kv_off + within * 8;
+            __builtin_amdgcn_global_load_lds((global_cptr)src, (lds_ptr)(smem + lds_byte + r * 4096 + wave * 1024), 16,
+                                             0, 0);
         }
-        if (tile_base + kTileTokens > it.kv_total) {  // the sequence's last tile: pool rows never written
+    };
+    // V rows of positions >= kv_total were never written: zero them in LDS (each thread fixes the granules it
+    // loaded itself, after its own loads have landed).  Only the sequence's last tile needs it.
+    auto fix_v_tail = [&](int ti, int lds_byte) {
+        const int tile_base = it.kv_begin + ti * kTileTokens;
+        if (tile_base + kTileTokens > it.kv_total) {
 #pragma unroll
             for (int r = 0; r < ROUNDS; ++r) {
                 const int gid = r * kThreads + tid;
                 const int s = gid / GPP, within = gid % GPP;
-                vst[r] = zero_unwritten(vst[r], tile_base + s * 16 + (within / HD) * 8, it.kv_total);
+                u32x4* cell = reinterpret_cast<u32x4*>(smem + lds_byte + gid * 16);
+                *cell = zero_unwritten(*cell, tile_base + s * 16 + (within / HD) * 8, it.kv_total);
             }
         }
     };
-    auto store_stage = [&](int buf) {
-        char* base = smem + buf * STAGE;
-#pragma unroll
-        for (int r = 0; r < ROUNDS; ++r) {
-            const int gid = r * kThreads + tid;
-            *reinterpret_cast<u32x4*>(base + gid * 16) = kst[r];
-            *reinterpret_cast<u32x4*>(base + KBYTES + gid * 16) = vst[r];
-        }
-    };
+    auto wait_loads = [&]() { asm volatile("s_waitcnt vmcnt(0)" ::: "memory"); };
 
     f32x16 oacc[DB];
 #pragma unroll
@@ -218,39 +234,45 @@ __device__ __forceinline__ void mfma_item(const KParams& P, const ppd_work_item&
     //   page = bit4(r), token-in-page = 8*bit2(r) + 4*bit3(r) + (r & 3)
     // so that accumulator registers 8*s2 .. 8*s2+7 of a lane are 8 consecutive tokens of one page.
     const int k_tok = ((l32 >> 2) & 1) * 8 + ((l32 >> 3) & 1) * 4 + (l32 & 3);
-    const int k_lane_off = (l32 >> 4) * PB + k_tok * 16 + h * 256;  // + tb*2*PB + ks*512
-    const int v_lane_off = (h * HD + l32) * 16;                     // + s*PB + db*512
+    const int k_lane_off = (l32 >> 4) * PB + k_tok * 16 + h * 256;  // + stage + tb*2*PB + ks*512
+    const int v_lane_off = VRING + (h * HD + l32) * 16;             // + stage + s*PB + db*512
 
-    fetch_pages(0);
-    issue_loads(0);
-    if (ntiles > 1) fetch_pages(1);
-    store_stage(0);
+    auto qk_tile = [&](int stage, f32x16 (&sacc)[2]) {
+        const char* kb = smem + stage * KBYTES + k_lane_off;
+#pragma unroll
+        for (int tb = 0; tb < 2; ++tb)
+#pragma unroll
+            for (int i = 0; i < 16; ++i) sacc[tb][i] = 0.f;
+#pragma unroll
+        for (int ks = 0; ks < KS; ++ks)
+#pragma unroll
+            for (int tb = 0; tb < 2; ++tb) {
+                bf16x8 a = as_bf16x8(*reinterpret_cast<const u32x4*>(kb + tb * 2 * PB + ks * 512));
+                sacc[tb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, qreg[ks], sacc[tb], 0, 0, 0);
+            }
+    };
+
+    // prologue: K(0), V(0), K(1) land; S^T of tile 0
+    {
+        const TilePages t0 = tile_pages(0);
+        load_block(t0, 0, 0);
+        load_block(t0, VRING, v_off);
+        if (ntiles > 1) load_block(tile_pages(1), KBYTES, 0);
+    }
+    wait_loads();
+    fix_v_tail(0, VRING);
     __syncthreads();
+    f32x16 s_cur[2], s_nxt[2];
+    if (wave_active) qk_tile(0, s_cur);
+    __syncthreads();  // K stage 0 is overwritten by the first iteration's loads
 
     PPD_TICK_DECL();
     for (int ti = 0; ti < ntiles; ++ti) {
-        const int buf = ti & 1;
-        if (ti + 1 < ntiles) {
-            issue_loads(ti + 1);
-            if (ti + 2 < ntiles) fetch_pages(ti + 2);
-        }
+        advance_pages(ti + 1);
+        if (ti + 1 < ntiles) load_block(tile_pages(ti + 1), VRING + ((ti + 1) & 1) * KBYTES, v_off);
+        if (ti + 2 < ntiles) load_block(tile_pages(ti + 2), (ti & 1) * KBYTES, 0);
         PPD_TICK(0);
         if (wave_active) {
-            const char* kb = smem + buf * STAGE + k_lane_off;
-            const char* vb = smem + buf * STAGE + KBYTES + v_lane_off;
-            f32x16 sacc[2];
-#pragma unroll
-            for (int tb = 0; tb < 2; ++tb)
-#pragma unroll
-                for (int i = 0; i < 16; ++i) sacc[tb][i] = 0.f;
-#pragma unroll
-            for (int ks = 0; ks < KS; ++ks)
-#pragma unroll
-                for (int tb = 0; tb < 2; ++tb) {
-                    bf16x8 a = as_bf16x8(*reinterpret_cast<const u32x4*>(kb + tb * 2 * PB + ks * 512));
-                    sacc[tb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, qreg[ks], sacc[tb], 0, 0, 0);
-                }
-            PPD_TICK(1);
             const int tile_base = it.kv_begin + ti * kTileTokens;
             if (tile_base + kTileTokens - 1 > wmin_limit) {  // causal boundary crosses this tile
 #pragma unroll
@@ -258,14 +280,14 @@ __device__ __forceinline__ void mfma_item(const KParams& P, const ppd_work_item&
 #pragma unroll
                     for (int i = 0; i < 16; ++i) {
                         const int pos = tile_base + (tb * 2 + (i >> 3)) * 16 + h * 8 + (i & 7);
-                        if (pos > limit) sacc[tb][i] = NEG_INF;
+                        if (pos > limit) s_cur[tb][i] = NEG_INF;
                     }
             }
-            float mx = sacc[0][0];
+            float mx = s_cur[0][0];
 #pragma unroll
             for (int tb = 0; tb < 2; ++tb)
 #pragma unroll
-                for (int i = 0; i < 16; ++i) mx = fmaxf(mx, sacc[tb][i]);
+                for (int i = 0; i < 16; ++i) mx = fmaxf(mx, s_cur[tb][i]);
             mx = max_halves(mx);
             const float m_new = fmaxf(m_run, mx);
             if (__any((m_new - m_run) * c > kLazyRescale)) {  // -inf -> finite counts; -inf -> -inf does not
@@ -279,14 +301,18 @@ __device__ __forceinline__ void mfma_item(const KParams& P, const ppd_work_item&
                 m_run = m_new;
             }
             const float mc = m_run == NEG_INF ? 0.f : m_run * c;
+            PPD_TICK(1);
+            // S^T of the next tile (matrix pipe) next to the exponentials of this one (vector pipe)
+            if (ti + 1 < ntiles) qk_tile((ti + 1) & 1, s_nxt);
             PPD_TICK(2);
+            const char* vb = smem + (ti & 1) * KBYTES + v_lane_off;
             float psum = 0.f;
 #pragma unroll
             for (int tb = 0; tb < 2; ++tb)
 #pragma unroll
                 for (int i = 0; i < 16; ++i) {
-                    const float p = fast_exp2(__builtin_fmaf(sacc[tb][i], c, -mc));
-                    sacc[tb][i] = p;
+                    const float p = fast_exp2(__builtin_fmaf(s_cur[tb][i], c, -mc));
+                    s_cur[tb][i] = p;
                     psum += p;
                 }
             l_run += psum;
@@ -295,7 +321,7 @@ __device__ __forceinline__ void mfma_item(const KParams& P, const ppd_work_item&
                 u32x4 pw;
 #pragma unroll
                 for (int e = 0; e < 4; ++e)
-                    pw[e] = pack_bf16(sacc[s >> 1][(s & 1) * 8 + 2 * e], sacc[s >> 1][(s & 1) * 8 + 2 * e + 1]);
+                    pw[e] = pack_bf16(s_cur[s >> 1][(s & 1) * 8 + 2 * e], s_cur[s >> 1][(s & 1) * 8 + 2 * e + 1]);
                 const bf16x8 pb = as_bf16x8(pw);
 #pragma unroll
                 for (int db = 0; db < DB; ++db) {
@@ -303,9 +329,12 @@ __device__ __forceinline__ void mfma_item(const KParams& P, const ppd_work_item&
                     oacc[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, pb, oacc[db], 0, 0, 0);
                 }
             }
+#pragma unroll
+            for (int tb = 0; tb < 2; ++tb) s_cur[tb] = s_nxt[tb];
         }
         PPD_TICK(3);
-        if (ti + 1 < ntiles) store_stage(buf ^ 1);
+        wait_loads();
+        if (ti + 1 < ntiles) fix_v_tail(ti + 1, VRING + ((ti + 1) & 1) * KBYTES);
         PPD_TICK(4);
         __syncthreads();
         PPD_TICK(5);

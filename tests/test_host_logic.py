@@ -1,0 +1,158 @@
+"""Host-side tests that need no GPU: the C ABI exports what include/ppd.h declares, and the planner's
+work list covers every visible (row, key) pair exactly once with non-overlapping partials."""
+import ctypes
+import os
+import re
+
+import numpy as np
+import pytest
+
+import paper_2603_13358_amd as ppd
+import synthetic_inputs as si
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def declared_functions():
+    text = open(os.path.join(ROOT, "include", "ppd.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(ppd_[a-z_0-9]+)\s*\(", text)))
+
+
+def test_library_exports_every_declared_symbol():
+    names = declared_functions()
+    assert len(names) >= 10
+    lib = ctypes.CDLL(ppd.lib_path())
+    for name in names:
+        assert hasattr(lib, name), "libppd.so does not export " + name
+    # and the binding wraps every one of them under the same name
+    for name in names:
+        assert hasattr(ppd, name), "binding lacks " + name
+
+
+def test_create_fails_loudly_without_a_gpu():
+    import torch
+    if torch.cuda.is_available():
+        pytest.skip("a GPU is present")
+    with pytest.raises(ppd.PPDError) as e:
+        ppd.ppd_create(32, 8, 128, 16, 64)
+    assert e.value.status == -6 and "no CPU path" in str(e.value)
+
+
+def replay(items, L, n, Hkv, G, D):
+    """Checks the tile list against the definition: row j of sequence i sees keys 0 .. L_i + j."""
+    B = len(L)
+    cover = {}
+    for it in items:
+        assert 0 <= it.seq < B and 0 <= it.kvh < Hkv
+        assert it.L == L[it.seq] and it.kv_total == L[it.seq] + n[it.seq]
+        assert 0 <= it.row0 and it.nrows >= 1 and it.row0 + it.nrows <= n[it.seq]
+        assert it.grow0 == int(np.sum(n[:it.seq])) + it.row0
+        assert it.kv_begin % 64 == 0 and it.kv_begin < it.kv_end <= it.L + it.row0 + it.nrows
+        if it.kind == 0:
+            assert it.nrows * G <= 16 and it.row0 == 0 and it.nrows == n[it.seq]
+        else:
+            assert it.nrows * G <= 128
+        cover.setdefault((it.seq, it.kvh, it.row0, it.nrows), []).append(it)
+    # every row of every (sequence, kv head) is in exactly one row block
+    for i in range(B):
+        for h in range(Hkv):
+            rows = sorted((k[2], k[3]) for k in cover if k[0] == i and k[1] == h)
+            at = 0
+            for r0, nr in rows:
+                assert r0 == at
+                at += nr
+            assert at == n[i]
+    # the key ranges of a block tile [0, L + row0 + nrows) without gaps or overlap
+    part_ranges = []
+    for (i, h, r0, nr), its in cover.items():
+        its = sorted(its, key=lambda t: t.kv_begin)
+        at = 0
+        for t in its:
+            assert t.kv_begin == at
+            at = t.kv_end
+        assert at == L[i] + r0 + nr
+        if len(its) == 1:
+            assert its[0].part_off == -1 and its[0].group == -1
+        else:
+            g = {t.group for t in its}
+            assert len(g) == 1 and -1 not in g
+            stride = nr * G * (D + 2)
+            offs = [t.part_off for t in its]
+            assert offs == [offs[0] + stride * k for k in range(len(its))]
+            part_ranges.append((offs[0], offs[0] + stride * len(its)))
+    part_ranges.sort()
+    for a, b in zip(part_ranges, part_ranges[1:]):
+        assert a[1] <= b[0], "partials overlap"
+    return part_ranges[-1][1] if part_ranges else 0
+
+
+@pytest.mark.parametrize("opts", [{}, {"narrow_chunk": 64, "mfma_chunk": 64}, {"narrow_chunk": 1024, "mfma_chunk": 256},
+                                  {"force_kind": 1}, {"grid": 7}])
+def test_plan_covers_every_pair_once(opts):
+    rng = np.random.default_rng(3)
+    for Hq, Hkv, D in [(32, 8, 128), (8, 2, 64), (8, 8, 128), (8, 1, 64)]:
+        L = rng.integers(0, 3000, size=24)
+        n = np.where(rng.random(24) < 0.5, 1, rng.integers(1, 400, size=24))
+        L[0], n[0] = 0, 1
+        L[1], n[1] = 0, 300
+        items, st = ppd.ppd_plan_build(Hq, Hkv, D, 16, 1 << 20, L, n, **opts)
+        assert st.n_items == len(items) == st.n_narrow + st.n_mfma
+        used = replay(items, L, n, Hkv, Hq // Hkv, D)
+        assert used == st.partial_floats
+        # queues: MFMA tiles first, each queue longest-first
+        kinds = [t.kind for t in items]
+        assert kinds == sorted(kinds, reverse=True)
+        for kind in (0, 1):
+            lens = [t.kv_end - t.kv_begin for t in items if t.kind == kind]
+            assert lens == sorted(lens, reverse=True)
+        b = si.make_batch("x", L=L, n=n, Hq=Hq, Hkv=Hkv, D=D, seed=0, with_data=False)
+        assert st.kv_bytes == b.kv_read_bytes()
+        assert abs(st.flops - b.attention_flops()) <= 1e-9 * st.flops
+        assert st.kv_bytes_tiles >= st.kv_bytes - 1
+        assert 1 <= st.grid <= max(1, st.n_items)
+
+
+def test_plan_classification_follows_L_and_n():
+    # n*G <= 16 columns is the narrow (decode-like) path; more rows go to the MFMA row blocks
+    items, st = ppd.ppd_plan_build(32, 8, 128, 16, 1024, [100, 100, 100, 0], [1, 4, 5, 64])
+    kinds = {}
+    for t in items:
+        kinds.setdefault(t.seq, set()).add(t.kind)
+    assert kinds == {0: {0}, 1: {0}, 2: {1}, 3: {1}}
+    # cost of append-prefill vs full prefill of the same total length: roughly (L+n)/n times cheaper when n << L
+    _, ap = ppd.ppd_plan_build(32, 8, 128, 16, 1 << 20, [8192], [128])
+    _, full = ppd.ppd_plan_build(32, 8, 128, 16, 1 << 20, [0], [8192 + 128])
+    ratio = full.flops / ap.flops
+    assert 0.45 * (8320 / 128) < ratio < 0.55 * (8320 / 128)   # ~ (L+n)/(2n): the causal half of the square
+
+
+def test_plan_rejects_bad_arguments():
+    for L, n, code in [([5], [0], -3), ([-1], [1], -3), ([2 ** 30], [5], -3)]:
+        with pytest.raises(ppd.PPDError) as e:
+            ppd.ppd_plan_build(32, 8, 128, 16, 64, L, n)
+        assert e.value.status == code
+    for shape in [(32, 8, 100, 16, 64), (32, 8, 128, 8, 64), (32, 5, 128, 16, 64), (64, 2, 128, 16, 64),
+                  (32, 8, 128, 16, 0)]:
+        with pytest.raises(ppd.PPDError) as e:
+            ppd.ppd_plan_build(*shape, [5], [1])
+        assert e.value.status == -2
+    with pytest.raises(ppd.PPDError) as e:
+        ppd.ppd_plan_build(32, 8, 128, 16, 64, [5], [1], narrow_chunk=100)
+    assert e.value.status == -3
+    items, st = ppd.ppd_plan_build(32, 8, 128, 16, 64, [], [])
+    assert items == [] and st.n_items == 0
+
+
+def test_trace_schedule_is_consistent():
+    steps, max_tokens = si.cfg5_trace(seed=0, n_conv=12, turns=3, start_spread=20)
+    cached = np.zeros(12, np.int64)
+    seen_attend = False
+    for s in steps:
+        assert np.array_equal(s.L, cached[s.conv]) and (s.n >= 1).all()
+        if not s.attend:
+            assert (s.L == 0).all()          # landing of transferred KV happens on turn 1 only
+        else:
+            seen_attend = True
+        cached[s.conv] += s.n
+    assert seen_attend and np.array_equal(cached, max_tokens)
