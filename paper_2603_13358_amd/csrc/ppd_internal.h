@@ -10,9 +10,20 @@ namespace ppd {
 
 constexpr int kPage = 16;            // tokens per page
 constexpr int kNarrowCols = 16;      // a narrow tile holds rows*G <= 16 query columns
-constexpr int kMfmaCols = 128;       // an MFMA row-block tile holds up to 128 query columns (4 waves x 32)
+#ifndef PPD_WAVES
+#define PPD_WAVES 8
+#endif
+#ifndef PPD_STAGES
+#define PPD_STAGES 3
+#endif
+constexpr int kWaves = PPD_WAVES;            // waves per workgroup of the mixed kernel
+constexpr int kThreads = 64 * kWaves;
+constexpr int kMfmaCols = 32 * kWaves;       // an MFMA row-block tile holds up to 32 query columns per wave
+constexpr int kStages = PPD_STAGES;          // LDS ring depth of the K and of the V tiles
+constexpr int kWgPerCu = kWaves == 8 ? 1 : 2;  // resident workgroups per compute unit (256 VGPRs per wave)
 constexpr int kTileTokens = 64;      // key tile of the MFMA path; every split boundary is a multiple of it
-constexpr int kThreads = 256;
+constexpr int kMaxMfmaChunk = 8192;  // keys per MFMA row-block tile at most (its 512 page ids are staged in LDS)
+constexpr int kSmallThreads = 256;   // block size of the append and merge kernels
 
 // One merge group: a row block whose key range was split over `nsplit` tiles with consecutive partials.
 struct MergeGroup {

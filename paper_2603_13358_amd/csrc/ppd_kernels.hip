@@ -122,22 +122,33 @@ __device__ __forceinline__ u32x4 zero_unwritten(u32x4 v, int first, int kv_total
 // MFMA row-block tile: up to 128 query columns (rows x G heads of one KV head) against keys
 // [kv_begin, kv_end).  4 waves x 32 columns; key tiles of 64 tokens (4 pages); v_mfma_f32_32x32x16_bf16 for
 // both products.  K and V tiles go from the pool straight into LDS (global_load_lds, 16 bytes per lane, no
-// staging registers), each in a ring of two stages.  The loop is software-pipelined: iteration i computes
-// S^T of tile i+1 while it runs the softmax and the PV product of tile i, so that matrix and vector
-// instructions of one wave are independent of each other and can overlap.
-//   iteration i:  loads K(i+2) -> Kring[i&1], V(i+1) -> Vring[(i+1)&1]
-//                 reads K(i+1) from Kring[(i+1)&1], V(i) from Vring[i&1]
-//   one barrier per iteration (after the loads of the iteration have landed).
+// staging registers), each in a ring of kStages stages.  The loop is software-pipelined: iteration i
+// computes S^T of tile i+1 while it runs the softmax and the PV product of tile i, so that matrix and
+// vector instructions of one wave are independent of each other and can overlap.  With NS = kStages:
+//   iteration i:  loads K(i+NS) -> Kring[i % NS], V(i+NS-1) -> Vring[(i+NS-1) % NS]
+//                 reads K(i+1) from Kring[(i+1) % NS], V(i) from Vring[i % NS]
+//   one barrier per iteration, after K(i+2) and V(i+1) have landed (loads issued NS-2 iterations later may
+//   still be in flight).
 // ---------------------------------------------------------------------------------------------------
-typedef const void __attribute__((address_space(1))) * global_cptr;
-typedef void __attribute__((address_space(3))) * lds_ptr;
+// 16 bytes per lane from global memory straight into LDS: lane i of the wave writes lds_base + 16*i
+// (lds_base is wave-uniform and travels in M0).  Written as inline asm so that the compiler's wait-count pass
+// does not see an LDS write it would have to order every later LDS read behind (it would drain the memory
+// counter before the first operand read of each tile); completion is awaited explicitly with s_waitcnt vmcnt.
+__device__ __forceinline__ void lds_direct_load16(const void* gsrc, const char* lds_base) {
+    const uint32_t lds_off = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) const char*)lds_base;
+    asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, off"
+                 :
+                 : "v"(gsrc), "s"(__builtin_amdgcn_readfirstlane(lds_off))
+                 : "memory", "m0");
+}
 
 template <int HD>
 __device__ __forceinline__ void mfma_item(const KParams& P, const ppd_work_item& it, char* smem) {
     constexpr int PB = kPage * HD * 2;         // bytes of one (page, head) block of K or of V
     constexpr int GPP = PB / 16;               // 16-byte granules per block
     constexpr int KBYTES = 4 * PB;             // one stage: 4 pages of K (or of V)
-    constexpr int VRING = 2 * KBYTES;          // LDS: K ring at 0, V ring behind it
+    constexpr int NS = kStages;
+    constexpr int VRING = NS * KBYTES;         // LDS: K ring at 0, V ring behind it
     constexpr int ROUNDS = 4 * GPP / kThreads; // granules of K (and of V) each thread moves per tile
     constexpr int KS = HD / 16;                // k-steps of S^T = K Q^T
     constexpr int DB = HD / 32;                // 32-row d blocks of O^T
@@ -172,38 +183,34 @@ __device__ __forceinline__ void mfma_item(const KParams& P, const ppd_work_item&
     const int64_t head_off = (int64_t)it.kvh * (kPage * HD);
     const int64_t v_off = (int64_t)P.Hkv * (kPage * HD);
 
-    // Page ids: lane i of `ids_cur` holds the id of the item's logical page cur_batch*64 + i (16 tiles per
-    // batch), `ids_nxt` the batch after it, loaded a whole batch ahead; a tile's four ids are read out of the
-    // register with v_readlane, so no tile waits on a page-table load.
+    // Page ids of the whole key range go to LDS once, checked, before the loop (at most 512: the planner
+    // caps a row-block tile at 8192 keys); a tile reads its four ids with one broadcast LDS read.  Nothing in
+    // the loop then depends on a page-table load, so no wait on the memory counter is needed there.
     struct TilePages { int p[4]; };
-    int cur_batch = 0;
-    int ids_cur = load_page_id(pt_row, first_page + lane, last_page);
-    int ids_nxt = load_page_id(pt_row, first_page + 64 + lane, last_page);
-    auto advance_pages = [&](int ti) {  // makes tile ti addressable (ti never goes back)
-        if ((ti >> 4) > cur_batch) {
-            ids_cur = ids_nxt;
-            ++cur_batch;
-            ids_nxt = load_page_id(pt_row, first_page + (cur_batch + 1) * 64 + lane, last_page);
-        }
-    };
-    auto tile_pages = [&](int ti) {  // ti in batch cur_batch or cur_batch + 1
+    int* lds_ids = reinterpret_cast<int*>(smem + 2 * NS * KBYTES);
+    for (int i = tid; i < ntiles * 4; i += kThreads)
+        lds_ids[i] = (int)checked_page(P, load_page_id(pt_row, first_page + i, last_page));
+    auto tile_pages = [&](int ti) {
+        const u32x4 v = *reinterpret_cast<const u32x4*>(lds_ids + ti * 4);
         TilePages t;
-        const int src = (ti >> 4) == cur_batch ? ids_cur : ids_nxt;
 #pragma unroll
-        for (int s = 0; s < 4; ++s) t.p[s] = __builtin_amdgcn_readlane(src, ((ti & 15) << 2) + s);
+        for (int s = 0; s < 4; ++s) t.p[s] = __builtin_amdgcn_readfirstlane((int)v[s]);
         return t;
     };
+    // Workgroup barrier for LDS traffic only: unlike __syncthreads() it does not drain the memory counter, so
+    // LDS-direct loads of later tiles stay in flight across it.
+    auto lds_barrier = [&]() { asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory"); };
     // Granule gid = r*256 + tid of the tile's 4 page blocks goes to LDS byte gid*16 of the stage: a wave
     // writes 1 KiB contiguous per round, which is what a wave-wide LDS-direct load does.  The page a thread
-    // reads in round r is the same for its whole wave (s = r at HD = 128, s = 2r + wave/2 at HD = 64).
+    // reads in round r is the same for its whole wave: s = (r*kThreads + wave*64) / GPP.
     auto load_block = [&](const TilePages& t, int lds_byte, int64_t kv_off) {
 #pragma unroll
         for (int r = 0; r < ROUNDS; ++r) {
             const int within = (r * kThreads + tid) % GPP;
-            const int page = ROUNDS == 4 ? t.p[r] : ((wave >> 1) ? t.p[2 * r + 1] : t.p[2 * r]);
-            const uint16_t* src = P.pool + checked_page(P, page) * P.page_stride + head_off + kv_off + within * 8;
-            __builtin_amdgcn_global_load_lds((global_cptr)src, (lds_ptr)(smem + lds_byte + r * 4096 + wave * 1024), 16,
-                                             0, 0);
+            const int s = (r * kThreads + wave * 64) / GPP;
+            const int page = s == 0 ? t.p[0] : s == 1 ? t.p[1] : s == 2 ? t.p[2] : t.p[3];
+            const uint16_t* src = P.pool + (int64_t)page * P.page_stride + head_off + kv_off + within * 8;
+            lds_direct_load16(src, smem + lds_byte + r * (kThreads * 16) + wave * 1024);
         }
     };
     // V rows of positions >= kv_total were never written: zero them in LDS (each thread fixes the granules it
@@ -220,7 +227,14 @@ __device__ __forceinline__ void mfma_item(const KParams& P, const ppd_work_item&
             }
         }
     };
-    auto wait_loads = [&]() { asm volatile("s_waitcnt vmcnt(0)" ::: "memory"); };
+    // Loads retire in order: waiting until at most `newer` are outstanding guarantees everything issued
+    // before those has landed in LDS.
+    auto wait_all_loads = [&]() { asm volatile("s_waitcnt vmcnt(0)" ::: "memory"); };
+    auto wait_older_loads = [&]() {  // all but the 2*ROUNDS loads of the current iteration
+        if (ROUNDS == 1) asm volatile("s_waitcnt vmcnt(2)" ::: "memory");
+        if (ROUNDS == 2) asm volatile("s_waitcnt vmcnt(4)" ::: "memory");
+        if (ROUNDS == 4) asm volatile("s_waitcnt vmcnt(8)" ::: "memory");
+    };
 
     f32x16 oacc[DB];
 #pragma unroll
@@ -252,25 +266,40 @@ __device__ __forceinline__ void mfma_item(const KParams& P, const ppd_work_item&
             }
     };
 
-    // prologue: K(0), V(0), K(1) land; S^T of tile 0
+    // prologue: K(0..NS-1) and V(0..NS-2) are issued, K(0), K(1), V(0) must land; S^T of tile 0
+    __syncthreads();  // page ids are in LDS
     {
-        const TilePages t0 = tile_pages(0);
-        load_block(t0, 0, 0);
-        load_block(t0, VRING, v_off);
-        if (ntiles > 1) load_block(tile_pages(1), KBYTES, 0);
+#pragma unroll
+        for (int t = 0; t < NS; ++t) {
+            if (t < ntiles) {
+                const TilePages tp = tile_pages(t);
+                load_block(tp, t * KBYTES, 0);
+                if (t < NS - 1) load_block(tp, VRING + t * KBYTES, v_off);
+            }
+        }
     }
-    wait_loads();
-    fix_v_tail(0, VRING);
-    __syncthreads();
+    wait_all_loads();
+    // The compiler does not count the asm loads; make it settle its own pending loads (the Q operand) here, or
+    // it would place ever-decreasing memory-counter waits at their first use inside the loop and drain the
+    // LDS-direct loads in flight there.
+#pragma unroll
+    for (int ks = 0; ks < KS; ++ks) asm volatile("" ::"v"(qreg[ks]));
+#pragma unroll
+    for (int t = 0; t < NS - 1; ++t)
+        if (t < ntiles) fix_v_tail(t, VRING + t * KBYTES);
+    lds_barrier();
     f32x16 s_cur[2], s_nxt[2];
     if (wave_active) qk_tile(0, s_cur);
-    __syncthreads();  // K stage 0 is overwritten by the first iteration's loads
+    lds_barrier();  // K stage 0 is overwritten by the first iteration's loads
+    int st_cur = 0;   // ti % NS
 
     PPD_TICK_DECL();
     for (int ti = 0; ti < ntiles; ++ti) {
-        advance_pages(ti + 1);
-        if (ti + 1 < ntiles) load_block(tile_pages(ti + 1), VRING + ((ti + 1) & 1) * KBYTES, v_off);
-        if (ti + 2 < ntiles) load_block(tile_pages(ti + 2), (ti & 1) * KBYTES, 0);
+        const int st_nxt = st_cur + 1 == NS ? 0 : st_cur + 1;            // (ti + 1) % NS
+        const int st_prv = st_cur == 0 ? NS - 1 : st_cur - 1;            // (ti + NS - 1) % NS
+        const bool full_issue = ti + NS < ntiles;
+        if (ti + NS - 1 < ntiles) load_block(tile_pages(ti + NS - 1), VRING + st_prv * KBYTES, v_off);
+        if (full_issue) load_block(tile_pages(ti + NS), st_cur * KBYTES, 0);
         PPD_TICK(0);
         if (wave_active) {
             const int tile_base = it.kv_begin + ti * kTileTokens;
@@ -303,9 +332,9 @@ __device__ __forceinline__ void mfma_item(const KParams& P, const ppd_work_item&
             const float mc = m_run == NEG_INF ? 0.f : m_run * c;
             PPD_TICK(1);
             // S^T of the next tile (matrix pipe) next to the exponentials of this one (vector pipe)
-            if (ti + 1 < ntiles) qk_tile((ti + 1) & 1, s_nxt);
+            if (ti + 1 < ntiles) qk_tile(st_nxt, s_nxt);
             PPD_TICK(2);
-            const char* vb = smem + (ti & 1) * KBYTES + v_lane_off;
+            const char* vb = smem + st_cur * KBYTES + v_lane_off;
             float psum = 0.f;
 #pragma unroll
             for (int tb = 0; tb < 2; ++tb)
@@ -333,10 +362,15 @@ __device__ __forceinline__ void mfma_item(const KParams& P, const ppd_work_item&
             for (int tb = 0; tb < 2; ++tb) s_cur[tb] = s_nxt[tb];
         }
         PPD_TICK(3);
-        wait_loads();
-        if (ti + 1 < ntiles) fix_v_tail(ti + 1, VRING + ((ti + 1) & 1) * KBYTES);
+        // K(ti+2) and V(ti+1) must have landed; with NS = 3 the loads issued in this iteration may stay in flight
+        if (NS == 3 && full_issue)
+            wait_older_loads();
+        else
+            wait_all_loads();
+        if (ti + 1 < ntiles) fix_v_tail(ti + 1, VRING + st_nxt * KBYTES);
+        st_cur = st_nxt;
         PPD_TICK(4);
-        __syncthreads();
+        lds_barrier();
         PPD_TICK(5);
     }
     PPD_TICK_FLUSH(P);
@@ -376,9 +410,9 @@ __device__ __forceinline__ void mfma_item(const KParams& P, const ppd_work_item&
 }
 
 // ---------------------------------------------------------------------------------------------------
-// Narrow tile: rows*G <= 16 query columns (decode: 1 row x G heads).  HBM-bound: each of the 4 waves
-// streams its own quarter of the key range straight from the pool into MFMA operand registers
-// (v_mfma_f32_16x16x32_bf16; 32 tokens = 2 pages per step, one step prefetched), then the four
+// Narrow tile: rows*G <= 16 query columns (decode: 1 row x G heads).  HBM-bound: each of the waves
+// streams its own share of the key range straight from the pool into MFMA operand registers
+// (v_mfma_f32_16x16x32_bf16; 32 tokens = 2 pages per step, one step prefetched), then the waves'
 // (o, m, l) are combined through LDS.
 // ---------------------------------------------------------------------------------------------------
 template <int HD>
@@ -414,7 +448,7 @@ __device__ __forceinline__ void narrow_item(const KParams& P, const ppd_work_ite
     const int32_t* pt_row = P.page_tables + (int64_t)it.seq * P.max_pages;
     const int last_page = (it.kv_total - 1) >> 4;
     const int nsteps = (it.kv_end - it.kv_begin + 31) >> 5;
-    const int s_lo = wave * nsteps / 4, s_hi = (wave + 1) * nsteps / 4;
+    const int s_lo = wave * nsteps / kWaves, s_hi = (wave + 1) * nsteps / kWaves;
     const int wave_first_page = (it.kv_begin >> 4) + s_lo * 2;
     const int64_t head_off = (int64_t)it.kvh * (kPage * HD);
     const int64_t v_off = (int64_t)P.Hkv * (kPage * HD);
@@ -541,15 +575,15 @@ __device__ __forceinline__ void narrow_item(const KParams& P, const ppd_work_ite
     const float* all = reinterpret_cast<const float*>(smem);
     for (int idx = tid; idx < ncols * HD; idx += kThreads) {
         const int col = idx / HD, d = idx % HD;
-        float mw[4], mm = NEG_INF;
+        float mw[kWaves], mm = NEG_INF;
 #pragma unroll
-        for (int w = 0; w < 4; ++w) {
+        for (int w = 0; w < kWaves; ++w) {
             mw[w] = all[w * WSTRIDE + kNarrowCols * HD + col * 2];
             mm = fmaxf(mm, mw[w]);
         }
         float o = 0.f, l = 0.f;
 #pragma unroll
-        for (int w = 0; w < 4; ++w) {
+        for (int w = 0; w < kWaves; ++w) {
             const float f = mw[w] == NEG_INF ? 0.f : fast_exp2((mw[w] - mm) * c);
             o += f * all[w * WSTRIDE + col * HD + d];
             l += f * all[w * WSTRIDE + kNarrowCols * HD + col * 2 + 1];
@@ -572,12 +606,11 @@ __device__ __forceinline__ void narrow_item(const KParams& P, const ppd_work_ite
 
 template <int HD>
 __global__ __launch_bounds__(kThreads, 2) void ppd_mixed_kernel(const KParams P) {
-    // Two stages of (4 pages of K + 4 pages of V) for the MFMA path = 512*HD bytes (64 KiB at HD = 128, the
-    // static limit).  The narrow path's combine buffer uses the first 256*(HD+2) bytes.  The next-tile index
-    // is broadcast through the last word: the MFMA path ends on a barrier and the narrow path never
-    // touches that word, so it is free whenever a tile has finished.
-    __shared__ __attribute__((aligned(16))) char smem[512 * HD];
-    volatile int* s_next = reinterpret_cast<volatile int*>(smem + 512 * HD - 4);
+    // Dynamic LDS: kStages stages of 4 pages of K and as many of V for the MFMA path (96 KiB at HD = 128 with
+    // three stages); the narrow path's combine buffer (kWaves * 16 * (HD+2) floats) uses the front of it.
+    extern __shared__ __attribute__((aligned(16))) char smem[];
+    __shared__ int s_next_slot;
+    volatile int* s_next = &s_next_slot;
     const int tid = threadIdx.x;
     // Two queues in one list: MFMA row-block tiles [0, n_mfma) and narrow tiles [n_mfma, n_items), each
     // longest-first.  A workgroup prefers one kind and steals from the other when its own runs dry, so that
@@ -633,7 +666,7 @@ __global__ __launch_bounds__(kThreads, 2) void ppd_mixed_kernel(const KParams P)
 // splits taken in index order (deterministic).  One wave per (merge group, column): block b takes the 4
 // columns starting at units[b].col0 of group units[b].group.
 // ---------------------------------------------------------------------------------------------------
-__global__ __launch_bounds__(kThreads) void ppd_merge_kernel(const MergeParams M) {
+__global__ __launch_bounds__(kSmallThreads) void ppd_merge_kernel(const MergeParams M) {
     const MergeUnit u = M.units[blockIdx.x];
     const MergeGroup g = M.groups[u.group];
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
@@ -670,7 +703,7 @@ __global__ __launch_bounds__(kThreads) void ppd_merge_kernel(const MergeParams M
 //    write 128 contiguous bytes.  V: a granule is 8 tokens of one d; when the 8 tokens fill one aligned
 //    granule (the common case for prefill) each thread writes it whole, otherwise element by element.
 // ---------------------------------------------------------------------------------------------------
-__global__ __launch_bounds__(kThreads) void ppd_kv_append_kernel(const uint16_t* __restrict__ k,
+__global__ __launch_bounds__(kSmallThreads) void ppd_kv_append_kernel(const uint16_t* __restrict__ k,
                                                                  const uint16_t* __restrict__ v,
                                                                  uint16_t* __restrict__ pool,
                                                                  const int64_t* __restrict__ slots, int64_t T,
@@ -701,7 +734,7 @@ __global__ __launch_bounds__(kThreads) void ppd_kv_append_kernel(const uint16_t*
     const int64_t voff = (int64_t)Hkv * kPage * D + koff;
     // K: work unit = (granule c, token), token fastest
     const int kunits = (D / 8) * 8;
-    for (int u = tid; u < kunits; u += kThreads) {
+    for (int u = tid; u < kunits; u += kSmallThreads) {
         const int tok = u & 7, c = u >> 3;
         int64_t s = sl[0];
 #pragma unroll
@@ -714,7 +747,7 @@ __global__ __launch_bounds__(kThreads) void ppd_kv_append_kernel(const uint16_t*
     if (aligned) {
         const int64_t page = sl[0] >> 4;
         const int half = (int)((sl[0] & 15) >> 3);
-        for (int d = tid; d < D; d += kThreads) {
+        for (int d = tid; d < D; d += kSmallThreads) {
             uint32_t w[4];
 #pragma unroll
             for (int e = 0; e < 4; ++e) {
@@ -725,7 +758,7 @@ __global__ __launch_bounds__(kThreads) void ppd_kv_append_kernel(const uint16_t*
             *reinterpret_cast<u32x4*>(pool + page * S + voff + half * (D * 8) + d * 8) = u32x4{w[0], w[1], w[2], w[3]};
         }
     } else {
-        for (int u = tid; u < D * 8; u += kThreads) {
+        for (int u = tid; u < D * 8; u += kSmallThreads) {
             const int tok = u / D, d = u % D;
             int64_t s = sl[0];
 #pragma unroll
@@ -738,24 +771,40 @@ __global__ __launch_bounds__(kThreads) void ppd_kv_append_kernel(const uint16_t*
 }
 
 // ---------------------------------------------------------------------------------------------------
+static size_t mixed_lds_bytes(int head_dim) {
+    const size_t rings = (size_t)2 * kStages * 4 * kPage * head_dim * 2 + 2048;  // + page ids of one tile
+    const size_t combine = (size_t)kWaves * kNarrowCols * (head_dim + 2) * sizeof(float);
+    return rings > combine ? rings : combine;
+}
+
 int launch_mixed(const KParams& p, int head_dim, int grid, void* stream) {
     hipStream_t st = static_cast<hipStream_t>(stream);
+    static bool attr_set = false;
+    if (!attr_set) {  // more than 64 KiB of dynamic LDS has to be allowed once per kernel
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&ppd_mixed_kernel<128>),
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)mixed_lds_bytes(128));
+        if (e == hipSuccess)
+            e = hipFuncSetAttribute(reinterpret_cast<const void*>(&ppd_mixed_kernel<64>),
+                                    hipFuncAttributeMaxDynamicSharedMemorySize, (int)mixed_lds_bytes(64));
+        if (e != hipSuccess) return (int)e;
+        attr_set = true;
+    }
     if (head_dim == 128)
-        hipLaunchKernelGGL(ppd_mixed_kernel<128>, dim3(grid), dim3(kThreads), 0, st, p);
+        hipLaunchKernelGGL(ppd_mixed_kernel<128>, dim3(grid), dim3(kThreads), mixed_lds_bytes(128), st, p);
     else
-        hipLaunchKernelGGL(ppd_mixed_kernel<64>, dim3(grid), dim3(kThreads), 0, st, p);
+        hipLaunchKernelGGL(ppd_mixed_kernel<64>, dim3(grid), dim3(kThreads), mixed_lds_bytes(64), st, p);
     return (int)hipGetLastError();
 }
 
 int launch_merge(const MergeParams& p, void* stream) {
-    hipLaunchKernelGGL(ppd_merge_kernel, dim3(p.n_units), dim3(kThreads), 0, static_cast<hipStream_t>(stream), p);
+    hipLaunchKernelGGL(ppd_merge_kernel, dim3(p.n_units), dim3(kSmallThreads), 0, static_cast<hipStream_t>(stream), p);
     return (int)hipGetLastError();
 }
 
 int launch_kv_append(const uint16_t* k, const uint16_t* v, uint16_t* pool, const int64_t* slots, int64_t T, int Hkv,
                      int D, int64_t num_pages, uint32_t* err_flags, void* stream) {
     const int64_t blocks = (T + 7) / 8;
-    hipLaunchKernelGGL(ppd_kv_append_kernel, dim3((unsigned)blocks, (unsigned)Hkv), dim3(kThreads), 0,
+    hipLaunchKernelGGL(ppd_kv_append_kernel, dim3((unsigned)blocks, (unsigned)Hkv), dim3(kSmallThreads), 0,
                        static_cast<hipStream_t>(stream), k, v, pool, slots, T, Hkv, D, num_pages, err_flags);
     return (int)hipGetLastError();
 }

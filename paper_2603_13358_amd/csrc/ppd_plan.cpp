@@ -52,7 +52,7 @@ ppd_status build_plan(const ppd_shape& s, const int32_t* L, const int32_t* n, in
     static const char* kNull = "L / n is NULL";
     static const char* kNeg = "n_i must be >= 1 and L_i >= 0";
     static const char* kBig = "L_i + n_i and the total row count must stay below 2^30";
-    static const char* kChunk = "chunk options must be 0 or a positive multiple of 64; grid >= 0";
+    static const char* kChunk = "chunk options must be 0 or a positive multiple of 64 (mfma_chunk <= 8192); grid >= 0";
     const char* dummy;
     if (!err) err = &dummy;
     plan->items.clear();
@@ -62,7 +62,7 @@ ppd_status build_plan(const ppd_shape& s, const int32_t* L, const int32_t* n, in
     if (B < 0) { *err = kNeg; return PPD_ERR_RANGE; }
     if (B > 0 && (!L || !n)) { *err = kNull; return PPD_ERR_NULL; }
     if (o.narrow_chunk < 0 || o.narrow_chunk % kTileTokens || o.mfma_chunk < 0 || o.mfma_chunk % kTileTokens ||
-        o.grid < 0 || o.num_cus < 1) {
+        o.mfma_chunk > kMaxMfmaChunk || o.grid < 0 || o.num_cus < 1) {
         *err = kChunk; return PPD_ERR_RANGE;
     }
     const int D = s.head_dim, Hq = s.num_q_heads, Hkv = s.num_kv_heads, G = Hq / Hkv;
@@ -93,14 +93,14 @@ ppd_status build_plan(const ppd_shape& s, const int32_t* L, const int32_t* n, in
                 cost_total += 2.0 * Hkv * (L[i] + std::min<int64_t>(n[i], r0 + rows_per_block));
         }
     }
-    const int slots = o.grid > 0 ? o.grid : 2 * o.num_cus;  // two workgroups are resident per compute unit
+    const int slots = o.grid > 0 ? o.grid : kWgPerCu * o.num_cus;  // resident workgroups
     const double per_item = cost_total / (4.0 * slots);     // aim for ~4 tiles per resident workgroup
     int64_t narrow_chunk = o.narrow_chunk > 0
                                ? o.narrow_chunk
                                : std::min<int64_t>(8192, std::max<int64_t>(256, round_up((int64_t)per_item, kTileTokens)));
     int64_t mfma_chunk = o.mfma_chunk > 0
                              ? o.mfma_chunk
-                             : std::min<int64_t>(8192, std::max<int64_t>(512, round_up((int64_t)(per_item / 2), kTileTokens)));
+                             : std::min<int64_t>(kMaxMfmaChunk, std::max<int64_t>(512, round_up((int64_t)(per_item / 2), kTileTokens)));
 
     struct Keyed { double cost; ppd_work_item it; };
     std::vector<Keyed> keyed;
@@ -124,7 +124,7 @@ ppd_status build_plan(const ppd_shape& s, const int32_t* L, const int32_t* n, in
                     group = (int)plan->groups.size();
                     base = part_floats;
                     plan->groups.push_back(MergeGroup{(int32_t)(grow + r0), nrows, h, nsplit, base, stride});
-                    for (int c0 = 0; c0 < nrows * G; c0 += kThreads / 64) plan->units.push_back(MergeUnit{group, c0});
+                    for (int c0 = 0; c0 < nrows * G; c0 += kSmallThreads / 64) plan->units.push_back(MergeUnit{group, c0});
                     part_floats += stride * nsplit;
                 }
                 for (int sp = 0; sp < nsplit; ++sp) {

@@ -52,7 +52,7 @@ def replay(items, L, n, Hkv, G, D):
         if it.kind == 0:
             assert it.nrows * G <= 16 and it.row0 == 0 and it.nrows == n[it.seq]
         else:
-            assert it.nrows * G <= 128
+            assert it.nrows * G <= 256
         cover.setdefault((it.seq, it.kvh, it.row0, it.nrows), []).append(it)
     # every row of every (sequence, kv head) is in exactly one row block
     for i in range(B):
