@@ -164,9 +164,12 @@ def main():
     def run(name, steps, warmup, want_cpu=False):
         b = make_shapes(name, args.seed)
         r = Runner(b, torch, args.seed, options)
+        r.step()                                   # first call: plans and uploads
+        first_plan_us = r.ctx.plan_stats().plan_host_us
         ms = r.time_steps(steps, warmup)
         kms = r.kernel_ms(max(3, min(steps, 10)))
         st = r.ctx.plan_stats().as_dict()
+        st["plan_host_us"] = first_plan_us
         res = {"workload": name, "ms_per_step": ms, "mixed_kernel_ms": kms, "plan": st,
                "kv_bytes": b.kv_read_bytes(), "flops": b.attention_flops(), "rows": b.T, "sequences": b.B}
         if want_cpu:
@@ -221,7 +224,10 @@ def main():
         "config": {"workload": args.workload, "sequences": main_res["sequences"], "new_token_rows": main_res["rows"],
                    "heads": "32q/8kv", "head_dim": 128, "page_size": 16, "seed": args.seed,
                    "kv_bytes_per_step": b_bytes, "attention_flops_per_step": b_flops,
-                   "tiles": main_res["plan"]["n_items"], "grid": main_res["plan"]["grid"]},
+                   "tiles": main_res["plan"]["n_items"], "grid": main_res["plan"]["grid"],
+                   "plan_host_us": main_res["plan"]["plan_host_us"],
+                   "note": "steady state: the device plan is reused while L, n are unchanged, as across the "
+                           "layers of one engine step; plan_host_us is the once-per-step planning cost"},
         "roofline": roofline,
         "cpu_baseline": main_res.get("cpu"),
         "extras": extras,

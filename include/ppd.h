@@ -93,7 +93,7 @@ typedef struct {
     int32_t narrow_chunk;   /* split size (tokens) chosen for narrow tiles */
     int32_t mfma_chunk;     /* split size (tokens) chosen for MFMA tiles */
     int32_t grid;           /* workgroups launched */
-    int32_t reserved;
+    int32_t plan_host_us;   /* host time spent building and staging this plan, microseconds (0 for ppd_plan_build) */
 } ppd_plan_stats;
 
 /* Creates a context bound to HIP device `device` for pools of the given shape. */

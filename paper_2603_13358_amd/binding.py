@@ -33,7 +33,7 @@ class PlanStats(ctypes.Structure):
     _fields_ = [("n_items", ctypes.c_int64), ("n_narrow", ctypes.c_int64), ("n_mfma", ctypes.c_int64),
                 ("n_groups", ctypes.c_int64), ("partial_floats", ctypes.c_int64), ("kv_bytes", ctypes.c_int64),
                 ("kv_bytes_tiles", ctypes.c_int64), ("flops", ctypes.c_double), ("narrow_chunk", ctypes.c_int32),
-                ("mfma_chunk", ctypes.c_int32), ("grid", ctypes.c_int32), ("reserved", ctypes.c_int32)]
+                ("mfma_chunk", ctypes.c_int32), ("grid", ctypes.c_int32), ("plan_host_us", ctypes.c_int32)]
 
     def as_dict(self):
         return {f: getattr(self, f) for f, _ in self._fields_ if f != "reserved"}

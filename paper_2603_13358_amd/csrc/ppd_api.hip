@@ -1,10 +1,12 @@
 // Host side of libppd: context, argument checks, plan upload and kernel launches behind the C ABI.
 #include <hip/hip_runtime.h>
 
+#include <chrono>
 #include <cmath>
 #include <cstdio>
 #include <cstring>
 #include <string>
+#include <vector>
 
 #include "ppd_internal.h"
 
@@ -38,6 +40,11 @@ struct ppd_ctx {
     uint32_t* d_counters = nullptr;  // cursor, finished, error flags (+ padding)
     Staging staging[kStagingSlots];
     int next_slot = 0;
+    // the plan on the device stays valid while L, n and the planner options do not change (the layers of one
+    // engine step call with the same lengths): such calls skip planning and upload
+    std::vector<int32_t> plan_L, plan_n;
+    ppd::PlanOptions plan_opts;
+    bool plan_on_device = false;
     // optional timing of the mixed kernel alone (option "timing")
     bool timing = false;
     bool timed = false;
@@ -199,6 +206,7 @@ ppd_status ppd_mixed_attention(ppd_ctx* ctx, const void* q, const void* kv_pages
         ctx->plan.items.clear();
         ctx->plan.groups.clear();
         ctx->plan.units.clear();
+        ctx->plan_on_device = false;
         std::memset(&ctx->plan.stats, 0, sizeof ctx->plan.stats);
         return PPD_OK;
     }
@@ -206,8 +214,17 @@ ppd_status ppd_mixed_attention(ppd_ctx* ctx, const void* q, const void* kv_pages
         return fail(ctx, PPD_ERR_NULL, "q / kv_pages / page_tables / L / n / out is NULL");
     if (!(scale >= 0.f) || !std::isfinite(scale)) return fail(ctx, PPD_ERR_RANGE, "scale must be finite and >= 0");
     const char* msg = "";
-    ppd_status st = ppd::build_plan(ctx->shape, L, n, B, ctx->opts, &ctx->plan, &msg);
-    if (st != PPD_OK) return fail(ctx, st, msg);
+    ppd_status st = PPD_OK;
+    const bool same_opts = std::memcmp(&ctx->plan_opts, &ctx->opts, sizeof(ppd::PlanOptions)) == 0;
+    const bool reuse = ctx->plan_on_device && same_opts && (int32_t)ctx->plan_L.size() == B &&
+                       std::memcmp(ctx->plan_L.data(), L, sizeof(int32_t) * B) == 0 &&
+                       std::memcmp(ctx->plan_n.data(), n, sizeof(int32_t) * B) == 0;
+    const auto t_plan0 = std::chrono::steady_clock::now();
+    if (!reuse) {
+        ctx->plan_on_device = false;
+        st = ppd::build_plan(ctx->shape, L, n, B, ctx->opts, &ctx->plan, &msg);
+        if (st != PPD_OK) return fail(ctx, st, msg);
+    }
     for (int i = 0; i < B; ++i) {
         const int64_t need = ((int64_t)L[i] + n[i] + ppd::kPage - 1) / ppd::kPage;
         if (need > max_pages)
@@ -217,48 +234,56 @@ ppd_status ppd_mixed_attention(ppd_ctx* ctx, const void* q, const void* kv_pages
     hipStream_t hs = static_cast<hipStream_t>(stream);
     PPD_HIP(ctx, hipSetDevice(ctx->device));
 
-    // upload: [items][groups] through one pinned staging slot
     const ppd::Plan& plan = ctx->plan;
     const size_t items_bytes = plan.items.size() * sizeof(ppd_work_item);
     const size_t groups_bytes = plan.groups.size() * sizeof(ppd::MergeGroup);
     const size_t units_bytes = plan.units.size() * sizeof(ppd::MergeUnit);
     const size_t total = items_bytes + groups_bytes + units_bytes;
-    Staging& sg = ctx->staging[ctx->next_slot];
-    ctx->next_slot = (ctx->next_slot + 1) % kStagingSlots;
-    if (sg.in_flight) {
-        PPD_HIP(ctx, hipEventSynchronize(sg.done));
-        sg.in_flight = false;
-    }
-    if (sg.bytes < total) {
-        if (sg.host) PPD_HIP(ctx, hipHostFree(sg.host));
-        sg.host = nullptr;
-        sg.bytes = 0;
-        const size_t want = total + total / 4 + 4096;
-        if (hipHostMalloc(&sg.host, want, hipHostMallocDefault) != hipSuccess) {
-            (void)hipGetLastError();
-            sg.host = nullptr;
-            return fail(ctx, PPD_ERR_WORKSPACE, "pinned staging allocation failed");
+    if (!reuse) {
+        // upload: [items][groups][units] through one pinned staging slot
+        Staging& sg = ctx->staging[ctx->next_slot];
+        ctx->next_slot = (ctx->next_slot + 1) % kStagingSlots;
+        if (sg.in_flight) {
+            PPD_HIP(ctx, hipEventSynchronize(sg.done));
+            sg.in_flight = false;
         }
-        sg.bytes = want;
-    }
-    st = grow_device(ctx, &ctx->d_items, &ctx->d_items_bytes, total, hs);
-    if (st != PPD_OK) return st;
-    {
-        void* p = ctx->d_partials;
-        size_t have = ctx->d_partials_floats * sizeof(float);
-        st = grow_device(ctx, &p, &have, (size_t)plan.stats.partial_floats * sizeof(float), hs);
-        ctx->d_partials = static_cast<float*>(p);
-        ctx->d_partials_floats = have / sizeof(float);
+        if (sg.bytes < total) {
+            if (sg.host) PPD_HIP(ctx, hipHostFree(sg.host));
+            sg.host = nullptr;
+            sg.bytes = 0;
+            const size_t want = total + total / 4 + 4096;
+            if (hipHostMalloc(&sg.host, want, hipHostMallocDefault) != hipSuccess) {
+                (void)hipGetLastError();
+                sg.host = nullptr;
+                return fail(ctx, PPD_ERR_WORKSPACE, "pinned staging allocation failed");
+            }
+            sg.bytes = want;
+        }
+        st = grow_device(ctx, &ctx->d_items, &ctx->d_items_bytes, total, hs);
         if (st != PPD_OK) return st;
+        {
+            void* p = ctx->d_partials;
+            size_t have = ctx->d_partials_floats * sizeof(float);
+            st = grow_device(ctx, &p, &have, (size_t)plan.stats.partial_floats * sizeof(float), hs);
+            ctx->d_partials = static_cast<float*>(p);
+            ctx->d_partials_floats = have / sizeof(float);
+            if (st != PPD_OK) return st;
+        }
+        std::memcpy(sg.host, plan.items.data(), items_bytes);
+        if (groups_bytes) {
+            std::memcpy(static_cast<char*>(sg.host) + items_bytes, plan.groups.data(), groups_bytes);
+            std::memcpy(static_cast<char*>(sg.host) + items_bytes + groups_bytes, plan.units.data(), units_bytes);
+        }
+        PPD_HIP(ctx, hipMemcpyAsync(ctx->d_items, sg.host, total, hipMemcpyHostToDevice, hs));
+        PPD_HIP(ctx, hipEventRecord(sg.done, hs));
+        sg.in_flight = true;
+        ctx->plan_L.assign(L, L + B);
+        ctx->plan_n.assign(n, n + B);
+        ctx->plan_opts = ctx->opts;
+        ctx->plan_on_device = true;
+        ctx->plan.stats.plan_host_us = (int32_t)std::chrono::duration_cast<std::chrono::microseconds>(
+                                           std::chrono::steady_clock::now() - t_plan0).count();
     }
-    std::memcpy(sg.host, plan.items.data(), items_bytes);
-    if (groups_bytes) {
-        std::memcpy(static_cast<char*>(sg.host) + items_bytes, plan.groups.data(), groups_bytes);
-        std::memcpy(static_cast<char*>(sg.host) + items_bytes + groups_bytes, plan.units.data(), units_bytes);
-    }
-    PPD_HIP(ctx, hipMemcpyAsync(ctx->d_items, sg.host, total, hipMemcpyHostToDevice, hs));
-    PPD_HIP(ctx, hipEventRecord(sg.done, hs));
-    sg.in_flight = true;
 
     const int G = ctx->shape.num_q_heads / ctx->shape.num_kv_heads;
     // Masked scores are -inf and enter the exponent as s*c: keep c strictly positive so that scale = 0 gives

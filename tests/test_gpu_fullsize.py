@@ -1,0 +1,88 @@
+"""Full-size workloads in the launch configuration bench.py times, checked on sampled outputs the oracle can
+compute one by one: KV append bit-exact on the sampled sequences' pages, attention within the parity bar on
+sampled rows (all heads), plus properties that hold at any size (finite output, determinism)."""
+import numpy as np
+import pytest
+
+import oracle
+import synthetic_inputs as si
+from helpers import check_close
+
+pytestmark = pytest.mark.gpu
+
+
+def _run_and_check(name, seq_ids_fn, rows_per_seq=4):
+    import torch
+    import bench
+    b = bench.make_shapes(name, 0)
+    print("workload", name, "B", b.B, "T", b.T, flush=True)
+    r = bench.Runner(b, torch, 0)
+    w = r.w
+    seqs = seq_ids_fn(b)
+    # pages of the sampled sequences before the append
+    sub0, pool_before, rows = si.compact_subbatch(b, seqs, w["pool"], w["q"], torch)
+    r.step()
+    torch.cuda.synchronize()
+    assert r.ctx.device_error_flags() == 0
+    out1 = w["out"].clone()
+    sub, pool_after, rows = si.compact_subbatch(b, seqs, w["pool"], w["q"], torch)
+    # --- append: oracle-append the sampled sequences' new tokens into the 'before' pages
+    idx = torch.from_numpy(rows).to(w["k_new"].device)
+    k_new = w["k_new"].view(torch.int16)[idx].cpu().numpy().view(np.uint16)
+    v_new = w["v_new"].view(torch.int16)[idx].cpu().numpy().view(np.uint16)
+    slots = np.concatenate([sub.slots(i, int(sub.L[i]), int(sub.L[i] + sub.n[i])) for i in range(sub.B)])
+    ref_pool = pool_before.copy()
+    oracle.kv_append(k_new, v_new, ref_pool, slots, sub.Hkv, sub.D, sub.P, sub.num_pages)
+    assert np.array_equal(ref_pool, pool_after), "KV append is not bit-exact at full size"
+    # --- attention on sampled rows
+    mask = np.zeros(sub.T, np.uint8)
+    for i in range(sub.B):
+        n_i = int(sub.n[i])
+        pick = sorted(set([0, n_i - 1] + list(np.linspace(0, n_i - 1, rows_per_seq).astype(int))))
+        mask[int(sub.row_off[i]) + np.asarray(pick)] = 1
+    ref = oracle.mixed_attention(sub.q, pool_after, sub.page_tables, sub.L, sub.n, sub.Hq, sub.Hkv, sub.D, sub.P,
+                                 sub.num_pages, sub.scale, row_mask=mask)
+    got = out1.float().cpu().numpy()[rows]
+    sel = mask.astype(bool)
+    worst = check_close(got[sel], ref[sel])
+    print("  sampled %d rows of %d sequences: max-abs %.3e" % (int(sel.sum()), len(seqs), worst), flush=True)
+    # --- any-size properties
+    assert bool(torch.isfinite(out1.float()).all())
+    r.step()
+    torch.cuda.synchronize()
+    assert torch.equal(w["out"], out1), "not run-to-run deterministic"
+    r.close()
+
+
+def _shortest_longest(b, k=1):
+    order = np.argsort(b.L.astype(np.int64) + b.n)
+    return [int(order[0]), int(order[len(order) // 2]), int(order[-1])][:max(1, k)] if k < 3 else \
+        [int(order[0]), int(order[len(order) // 2]), int(order[-1])]
+
+
+def test_cfg2_decode_full_size():
+    _run_and_check("cfg2_decode", lambda b: _shortest_longest(b, 3))
+
+
+def test_cfg3_append_prefill_full_size():
+    def pick(b):
+        order = np.argsort(b.n)
+        return [int(order[0]), int(order[-1])]          # smallest and largest new-token count
+    _run_and_check("cfg3_ap", pick, rows_per_seq=5)
+
+
+def test_cfg4_mixed_full_size():
+    def pick(b):
+        dec = [i for i in range(b.B) if b.n[i] == 1]
+        ap = [i for i in range(b.B) if b.n[i] > 1]
+        dec = sorted(dec, key=lambda i: int(b.L[i]))
+        return [dec[0], dec[-1], ap[0]]
+    _run_and_check("cfg4_mixed_ap", pick, rows_per_seq=4)
+
+
+def test_cfg4_full_prefill_variant_full_size():
+    def pick(b):
+        full = sorted([i for i in range(b.B) if b.n[i] > 1], key=lambda i: int(b.n[i]))
+        dec = sorted([i for i in range(b.B) if b.n[i] == 1], key=lambda i: int(b.L[i]))
+        return [dec[len(dec) // 2], full[0]]
+    _run_and_check("cfg4_mixed_full", pick, rows_per_seq=5)
