@@ -27,6 +27,17 @@ HBM_PEAK_GBS = 8000.0       # MI355X HBM3E, published
 MFMA_BF16_PEAK_TFLOPS = 2500.0  # MI355X dense bf16 MFMA, published
 
 
+def measured_traffic(workload):
+    """HBM bytes per launch of the mixed kernel from the counter runs summarised in profiles/hbm_traffic.json
+    (FETCH_SIZE + WRITE_SIZE, each scaled by the factor a plain copy of known size gives); None if absent."""
+    path = os.path.join(ROOT, "profiles", "hbm_traffic.json")
+    try:
+        with open(path) as f:
+            return json.load(f)["workloads"][workload]["hbm_bytes_per_launch"]
+    except (OSError, KeyError, ValueError):
+        return None
+
+
 def make_shapes(name, seed):
     import synthetic_inputs as si
     if name == "cfg4_mixed_ap":
@@ -153,6 +164,8 @@ def main():
     ap.add_argument("--no-extras", action="store_true", help="time the chosen workload only")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle leg")
     ap.add_argument("--opt", action="append", default=[], help="library option key=value (tuning sweeps)")
+    ap.add_argument("--copy-probe", action="store_true",
+                    help="run a plain 1 GiB device copy a few times and exit (calibrates HBM byte counters)")
     args = ap.parse_args()
     if args.gpus != 1:
         raise SystemExit("bench.py measures one GPU: the step has no multi-GPU part in this build (--gpus 1 only)")
@@ -160,6 +173,15 @@ def main():
     if not torch.cuda.is_available():
         raise SystemExit("bench.py needs an MI355X: the library has no CPU path")
     options = {kv.split("=")[0]: int(kv.split("=")[1]) for kv in args.opt}
+    if args.copy_probe:
+        nbytes = 1 << 30
+        src = torch.arange(nbytes // 4, dtype=torch.int32, device="cuda:0")
+        dst = torch.empty_like(src)
+        for _ in range(5):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        print(json.dumps({"copy_probe_bytes_read": nbytes, "copy_probe_bytes_written": nbytes, "copies": 5}))
+        return
 
     def run(name, steps, warmup, want_cpu=False):
         b = make_shapes(name, args.seed)
@@ -188,7 +210,7 @@ def main():
         roofline = {"bound": "mfma", "achieved": b_flops / kernel_s / 1e12, "peak": MFMA_BF16_PEAK_TFLOPS,
                     "unit": "TFLOP/s"}
     roofline["frac"] = roofline["achieved"] / roofline["peak"]
-    roofline["traffic"] = None
+    roofline["traffic"] = measured_traffic(args.workload)
     roofline["kernel"] = "ppd_mixed_kernel<128>"
     roofline["kernel_ms"] = main_res["mixed_kernel_ms"]
 
