@@ -77,7 +77,7 @@ typedef struct {
     int32_t kv_begin; /* key range [kv_begin, kv_end) this tile covers; kv_begin is a multiple of 64 */
     int32_t kv_end;
     int32_t group;    /* merge group, or -1 when the tile covers the whole key range and writes `out` */
-    int32_t reserved;
+    int32_t queue;    /* work queue: 0..7 = MFMA tiles preferred by the workgroups of XCD `queue`, 8 = narrow tiles */
     int64_t part_off; /* float offset of this tile's partial (o, m, l) in the workspace, or -1 */
 } ppd_work_item;
 
@@ -106,9 +106,9 @@ const char *ppd_last_error(const ppd_ctx *ctx);
 
 /* Tuning knobs (all optional).  key: "narrow_chunk", "mfma_chunk" (tokens, multiple of 64, 0 = automatic),
  * "grid" (workgroups, 0 = automatic), "force_kind" (-1 automatic, 1 = route every sequence through the
- * MFMA row-block path; used to test that n = 1 append-prefill equals decode), "pref_mode" (0..3: how a
- * workgroup picks the tile queue it prefers -- 0 MFMA tiles first for all, 1 by parity of the workgroup
- * index, 2 lower / upper half of the grid (default), 3 by parity of index/8), "timing" (1 = record HIP
+ * MFMA row-block path; used to test that n = 1 append-prefill equals decode), "pref_mode" (0..3: which
+ * kind of tile a workgroup takes first -- 0 MFMA tiles for all, 1 alternating per group of 8 workgroups,
+ * 2 lower half of the grid MFMA / upper half narrow (default), 3 narrow tiles for all), "timing" (1 = record HIP
  * events on the call's stream right before and after the mixed-attention kernel, see ppd_last_kernel_ms). */
 ppd_status ppd_set_option(ppd_ctx *ctx, const char *key, int64_t value);
 
@@ -159,10 +159,11 @@ ppd_status ppd_device_error_flags(ppd_ctx *ctx, void *stream, uint32_t *flags);
  * the merge kernel are outside the bracket). */
 ppd_status ppd_last_kernel_ms(ppd_ctx *ctx, float *ms);
 
-/* Debugging aid: synchronises `stream` and copies the context's 16 device counters (work cursors, error
- * flags, finished count, and -- in a build with -DPPD_PHASE_TIMING -- six 64-bit per-phase cycle sums of the
- * MFMA tile loop in words 4..15) to HOST out16[16]; clear != 0 zeroes words 4..15 afterwards. */
-ppd_status ppd_debug_counters(ppd_ctx *ctx, void *stream, uint32_t *out16, int32_t clear);
+/* Debugging aid: synchronises `stream` and copies the context's 64 device counter words (words 0..8 queue
+ * cursors, 9 error flags, 10 finished workgroups, and -- in a build with -DPPD_PHASE_TIMING -- six 64-bit
+ * per-phase cycle sums of the MFMA tile loop in words 16..27) to HOST out64[64]; clear != 0 zeroes words
+ * 16..63 afterwards. */
+ppd_status ppd_debug_counters(ppd_ctx *ctx, void *stream, uint32_t *out64, int32_t clear);
 
 /* Library version, "major.minor". */
 const char *ppd_version(void);

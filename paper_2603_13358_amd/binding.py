@@ -26,7 +26,7 @@ class Shape(ctypes.Structure):
 class WorkItem(ctypes.Structure):
     _fields_ = [(name, ctypes.c_int32) for name in
                 ("kind", "seq", "kvh", "row0", "nrows", "grow0", "L", "kv_total", "kv_begin", "kv_end", "group",
-                 "reserved")] + [("part_off", ctypes.c_int64)]
+                 "queue")] + [("part_off", ctypes.c_int64)]
 
 
 class PlanStats(ctypes.Structure):
@@ -157,7 +157,7 @@ def ppd_last_kernel_ms(ctx):
 
 
 def ppd_debug_counters(ctx, stream=None, clear=False):
-    buf = (ctypes.c_uint32 * 16)()
+    buf = (ctypes.c_uint32 * 64)()
     _check(load_library().ppd_debug_counters(ctx, stream, buf, 1 if clear else 0), ctx)
     return [int(x) for x in buf]
 

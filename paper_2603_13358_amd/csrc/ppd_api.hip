@@ -37,7 +37,7 @@ struct ppd_ctx {
     size_t d_items_bytes = 0;
     float* d_partials = nullptr;
     size_t d_partials_floats = 0;
-    uint32_t* d_counters = nullptr;  // cursor, finished, error flags (+ padding)
+    uint32_t* d_counters = nullptr;  // 64 words: queue cursors, error flags, finished count, timing sums
     Staging staging[kStagingSlots];
     int next_slot = 0;
     // the plan on the device stays valid while L, n and the planner options do not change (the layers of one
@@ -130,8 +130,8 @@ ppd_status ppd_create(const ppd_shape* shape, int32_t device, ppd_ctx** out) {
     }
     ctx->num_cus = prop.multiProcessorCount > 0 ? prop.multiProcessorCount : 256;
     ctx->opts.num_cus = ctx->num_cus;
-    if ((e = hipMalloc((void**)&ctx->d_counters, 64)) != hipSuccess) return bail(e, "hipMalloc(counters)");
-    if ((e = hipMemset(ctx->d_counters, 0, 64)) != hipSuccess) return bail(e, "hipMemset(counters)");
+    if ((e = hipMalloc((void**)&ctx->d_counters, 256)) != hipSuccess) return bail(e, "hipMalloc(counters)");
+    if ((e = hipMemset(ctx->d_counters, 0, 256)) != hipSuccess) return bail(e, "hipMemset(counters)");
     for (auto& s : ctx->staging)
         if ((e = hipEventCreateWithFlags(&s.done, hipEventDisableTiming)) != hipSuccess) return bail(e, "hipEventCreate");
     if ((e = hipEventCreate(&ctx->ev_begin)) != hipSuccess) return bail(e, "hipEventCreate");
@@ -192,7 +192,7 @@ ppd_status ppd_kv_append(ppd_ctx* ctx, const void* k, const void* v, void* kv_pa
     PPD_HIP(ctx, hipSetDevice(ctx->device));
     int rc = ppd::launch_kv_append(static_cast<const uint16_t*>(k), static_cast<const uint16_t*>(v),
                                    static_cast<uint16_t*>(kv_pages), slot_mapping, T, ctx->shape.num_kv_heads,
-                                   ctx->shape.head_dim, ctx->shape.num_pages, ctx->d_counters + 2, stream);
+                                   ctx->shape.head_dim, ctx->shape.num_pages, ctx->d_counters + 9, stream);
     if (rc != 0) return hip_fail(ctx, (hipError_t)rc, "launch kv_append");
     return PPD_OK;
 }
@@ -301,7 +301,7 @@ ppd_status ppd_mixed_attention(ppd_ctx* ctx, const void* q, const void* kv_pages
     kp.num_pages = ctx->shape.num_pages;
     kp.page_stride = 2LL * ctx->shape.num_kv_heads * ppd::kPage * ctx->shape.head_dim;
     kp.n_items = (int32_t)plan.items.size();
-    kp.n_mfma = (int32_t)plan.stats.n_mfma;
+    std::memcpy(kp.queue_begin, plan.queue_begin, sizeof kp.queue_begin);
     kp.pref_mode = ctx->opts.pref_mode;
     kp.max_pages = max_pages;
     kp.Hq = ctx->shape.num_q_heads;
@@ -351,13 +351,13 @@ ppd_status ppd_last_kernel_ms(ppd_ctx* ctx, float* ms) {
     return PPD_OK;
 }
 
-ppd_status ppd_debug_counters(ppd_ctx* ctx, void* stream, uint32_t* out16, int32_t clear) {
-    if (!ctx || !out16) return fail(ctx, PPD_ERR_NULL, "ctx / out16 is NULL");
+ppd_status ppd_debug_counters(ppd_ctx* ctx, void* stream, uint32_t* out64, int32_t clear) {
+    if (!ctx || !out64) return fail(ctx, PPD_ERR_NULL, "ctx / out64 is NULL");
     hipStream_t hs = static_cast<hipStream_t>(stream);
     PPD_HIP(ctx, hipSetDevice(ctx->device));
     PPD_HIP(ctx, hipStreamSynchronize(hs));
-    PPD_HIP(ctx, hipMemcpy(out16, ctx->d_counters, 64, hipMemcpyDeviceToHost));
-    if (clear) PPD_HIP(ctx, hipMemset(ctx->d_counters + 4, 0, 48));
+    PPD_HIP(ctx, hipMemcpy(out64, ctx->d_counters, 256, hipMemcpyDeviceToHost));
+    if (clear) PPD_HIP(ctx, hipMemset(ctx->d_counters + 16, 0, 192));
     return PPD_OK;
 }
 
@@ -367,8 +367,8 @@ ppd_status ppd_device_error_flags(ppd_ctx* ctx, void* stream, uint32_t* flags) {
     PPD_HIP(ctx, hipSetDevice(ctx->device));
     PPD_HIP(ctx, hipStreamSynchronize(hs));
     uint32_t v = 0;
-    PPD_HIP(ctx, hipMemcpy(&v, ctx->d_counters + 2, sizeof v, hipMemcpyDeviceToHost));
-    PPD_HIP(ctx, hipMemset(ctx->d_counters + 2, 0, sizeof v));
+    PPD_HIP(ctx, hipMemcpy(&v, ctx->d_counters + 9, sizeof v, hipMemcpyDeviceToHost));
+    PPD_HIP(ctx, hipMemset(ctx->d_counters + 9, 0, sizeof v));
     *flags = v;
     return PPD_OK;
 }

@@ -41,7 +41,11 @@ struct MergeUnit {
     int32_t col0;
 };
 
+constexpr int kXcds = 8;             // MFMA tile queues, one per XCD (each XCD has its own L2)
+constexpr int kNarrowQueue = kXcds;  // index of the narrow-tile queue
+
 struct Plan {
+    int32_t queue_begin[kXcds + 2];  // items [queue_begin[q], queue_begin[q+1]) belong to queue q
     std::vector<ppd_work_item> items;
     std::vector<MergeGroup> groups;
     std::vector<MergeUnit> units;
@@ -70,11 +74,11 @@ struct KParams {
     const int32_t* page_tables;
     const ppd_work_item* items;
     float* partials;
-    uint32_t* counters;   // [0] MFMA-queue cursor, [1] narrow-queue cursor, [2] sticky error flags, [3] finished workgroups
+    uint32_t* counters;   // [0..8] queue cursors, [9] sticky error flags, [10] finished workgroups, [16..] timing
+    int32_t queue_begin[kXcds + 2];
     int64_t num_pages;
     int64_t page_stride;  // elements per page = 2 * Hkv * 16 * D
     int32_t n_items;
-    int32_t n_mfma;       // items [0, n_mfma) are MFMA row-block tiles, the rest narrow tiles
     int32_t pref_mode;    // how a workgroup picks its preferred queue (see ppd_mixed_kernel)
     int32_t max_pages;
     int32_t Hq, Hkv, G, lgG;

@@ -24,7 +24,7 @@ typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 #define NEG_INF (-__builtin_inff())
 
 // Optional phase timing of the MFMA tile loop (build with -DPPD_PHASE_TIMING): shader-clock cycles of wave 0
-// of every workgroup, summed per phase into counters[4..15] as six 64-bit sums.  Off in the product build.
+// of every workgroup, summed per phase into counters[16..27] as six 64-bit sums.  Off in the product build.
 #ifdef PPD_PHASE_TIMING
 #define PPD_TICK_DECL() long long tick_last_ = clock64(); long long tick_sum_[6] = {0, 0, 0, 0, 0, 0}
 #define PPD_TICK(k)                              \
@@ -37,7 +37,7 @@ typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
     do {                                                                                                   \
         if (threadIdx.x == 0)                                                                              \
             for (int k_ = 0; k_ < 6; ++k_)                                                                 \
-                atomicAdd(reinterpret_cast<unsigned long long*>((P).counters + 4) + k_, (unsigned long long)tick_sum_[k_]); \
+                atomicAdd(reinterpret_cast<unsigned long long*>((P).counters + 16) + k_, (unsigned long long)tick_sum_[k_]); \
     } while (0)
 #else
 #define PPD_TICK_DECL() do {} while (0)
@@ -114,7 +114,7 @@ __device__ __forceinline__ int load_page_id_uniform(const int32_t* pt_row, int p
 // page 0, so that no access leaves the pool.
 __device__ __forceinline__ int64_t checked_page(const KParams& P, int page) {
     if (page < 0 || page >= P.num_pages) {
-        atomicOr(&P.counters[2], 2u);
+        atomicOr(&P.counters[9], 2u);
         page = 0;
     }
     return page;
@@ -664,31 +664,46 @@ __global__ __launch_bounds__(kThreads, 2) void ppd_mixed_kernel(const KParams P)
     __shared__ int s_next_slot;
     volatile int* s_next = &s_next_slot;
     const int tid = threadIdx.x;
-    // Two queues in one list: MFMA row-block tiles [0, n_mfma) and narrow tiles [n_mfma, n_items), each
-    // longest-first.  A workgroup prefers one kind and steals from the other when its own runs dry, so that
-    // the two workgroups resident on a compute unit tend to run one HBM-bound and one MFMA-bound tile.
+    // Nine queues in one list: MFMA row-block tiles in eight queues, one per XCD (tiles that read the same K/V
+    // sit in the same queue, next to each other, so the workgroups of one XCD find them in their L2), and one
+    // queue of narrow tiles; each longest-first.  A workgroup prefers one kind -- lower half of the grid MFMA
+    // tiles, upper half narrow tiles -- so that HBM-bound and MFMA-bound tiles run side by side on different
+    // compute units, takes MFMA tiles from its own XCD's queue first, and steals from the other queues when
+    // its own run dry.
     int pref;
     switch (P.pref_mode) {
-        case 1: pref = blockIdx.x & 1; break;
+        case 1: pref = (blockIdx.x >> 3) & 1; break;
         case 2: pref = blockIdx.x >= (gridDim.x >> 1) ? 1 : 0; break;
-        case 3: pref = (blockIdx.x >> 3) & 1; break;
+        case 3: pref = 1; break;
         default: pref = 0; break;
     }
-    bool dry0 = false, dry1 = false;  // only thread 0 uses these
+    const int xcd = (int)(__builtin_amdgcn_s_getreg((3 << 11) | (0 << 6) | 20) & (kXcds - 1));  // HW_REG_XCC_ID
+    unsigned dry = 0;  // bit q: queue q is exhausted (only thread 0 uses it)
     for (;;) {
         if (tid == 0) {
             int idx = -1;
 #pragma unroll
             for (int attempt = 0; attempt < 2 && idx < 0; ++attempt) {
-                const int kind = attempt == 0 ? pref : 1 - pref;  // 0: MFMA queue, 1: narrow queue
-                bool& dry = kind == 0 ? dry0 : dry1;
-                if (dry) continue;
-                const int count = kind == 0 ? P.n_mfma : P.n_items - P.n_mfma;
-                const int got = (int)atomicAdd(&P.counters[kind], 1u);
-                if (got < count)
-                    idx = (kind == 0 ? 0 : P.n_mfma) + got;
-                else
-                    dry = true;
+                const bool want_narrow = (attempt == 0) == (pref == 1);
+                if (want_narrow) {
+                    if (!(dry & (1u << kNarrowQueue))) {
+                        const int got = (int)atomicAdd(&P.counters[kNarrowQueue], 1u);
+                        if (got < P.queue_begin[kNarrowQueue + 1] - P.queue_begin[kNarrowQueue])
+                            idx = P.queue_begin[kNarrowQueue] + got;
+                        else
+                            dry |= 1u << kNarrowQueue;
+                    }
+                } else {
+                    for (int a = 0; a < kXcds && idx < 0; ++a) {
+                        const int q = (xcd + a) & (kXcds - 1);
+                        if (dry & (1u << q)) continue;
+                        const int got = (int)atomicAdd(&P.counters[q], 1u);
+                        if (got < P.queue_begin[q + 1] - P.queue_begin[q])
+                            idx = P.queue_begin[q] + got;
+                        else
+                            dry |= 1u << q;
+                    }
+                }
             }
             *s_next = idx;
         }
@@ -704,11 +719,12 @@ __global__ __launch_bounds__(kThreads, 2) void ppd_mixed_kernel(const KParams P)
     }
     if (tid == 0) {
         // the last workgroup to run out of work re-arms the cursors for the next launch
-        const unsigned done = atomicAdd(&P.counters[3], 1u);
+        const unsigned done = atomicAdd(&P.counters[10], 1u);
         if (done == gridDim.x - 1) {
-            __hip_atomic_store(&P.counters[0], 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-            __hip_atomic_store(&P.counters[1], 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-            __hip_atomic_store(&P.counters[3], 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+#pragma unroll
+            for (int q = 0; q <= kNarrowQueue; ++q)
+                __hip_atomic_store(&P.counters[q], 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            __hip_atomic_store(&P.counters[10], 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
         }
     }
 }

@@ -8,6 +8,7 @@
 #include <algorithm>
 #include <cmath>
 #include <cstring>
+#include <unordered_map>
 
 #include "ppd_internal.h"
 
@@ -59,6 +60,7 @@ ppd_status build_plan(const ppd_shape& s, const int32_t* L, const int32_t* n, in
     plan->groups.clear();
     plan->units.clear();
     std::memset(&plan->stats, 0, sizeof plan->stats);
+    std::memset(plan->queue_begin, 0, sizeof plan->queue_begin);
     if (B < 0) { *err = kNeg; return PPD_ERR_RANGE; }
     if (B > 0 && (!L || !n)) { *err = kNull; return PPD_ERR_NULL; }
     if (o.narrow_chunk < 0 || o.narrow_chunk % kTileTokens || o.mfma_chunk < 0 || o.mfma_chunk % kTileTokens ||
@@ -151,14 +153,55 @@ ppd_status build_plan(const ppd_shape& s, const int32_t* L, const int32_t* n, in
         }
         grow += n[i];
     }
-    // two queues in one list: MFMA tiles first, then narrow tiles; each longest-first (stable, so the row
-    // blocks that share a key range stay adjacent and run at about the same time)
-    std::stable_sort(keyed.begin(), keyed.end(), [](const Keyed& a, const Keyed& b) {
-        if (a.it.kind != b.it.kind) return a.it.kind > b.it.kind;
-        return a.cost > b.cost;
-    });
+    // Queues.  Narrow tiles read every key once: one queue, longest first.  MFMA row-block tiles of one
+    // (sequence, KV head, key range) read the same K/V: they form a sharing group that is kept together in
+    // one of eight per-XCD queues (the workgroups of an XCD share its L2), groups spread over the queues
+    // longest-first onto the least loaded queue; inside a queue the tiles of a group stay adjacent so that they
+    // run at about the same time.
+    std::vector<Keyed> narrow_items;
+    struct Share { double cost; std::vector<ppd_work_item> items; };
+    std::vector<Share> shares;
+    {
+        std::unordered_map<uint64_t, size_t> index;
+        for (auto& k : keyed) {
+            if (k.it.kind == 0) { narrow_items.push_back(k); continue; }
+            const uint64_t key = ((uint64_t)k.it.seq * (uint64_t)Hkv + (uint64_t)k.it.kvh) * (1ull << 24) +
+                                 (uint64_t)(k.it.kv_begin / kTileTokens);
+            auto f = index.find(key);
+            if (f == index.end()) {
+                index.emplace(key, shares.size());
+                shares.push_back(Share{0.0, {}});
+                f = index.find(key);
+            }
+            shares[f->second].cost += k.cost;
+            shares[f->second].items.push_back(k.it);
+        }
+    }
+    std::stable_sort(shares.begin(), shares.end(), [](const Share& a, const Share& b) { return a.cost > b.cost; });
+    std::vector<ppd_work_item> queues[kXcds];
+    double load[kXcds] = {0};
+    for (auto& sh : shares) {
+        int q = 0;
+        for (int x = 1; x < kXcds; ++x)
+            if (load[x] < load[q]) q = x;
+        load[q] += sh.cost;
+        for (auto& it : sh.items) {
+            it.queue = q;
+            queues[q].push_back(it);
+        }
+    }
+    std::stable_sort(narrow_items.begin(), narrow_items.end(), [](const Keyed& a, const Keyed& b) { return a.cost > b.cost; });
     plan->items.reserve(keyed.size());
-    for (auto& k : keyed) plan->items.push_back(k.it);
+    for (int q = 0; q < kXcds; ++q) {
+        plan->queue_begin[q] = (int32_t)plan->items.size();
+        for (auto& it : queues[q]) plan->items.push_back(it);
+    }
+    plan->queue_begin[kNarrowQueue] = (int32_t)plan->items.size();
+    for (auto& k : narrow_items) {
+        k.it.queue = kNarrowQueue;
+        plan->items.push_back(k.it);
+    }
+    plan->queue_begin[kNarrowQueue + 1] = (int32_t)plan->items.size();
 
     ppd_plan_stats& st = plan->stats;
     st.n_items = (int64_t)plan->items.size();

@@ -100,12 +100,22 @@ def test_plan_covers_every_pair_once(opts):
         assert st.n_items == len(items) == st.n_narrow + st.n_mfma
         used = replay(items, L, n, Hkv, Hq // Hkv, D)
         assert used == st.partial_floats
-        # queues: MFMA tiles first, each queue longest-first
-        kinds = [t.kind for t in items]
-        assert kinds == sorted(kinds, reverse=True)
-        for kind in (0, 1):
-            lens = [t.kv_end - t.kv_begin for t in items if t.kind == kind]
-            assert lens == sorted(lens, reverse=True)
+        # queues: eight MFMA queues, then the narrow queue (longest first); tiles that read the same K/V
+        # (same sequence, KV head and key range) sit in one queue, next to each other
+        queues = [t.queue for t in items]
+        assert queues == sorted(queues)
+        assert all((t.kind == 0) == (t.queue == 8) for t in items)
+        lens = [t.kv_end - t.kv_begin for t in items if t.kind == 0]
+        assert lens == sorted(lens, reverse=True)
+        seen, last = set(), None
+        for t in items:
+            if t.kind == 0:
+                continue
+            key = (t.seq, t.kvh, t.kv_begin)
+            if key != last:
+                assert key not in seen, "a sharing group is split"
+                seen.add(key)
+                last = key
         b = si.make_batch("x", L=L, n=n, Hq=Hq, Hkv=Hkv, D=D, seed=0, with_data=False)
         assert st.kv_bytes == b.kv_read_bytes()
         assert abs(st.flops - b.attention_flops()) <= 1e-9 * st.flops
