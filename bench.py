@@ -153,6 +153,95 @@ def cpu_baseline(runner, budget_s=15.0):
             "max_abs_err_vs_gpu": err}
 
 
+def run_trace(torch, seed, max_steps, pool_gb):
+    """Multi-turn trace on a 70B-class GQA layer (64 q / 8 kv heads): every engine step = one KV append plus one
+    mixed attention over all active conversations, pages drawn at random from a large shared pool."""
+    import paper_2603_13358_amd as ppd
+    import synthetic_inputs as si
+    Hq, Hkv, D, P = 64, 8, 128, 16
+    steps, max_tokens = si.cfg5_trace(seed)
+    page_bytes = 2 * Hkv * P * D * 2
+    free_b, _ = torch.cuda.mem_get_info()
+    num_pages = int(min(pool_gb * 1e9, free_b * 0.9) // page_bytes)
+    rng = np.random.default_rng(9000 + seed)
+    need = (max_tokens + P - 1) // P
+    pages = rng.choice(num_pages, size=int(need.sum()), replace=False).astype(np.int32)
+    pt = np.full((len(need), int(need.max())), -1, np.int32)
+    at = 0
+    for c in range(len(need)):
+        pt[c, :need[c]] = pages[at:at + need[c]]
+        at += int(need[c])
+    dev = torch.device("cuda:0")
+    ctx = ppd.Context(Hq, Hkv, D, num_pages)
+    pool = torch.empty((num_pages * page_bytes // 2,), dtype=torch.bfloat16, device=dev)   # contents: whatever
+    # only the pages in use need defined values
+    pool.view(num_pages, -1)[torch.from_numpy(pages.astype(np.int64)).to(dev)] = 0
+    pt_d = torch.from_numpy(pt).to(dev)
+    stream = torch.cuda.current_stream().cuda_stream
+    scale = 1.0 / np.sqrt(D)
+    gen = torch.Generator(device=dev)
+    gen.manual_seed(seed)
+    rec, plan_us, first_us = [], [], []
+    if max_steps:
+        steps = steps[:max_steps]
+    t_all0 = time.perf_counter()
+    for st in steps:
+        T = int(st.n.sum())
+        k = torch.empty((T, Hkv, D), dtype=torch.bfloat16, device=dev).normal_(generator=gen)
+        v = torch.empty((T, Hkv, D), dtype=torch.bfloat16, device=dev).normal_(generator=gen)
+        slots = np.concatenate([pt[c, (np.arange(L, L + n)) // P].astype(np.int64) * P + np.arange(L, L + n) % P
+                                for c, L, n in zip(st.conv, st.L, st.n)])
+        slots_d = torch.from_numpy(slots).to(dev)
+        q = torch.empty((T, Hq, D), dtype=torch.bfloat16, device=dev).normal_(generator=gen)
+        out = torch.empty((T, Hq, D), dtype=torch.bfloat16, device=dev)
+        sub_pt = pt_d[torch.from_numpy(st.conv.astype(np.int64)).to(dev)].contiguous()
+        # "layer 0" plans and uploads (the lengths changed since the previous step); "layer 1" repeats the
+        # same append + attention with the plan already on the device, as every further layer of a model would
+        e0, e1, e2 = (torch.cuda.Event(enable_timing=True) for _ in range(3))
+        torch.cuda.synchronize()
+        e0.record()
+        ctx.kv_append(k, v, pool, slots_d, stream=stream)
+        if st.attend:
+            ctx.mixed_attention(q, pool, sub_pt, st.L, st.n, scale, out, stream=stream)
+        e1.record()
+        ctx.kv_append(k, v, pool, slots_d, stream=stream)
+        if st.attend:
+            ctx.mixed_attention(q, pool, sub_pt, st.L, st.n, scale, out, stream=stream)
+        e2.record()
+        e2.synchronize()
+        us0 = e0.elapsed_time(e1) * 1e3
+        us = e1.elapsed_time(e2) * 1e3
+        plan_us.append(ctx.plan_stats().plan_host_us if st.attend else 0)
+        first_us.append(us0)
+        kv_bytes = int((st.L + st.n).sum()) * 2 * Hkv * D * 2 if st.attend else 0
+        flops = float(4.0 * Hq * D * np.sum(st.n * st.L + st.n * (st.n + 1) / 2.0)) if st.attend else 0.0
+        rec.append((us, st.attend, int((st.n > 1).sum()), int(len(st.n)), kv_bytes, flops))
+    wall = time.perf_counter() - t_all0
+    ctx.close()
+    us = np.array([r[0] for r in rec])
+    dec = np.array([r[1] and r[2] == 0 for r in rec])
+    apm = np.array([r[1] and r[2] > 0 for r in rec])
+    land = np.array([not r[1] for r in rec])
+    kvb = np.array([r[4] for r in rec], np.float64)
+    fl = np.array([r[5] for r in rec], np.float64)
+
+    def dist(x):
+        return {"n": int(x.size), "p10": float(np.percentile(x, 10)), "p50": float(np.percentile(x, 50)),
+                "p90": float(np.percentile(x, 90)), "mean": float(x.mean())} if x.size else {"n": 0}
+    return {"steps": len(rec), "pool_pages": num_pages, "pool_GB": num_pages * page_bytes / 1e9,
+            "total_gpu_ms": float(us.sum() / 1e3), "wall_s_incl_input_generation": wall,
+            "decode_only_steps_us": dist(us[dec]), "steps_with_append_prefill_us": dist(us[apm]),
+            "first_layer_decode_only_steps_us": dist(np.array(first_us)[dec]),
+            "first_layer_steps_with_append_prefill_us": dist(np.array(first_us)[apm]),
+            "plan_host_us": dist(np.array(plan_us, np.float64)[dec | apm]),
+            "kv_landing_steps_us": dist(us[land]),
+            "decode_only_aggregate_HBM_GBs": float(kvb[dec].sum() / (us[dec].sum() * 1e-6) / 1e9) if dec.any() else None,
+            "ap_steps_aggregate_TFLOPs": float(fl[apm].sum() / (us[apm].sum() * 1e-6) / 1e12) if apm.any() else None,
+            "note": "per-step times = HIP events around kv_append + mixed_attention of one layer with the step's plan "
+                    "already on the device (every layer but the first of an engine step); first_layer_* include "
+                    "planning and upload; 70B-class layer 64q/8kv heads, D=128"}
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -164,6 +253,9 @@ def main():
     ap.add_argument("--no-extras", action="store_true", help="time the chosen workload only")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle leg")
     ap.add_argument("--opt", action="append", default=[], help="library option key=value (tuning sweeps)")
+    ap.add_argument("--trace", action="store_true", help="run the multi-turn conversation trace (cfg5) and exit")
+    ap.add_argument("--trace-steps", type=int, default=0, help="limit the trace to its first N engine steps")
+    ap.add_argument("--trace-pool-gb", type=float, default=200.0)
     ap.add_argument("--copy-probe", action="store_true",
                     help="run a plain 1 GiB device copy a few times and exit (calibrates HBM byte counters)")
     args = ap.parse_args()
@@ -173,6 +265,10 @@ def main():
     if not torch.cuda.is_available():
         raise SystemExit("bench.py needs an MI355X: the library has no CPU path")
     options = {kv.split("=")[0]: int(kv.split("=")[1]) for kv in args.opt}
+    if args.trace:
+        print(json.dumps({"workload": "cfg5_multi_turn_trace", "trace": run_trace(torch, args.seed, args.trace_steps,
+                                                                                 args.trace_pool_gb)}))
+        return
     if args.copy_probe:
         nbytes = 1 << 30
         src = torch.arange(nbytes // 4, dtype=torch.int32, device="cuda:0")
