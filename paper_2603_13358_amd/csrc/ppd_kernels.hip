@@ -80,16 +80,6 @@ __device__ __forceinline__ float sum_halves(float v) {
 
 // The running maximum is only raised (and the accumulators rescaled) when it would grow by more than this many
 // powers of two; until then probabilities may exceed 1, by at most 2^kLazyRescale.  The final o / l is unchanged.
-// Scheduling-barrier mask: vector ALU, scalar ALU and transcendental instructions may move across, matrix and
-// LDS instructions may not (keeps operand reads a whole group ahead of the MFMAs that consume them).
-#define kSchedVectorOnly (0x2 | 0x4 | 0x400)
-
-#ifndef PPD_NO_SCHED_FENCE
-#define PPD_SCHED_FENCE() __builtin_amdgcn_sched_barrier(0)
-#else
-#define PPD_SCHED_FENCE() do {} while (0)
-#endif
-
 #ifndef kLazyRescale
 #define kLazyRescale 8.0f
 #endif
@@ -261,11 +251,6 @@ __device__ __forceinline__ void mfma_item(const KParams& P, const ppd_work_item&
     const int k_lane_off = (l32 >> 4) * PB + k_tok * 16 + h * 256;  // + stage + tb*2*PB + ks*512
     const int v_lane_off = VRING + (h * HD + l32) * 16;             // + stage + s*PB + db*512
 
-    // S^T of one tile, all k-steps (used for tile 0 only; later tiles are computed inside the loop, a quarter
-    // per step).  Fragment f = 2*ks + tb of the K tile feeds MFMA f.
-    auto k_frag = [&](const char* kb, int f) {
-        return *reinterpret_cast<const u32x4*>(kb + (f & 1) * 2 * PB + (f >> 1) * 512);
-    };
     auto qk_tile = [&](int stage, f32x16 (&sacc)[2]) {
         const char* kb = smem + stage * KBYTES + k_lane_off;
 #pragma unroll
@@ -273,8 +258,12 @@ __device__ __forceinline__ void mfma_item(const KParams& P, const ppd_work_item&
 #pragma unroll
             for (int i = 0; i < 16; ++i) sacc[tb][i] = 0.f;
 #pragma unroll
-        for (int f = 0; f < 2 * KS; ++f)
-            sacc[f & 1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(as_bf16x8(k_frag(kb, f)), qreg[f >> 1], sacc[f & 1], 0, 0, 0);
+        for (int ks = 0; ks < KS; ++ks)
+#pragma unroll
+            for (int tb = 0; tb < 2; ++tb) {
+                bf16x8 a = as_bf16x8(*reinterpret_cast<const u32x4*>(kb + tb * 2 * PB + ks * 512));
+                sacc[tb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, qreg[ks], sacc[tb], 0, 0, 0);
+            }
     };
 
     // prologue: K(0..NS-1) and V(0..NS-2) are issued, K(0), K(1), V(0) must land; S^T of tile 0
@@ -299,48 +288,20 @@ __device__ __forceinline__ void mfma_item(const KParams& P, const ppd_work_item&
     for (int t = 0; t < NS - 1; ++t)
         if (t < ntiles) fix_v_tail(t, VRING + t * KBYTES);
     lds_barrier();
-    f32x16 s_a[2], s_b[2];
-    if (wave_active) qk_tile(0, s_a);
+    f32x16 s_cur[2], s_nxt[2];
+    if (wave_active) qk_tile(0, s_cur);
     lds_barrier();  // K stage 0 is overwritten by the first iteration's loads
     int st_cur = 0;   // ti % NS
 
     PPD_TICK_DECL();
-    // One iteration = one key tile.  `cur` holds S^T of tile ti (computed one iteration earlier), `nxt`
-    // receives S^T of tile ti+1.  The body is four steps; step s turns the 8 scores per lane of page s into
-    // probabilities (vector pipe), then issues the PV MFMAs of page s and a quarter of the QK MFMAs of the next
-    // tile (matrix pipe), then reads the LDS operands of step s+1.  Alternating chunks of comparable length
-    // let the two waves that share a SIMD keep both pipes busy.
-    auto iteration = [&](int ti, f32x16 (&cur)[2], f32x16 (&nxt)[2]) {
+    for (int ti = 0; ti < ntiles; ++ti) {
         const int st_nxt = st_cur + 1 == NS ? 0 : st_cur + 1;            // (ti + 1) % NS
         const int st_prv = st_cur == 0 ? NS - 1 : st_cur - 1;            // (ti + NS - 1) % NS
         const bool full_issue = ti + NS < ntiles;
-        // The tile loads of this iteration are issued behind the matrix chunks of steps 0 and 1, where their
-        // address arithmetic runs while the MFMAs execute (V first: the memory counter wait below relies on
-        // the order V, K).
-        auto issue_v = [&]() {
-            if (ti + NS - 1 < ntiles) load_block(tile_pages(ti + NS - 1), VRING + st_prv * KBYTES, v_off);
-        };
-        auto issue_k = [&]() {
-            if (full_issue) load_block(tile_pages(ti + NS), st_cur * KBYTES, 0);
-        };
-        if (!wave_active) {
-            issue_v();
-            issue_k();
-        }
+        if (ti + NS - 1 < ntiles) load_block(tile_pages(ti + NS - 1), VRING + st_prv * KBYTES, v_off);
+        if (full_issue) load_block(tile_pages(ti + NS), st_cur * KBYTES, 0);
         PPD_TICK(0);
         if (wave_active) {
-            const bool has_next = ti + 1 < ntiles;
-            const char* kb = smem + st_nxt * KBYTES + k_lane_off;
-            const char* vb = smem + st_cur * KBYTES + v_lane_off;
-            constexpr int QPS = 2 * KS / 4;  // QK MFMAs per step
-            u32x4 kf[QPS], vf[DB];
-            auto load_step = [&](int sidx) {
-#pragma unroll
-                for (int db = 0; db < DB; ++db) vf[db] = *reinterpret_cast<const u32x4*>(vb + sidx * PB + db * 512);
-#pragma unroll
-                for (int j = 0; j < QPS; ++j) kf[j] = k_frag(kb, sidx * QPS + j);
-            };
-            load_step(0);
             const int tile_base = it.kv_begin + ti * kTileTokens;
             if (tile_base + kTileTokens - 1 > wmin_limit) {  // causal boundary crosses this tile
 #pragma unroll
@@ -348,14 +309,14 @@ __device__ __forceinline__ void mfma_item(const KParams& P, const ppd_work_item&
 #pragma unroll
                     for (int i = 0; i < 16; ++i) {
                         const int pos = tile_base + (tb * 2 + (i >> 3)) * 16 + h * 8 + (i & 7);
-                        if (pos > limit) cur[tb][i] = NEG_INF;
+                        if (pos > limit) s_cur[tb][i] = NEG_INF;
                     }
             }
-            float mx = cur[0][0];
+            float mx = s_cur[0][0];
 #pragma unroll
             for (int tb = 0; tb < 2; ++tb)
 #pragma unroll
-                for (int i = 0; i < 16; ++i) mx = fmaxf(mx, cur[tb][i]);
+                for (int i = 0; i < 16; ++i) mx = fmaxf(mx, s_cur[tb][i]);
             mx = max_halves(mx);
             const float m_new = fmaxf(m_run, mx);
             if (__any((m_new - m_run) * c > kLazyRescale)) {  // -inf -> finite counts; -inf -> -inf does not
@@ -370,44 +331,35 @@ __device__ __forceinline__ void mfma_item(const KParams& P, const ppd_work_item&
             }
             const float mc = m_run == NEG_INF ? 0.f : m_run * c;
             PPD_TICK(1);
+            // S^T of the next tile (matrix pipe) next to the exponentials of this one (vector pipe)
+            if (ti + 1 < ntiles) qk_tile(st_nxt, s_nxt);
+            PPD_TICK(2);
+            const char* vb = smem + st_cur * KBYTES + v_lane_off;
+            float psum = 0.f;
 #pragma unroll
             for (int tb = 0; tb < 2; ++tb)
 #pragma unroll
-                for (int i = 0; i < 16; ++i) nxt[tb][i] = 0.f;
-            float psum = 0.f;
+                for (int i = 0; i < 16; ++i) {
+                    const float p = fast_exp2(__builtin_fmaf(s_cur[tb][i], c, -mc));
+                    s_cur[tb][i] = p;
+                    psum += p;
+                }
+            l_run += psum;
 #pragma unroll
             for (int s = 0; s < 4; ++s) {
-                // vector chunk: probabilities of page s
                 u32x4 pw;
 #pragma unroll
-                for (int e = 0; e < 4; ++e) {
-                    const int i0 = (s & 1) * 8 + 2 * e;
-                    const float p0 = fast_exp2(__builtin_fmaf(cur[s >> 1][i0], c, -mc));
-                    const float p1 = fast_exp2(__builtin_fmaf(cur[s >> 1][i0 + 1], c, -mc));
-                    psum += p0 + p1;
-                    pw[e] = pack_bf16(p0, p1);
-                }
+                for (int e = 0; e < 4; ++e)
+                    pw[e] = pack_bf16(s_cur[s >> 1][(s & 1) * 8 + 2 * e], s_cur[s >> 1][(s & 1) * 8 + 2 * e + 1]);
                 const bf16x8 pb = as_bf16x8(pw);
-                PPD_SCHED_FENCE();
-                // matrix chunk
 #pragma unroll
-                for (int db = 0; db < DB; ++db)
-                    oacc[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(as_bf16x8(vf[db]), pb, oacc[db], 0, 0, 0);
-                if (has_next) {
-#pragma unroll
-                    for (int j = 0; j < QPS; ++j) {
-                        const int f = s * QPS + j;
-                        nxt[f & 1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(as_bf16x8(kf[j]), qreg[f >> 1], nxt[f & 1], 0, 0, 0);
-                    }
+                for (int db = 0; db < DB; ++db) {
+                    bf16x8 a = as_bf16x8(*reinterpret_cast<const u32x4*>(vb + s * PB + db * 512));
+                    oacc[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, pb, oacc[db], 0, 0, 0);
                 }
-                PPD_SCHED_FENCE();
-                if (s + 1 < 4) load_step(s + 1);
-                if (s == 0) issue_v();
-                if (s == 1) issue_k();
-                PPD_SCHED_FENCE();
             }
-            l_run += psum;
-            PPD_TICK(2);
+#pragma unroll
+            for (int tb = 0; tb < 2; ++tb) s_cur[tb] = s_nxt[tb];
         }
         PPD_TICK(3);
         // K(ti+2) and V(ti+1) must have landed; with NS = 3 the loads issued in this iteration may stay in flight
@@ -420,10 +372,6 @@ __device__ __forceinline__ void mfma_item(const KParams& P, const ppd_work_item&
         PPD_TICK(4);
         lds_barrier();
         PPD_TICK(5);
-    };
-    for (int ti = 0; ti < ntiles; ti += 2) {  // unrolled by two so that the two S^T register sets swap roles
-        iteration(ti, s_a, s_b);
-        if (ti + 1 < ntiles) iteration(ti + 1, s_b, s_a);
     }
     PPD_TICK_FLUSH(P);
 
