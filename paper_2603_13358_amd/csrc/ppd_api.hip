@@ -163,7 +163,7 @@ ppd_status ppd_set_option(ppd_ctx* ctx, const char* key, int64_t value) {
     if (k == "narrow_chunk" || k == "mfma_chunk") {
         if (value < 0 || value % ppd::kTileTokens || value > (1 << 30) ||
             (k == "mfma_chunk" && value > ppd::kMaxMfmaChunk))
-            return fail(ctx, PPD_ERR_RANGE, k + " must be 0 or a positive multiple of 64 (mfma_chunk at most 8192)");
+            return fail(ctx, PPD_ERR_RANGE, k + " must be 0 or a positive multiple of 64 (mfma_chunk at most 32768)");
         (k == "narrow_chunk" ? ctx->opts.narrow_chunk : ctx->opts.mfma_chunk) = (int32_t)value;
     } else if (k == "grid") {
         if (value < 0 || value > 65536) return fail(ctx, PPD_ERR_RANGE, "grid must be in [0, 65536]");

@@ -119,8 +119,8 @@ __device__ __forceinline__ u32x4 zero_unwritten(u32x4 v, int first, int kv_total
 }
 
 // ---------------------------------------------------------------------------------------------------
-// MFMA row-block tile: up to 128 query columns (rows x G heads of one KV head) against keys
-// [kv_begin, kv_end).  4 waves x 32 columns; key tiles of 64 tokens (4 pages); v_mfma_f32_32x32x16_bf16 for
+// MFMA row-block tile: up to kMfmaCols query columns (rows x G heads of one KV head) against keys
+// [kv_begin, kv_end).  kWaves waves x 32 columns; key tiles of 64 tokens (4 pages); v_mfma_f32_32x32x16_bf16 for
 // both products.  K and V tiles go from the pool straight into LDS (global_load_lds, 16 bytes per lane, no
 // staging registers), each in a ring of kStages stages.  The loop is software-pipelined: iteration i
 // computes S^T of tile i+1 while it runs the softmax and the PV product of tile i, so that matrix and
@@ -183,8 +183,8 @@ __device__ __forceinline__ void mfma_item(const KParams& P, const ppd_work_item&
     const int64_t head_off = (int64_t)it.kvh * (kPage * HD);
     const int64_t v_off = (int64_t)P.Hkv * (kPage * HD);
 
-    // Page ids of the whole key range go to LDS once, checked, before the loop (at most 512: the planner
-    // caps a row-block tile at 8192 keys); a tile reads its four ids with one broadcast LDS read.  Nothing in
+    // Page ids of the whole key range go to LDS once, checked, before the loop (at most 2048: the planner
+    // caps a row-block tile at kMaxMfmaChunk keys); a tile reads its four ids with one broadcast LDS read.  Nothing in
     // the loop then depends on a page-table load, so no wait on the memory counter is needed there.
     struct TilePages { int p[4]; };
     int* lds_ids = reinterpret_cast<int*>(smem + 2 * NS * KBYTES);
@@ -788,7 +788,7 @@ __global__ __launch_bounds__(kSmallThreads) void ppd_kv_append_kernel(const uint
 
 // ---------------------------------------------------------------------------------------------------
 static size_t mixed_lds_bytes(int head_dim) {
-    const size_t rings = (size_t)2 * kStages * 4 * kPage * head_dim * 2 + 2048;  // + page ids of one tile
+    const size_t rings = (size_t)2 * kStages * 4 * kPage * head_dim * 2 + (kMaxMfmaChunk / kPage) * 4;  // + page ids of one row-block tile
     const size_t combine = (size_t)kWaves * kNarrowCols * (head_dim + 2) * sizeof(float);
     return rings > combine ? rings : combine;
 }

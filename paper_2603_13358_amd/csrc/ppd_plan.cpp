@@ -53,7 +53,7 @@ ppd_status build_plan(const ppd_shape& s, const int32_t* L, const int32_t* n, in
     static const char* kNull = "L / n is NULL";
     static const char* kNeg = "n_i must be >= 1 and L_i >= 0";
     static const char* kBig = "L_i + n_i and the total row count must stay below 2^30";
-    static const char* kChunk = "chunk options must be 0 or a positive multiple of 64 (mfma_chunk <= 8192); grid >= 0";
+    static const char* kChunk = "chunk options must be 0 or a positive multiple of 64 (mfma_chunk <= 32768); grid >= 0";
     const char* dummy;
     if (!err) err = &dummy;
     plan->items.clear();
@@ -87,12 +87,15 @@ ppd_status build_plan(const ppd_shape& s, const int32_t* L, const int32_t* n, in
     // Total cost in "token units": a narrow tile costs its tokens, an MFMA tile twice its tokens (rough
     // ratio of time per key at the rates the two paths reach; only the order of tiles depends on it).
     double cost_total = 0;
+    int64_t mfma_units = 0;  // (row block, KV head) pairs
     for (int i = 0; i < B; ++i) {
         if (is_narrow(i)) {
             cost_total += (double)Hkv * (L[i] + n[i]);
         } else {
-            for (int r0 = 0; r0 < n[i]; r0 += rows_per_block)
+            for (int r0 = 0; r0 < n[i]; r0 += rows_per_block) {
                 cost_total += 2.0 * Hkv * (L[i] + std::min<int64_t>(n[i], r0 + rows_per_block));
+                mfma_units += Hkv;
+            }
         }
     }
     const int slots = o.grid > 0 ? o.grid : kWgPerCu * o.num_cus;  // resident workgroups
@@ -102,7 +105,10 @@ ppd_status build_plan(const ppd_shape& s, const int32_t* L, const int32_t* n, in
                                : std::min<int64_t>(8192, std::max<int64_t>(256, round_up((int64_t)per_item, kTileTokens)));
     int64_t mfma_chunk = o.mfma_chunk > 0
                              ? o.mfma_chunk
-                             : std::min<int64_t>(kMaxMfmaChunk, std::max<int64_t>(512, round_up((int64_t)(per_item / 2), kTileTokens)));
+                             : std::min<int64_t>(8192, std::max<int64_t>(512, round_up((int64_t)(per_item / 2), kTileTokens)));
+    // Every split costs a partial (fp32 o, m, l per column) written and read back by the merge.  With many
+    // row blocks per workgroup the queue balances without splitting: keep each row block's key range whole.
+    if (o.mfma_chunk == 0 && mfma_units >= 16LL * slots) mfma_chunk = kMaxMfmaChunk;
 
     struct Keyed { double cost; ppd_work_item it; };
     std::vector<Keyed> keyed;

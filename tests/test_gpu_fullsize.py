@@ -86,3 +86,33 @@ def test_cfg4_full_prefill_variant_full_size():
         dec = sorted([i for i in range(b.B) if b.n[i] == 1], key=lambda i: int(b.L[i]))
         return [dec[len(dec) // 2], full[0]]
     _run_and_check("cfg4_mixed_full", pick, rows_per_seq=5)
+
+
+def test_long_context_single_sequences():
+    """Largest shapes of the context sweep the paper reports (64K-token contexts, appendix on context-length
+    sensitivity) and beyond: one 131072-token decode, one append-prefill of 300 tokens over 100000 cached
+    tokens, one 70000-token decode whose last page is partial."""
+    import torch
+    import paper_2603_13358_amd as ppd
+    b = si.make_batch("long", L=[131071, 100000, 70003], n=[1, 300, 1], Hq=32, Hkv=8, D=128, seed=31,
+                      slack_pages=9, with_data=False)
+    dev = torch.device("cuda:0")
+    w = si.device_workload(b, torch, dev, seed=4)
+    ctx = ppd.Context(b.Hq, b.Hkv, b.D, b.num_pages)
+    ctx.kv_append(w["k_new"], w["v_new"], w["pool"], w["slots"])
+    ctx.mixed_attention(w["q"], w["pool"], w["page_tables"], b.L, b.n, b.scale, w["out"])
+    torch.cuda.synchronize()
+    assert ctx.device_error_flags() == 0
+    st = ctx.plan_stats()
+    print("  tiles", st.n_items, "narrow", st.n_narrow, "mfma", st.n_mfma, "groups", st.n_groups, flush=True)
+    sub, pool, rows = si.compact_subbatch(b, [0, 1, 2], w["pool"], w["q"], torch)
+    mask = np.zeros(sub.T, np.uint8)
+    mask[[0, 1, 150, 300, 301]] = 1            # the decode rows, first / middle / last append-prefill rows
+    ref = oracle.mixed_attention(sub.q, pool, sub.page_tables, sub.L, sub.n, sub.Hq, sub.Hkv, sub.D, sub.P,
+                                 sub.num_pages, sub.scale, row_mask=mask)
+    got = w["out"].float().cpu().numpy()[rows]
+    sel = mask.astype(bool)
+    worst = check_close(got[sel], ref[sel])
+    print("  max-abs %.3e" % worst, flush=True)
+    assert bool(torch.isfinite(w["out"].float()).all())
+    ctx.close()
