@@ -91,15 +91,6 @@ __device__ __forceinline__ int load_page_id(const int32_t* pt_row, int pi, int l
     return pt_row[pi];
 }
 
-// Same for a wave-uniform pi: the page table is not written while the kernel runs, so it is read through the
-// constant address space, which lets a uniform address become a scalar load that nobody has to wait for
-// until the value is used.
-typedef const int32_t __attribute__((address_space(4))) * const_i32_ptr;
-__device__ __forceinline__ int load_page_id_uniform(const int32_t* pt_row, int pi, int last_page) {
-    pi = pi < last_page ? pi : last_page;
-    return reinterpret_cast<const_i32_ptr>(reinterpret_cast<uintptr_t>(pt_row))[pi];
-}
-
 // Checks a page id at the point of use: an id outside the pool raises the sticky flag and is replaced by
 // page 0, so that no access leaves the pool.
 __device__ __forceinline__ int64_t checked_page(const KParams& P, int page) {
