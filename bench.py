@@ -242,6 +242,48 @@ def run_trace(torch, seed, max_steps, pool_gb):
                     "planning and upload; 70B-class layer 64q/8kv heads, D=128"}
 
 
+def run_sweeps(torch, seed, steps, options):
+    """Attention-level analogues of the paper's interference experiments (section 4.1 and its appendix): a decode
+    batch co-located with append-prefill or with a full prefill of equal context, over batch size, over context
+    length, with 4 concurrent prefills, and with the append-prefill fed in token-budgeted chunks."""
+    import synthetic_inputs as si
+
+    def time_batch(L, n):
+        b = si.make_batch("sweep", L=L, n=n, Hq=32, Hkv=8, D=128, seed=seed, slack_pages=16, with_data=False)
+        r = Runner(b, torch, seed, options)
+        ms = r.time_steps(steps, 2)
+        r.close()
+        return ms * 1e3
+
+    def trio(dec_L, ap_L, ap_n, n_prefill=1):
+        dec_L = list(dec_L)
+        base = time_batch(dec_L, [1] * len(dec_L))
+        with_ap = time_batch(dec_L + [ap_L] * n_prefill, [1] * len(dec_L) + [ap_n] * n_prefill)
+        with_full = time_batch(dec_L + [0] * n_prefill, [1] * len(dec_L) + [ap_L + ap_n] * n_prefill)
+        return {"decode_only_us": base, "with_append_prefill_us": with_ap, "with_full_prefill_us": with_full,
+                "slowdown_append": with_ap / base - 1.0, "slowdown_full": with_full / base - 1.0}
+
+    rng = np.random.default_rng(seed)
+    out = {"setup": "32q/8kv heads, D=128; decode sequences at the stated context; one co-located prefill adds "
+                    "1024 new tokens either over the cached context (append) or recomputing it (full, L=0)"}
+    out["batch_size_sweep_ctx4096"] = {str(bs): trio([4096] * bs, 4096, 1024) for bs in (16, 64, 128, 200, 256)}
+    out["four_prefills_batch200_ctx4096"] = trio([4096] * 200, 4096, 1024, n_prefill=4)
+    out["context_sweep_batch128"] = {str(c): trio([c] * 128, c, 1024) for c in (2048, 8192, 16384, 32768, 65536)}
+    # chunked append-prefill: 2048 new tokens over 16384 cached, fed in chunks next to 128 decodes at 8192
+    dec = [8192] * 128
+    base = time_batch(dec, [1] * 128)
+    chunked = {}
+    for chunk in (128, 256, 512, 1024, 2048):
+        per_step = []
+        for c0 in range(0, 2048, chunk):
+            per_step.append(time_batch(dec + [16384 + c0], [1] * 128 + [chunk]))
+        chunked[str(chunk)] = {"steps": len(per_step), "mean_step_us": float(np.mean(per_step)),
+                               "decode_step_slowdown": float(np.mean(per_step)) / base - 1.0,
+                               "total_us_until_prefill_done": float(np.sum(per_step))}
+    out["chunked_append_prefill"] = {"decode_only_us": base, "by_chunk_tokens": chunked}
+    return out
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -256,6 +298,8 @@ def main():
     ap.add_argument("--trace", action="store_true", help="run the multi-turn conversation trace (cfg5) and exit")
     ap.add_argument("--trace-steps", type=int, default=0, help="limit the trace to its first N engine steps")
     ap.add_argument("--trace-pool-gb", type=float, default=200.0)
+    ap.add_argument("--sweeps", action="store_true",
+                    help="interference sweeps (batch size, context, 4 prefills, chunked append-prefill) and exit")
     ap.add_argument("--copy-probe", action="store_true",
                     help="run a plain 1 GiB device copy a few times and exit (calibrates HBM byte counters)")
     args = ap.parse_args()
@@ -268,6 +312,10 @@ def main():
     if args.trace:
         print(json.dumps({"workload": "cfg5_multi_turn_trace", "trace": run_trace(torch, args.seed, args.trace_steps,
                                                                                  args.trace_pool_gb)}))
+        return
+    if args.sweeps:
+        print(json.dumps({"workload": "interference_sweeps", "sweeps": run_sweeps(torch, args.seed, max(3, args.steps // 4),
+                                                                                  options)}))
         return
     if args.copy_probe:
         nbytes = 1 << 30

@@ -202,3 +202,40 @@ def test_host_argument_errors_enqueue_nothing():
         with pytest.raises(ppd.PPDError) as e:
             ppd.ppd_create(*shape)
         assert e.value.status == code
+
+
+def test_chunked_append_prefill_equals_one_shot():
+    """An append-prefill fed in chunks over several steps (token-budgeted steps, as chunked-prefill schedulers
+    do; the paper's related work, section 2.2) gives the rows of the one-shot append-prefill: each chunk is an
+    append-prefill whose cached length is everything before it."""
+    import torch
+    import paper_2603_13358_amd as ppd
+    from gpu_helpers import from_dev_u16, to_dev_u16
+    b = si.make_batch("chunks", L=[700, 90], n=[300, 300], Hq=32, Hkv=8, D=128, seed=41, slack_pages=2)
+    ref = oracle_out(b)
+    dev = torch.device("cuda:0")
+    ctx = ppd.Context(b.Hq, b.Hkv, b.D, b.num_pages)
+    pool = torch.zeros((ctx.pool_elems(),), dtype=torch.int16, device=dev)
+    k, v, slots = b.cached_part()
+    ctx.kv_append(to_dev_u16(k, torch, dev), to_dev_u16(v, torch, dev), pool, torch.from_numpy(slots).to(dev))
+    pt = torch.from_numpy(b.page_tables).to(dev)
+    done = np.zeros(2, np.int32)
+    for chunk in (64, 100, 136):
+        ks, vs, ss, qs = [], [], [], []
+        for i in range(2):
+            kk, vv = b.seq_kv(i)
+            a = int(b.L[i] + done[i])
+            ks.append(kk[a:a + chunk]); vs.append(vv[a:a + chunk]); ss.append(b.slots(i, a, a + chunk))
+            r0 = int(b.row_off[i] + done[i])
+            qs.append(b.q[r0:r0 + chunk])
+        ctx.kv_append(to_dev_u16(np.concatenate(ks), torch, dev), to_dev_u16(np.concatenate(vs), torch, dev), pool,
+                      torch.from_numpy(np.concatenate(ss)).to(dev))
+        out = torch.zeros((2 * chunk, b.Hq, b.D), dtype=torch.int16, device=dev)
+        ctx.mixed_attention(to_dev_u16(np.concatenate(qs), torch, dev), pool, pt, b.L + done, [chunk, chunk], b.scale, out)
+        got = bits_to_f32(from_dev_u16(out).reshape(2 * chunk, b.Hq, b.D))
+        for i in range(2):
+            r0 = int(b.row_off[i] + done[i])
+            check_close(got[i * chunk:(i + 1) * chunk], ref[r0:r0 + chunk])
+        done += chunk
+    assert ctx.device_error_flags() == 0
+    ctx.close()
