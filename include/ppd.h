@@ -123,6 +123,23 @@ ppd_status ppd_set_option(ppd_ctx *ctx, const char *key, int64_t value);
 ppd_status ppd_kv_append(ppd_ctx *ctx, const void *k, const void *v, void *kv_pages,
                          const int64_t *slot_mapping, int64_t T, void *stream);
 
+/* KV landing: the turn-1 side of a decode node.  The KV of a whole request, computed on a prefill node, arrives
+ * for all layers at once and is scattered into each layer's page pool (paper section 4.2: KV is transferred on
+ * turn 1 only; appendix "Bandwidth Simulation" for the sizes: 128 KiB per token over 32 layers).  Same semantics
+ * as num_layers calls of ppd_kv_append in one launch:
+ *   k, v                device bf16 [num_layers][T][Hkv][D], contiguous
+ *   kv_pages            device: pool of layer 0; pool of layer l starts layer_stride_elems * l elements later
+ *                       (layer_stride_elems >= elements of one pool)
+ *   slot_mapping        device int64 [T], shared by all layers (a request uses the same pages in every layer) */
+ppd_status ppd_kv_land(ppd_ctx *ctx, const void *k, const void *v, void *kv_pages, int64_t layer_stride_elems,
+                       int32_t num_layers, const int64_t *slot_mapping, int64_t T, void *stream);
+
+/* Extra delay that emulates a slower interconnect for a KV transfer (paper appendix "Bandwidth Simulation",
+ * its equation for the injected delay): max(0, n_tokens * kv_bytes_per_token / beta_target - t_fast), seconds.
+ * Host arithmetic only; returns -1 for invalid arguments. */
+double ppd_transfer_delay_s(int64_t n_tokens, int64_t kv_bytes_per_token, double beta_target_bytes_per_s,
+                            double t_fast_s);
+
 /* Mixed-batch paged attention (paper section 4.1 for append-prefill and full prefill, section 2.1 for
  * decode; the co-batching of the two is the interference experiment of section 4.1).
  *   q, out        device bf16 [T][Hq][D], T = sum n_i, rows grouped by sequence in batch order

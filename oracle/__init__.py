@@ -35,6 +35,10 @@ def _load():
         lib.ppd_oracle_mixed_attention.argtypes = [vp, vp, vp, i32, vp, vp, i32, i32, i32, i32, i32, i64,
                                                    ctypes.c_float, vp, vp]
         lib.ppd_oracle_mixed_attention.restype = i32
+        lib.ppd_oracle_kv_land.argtypes = [vp, vp, vp, i64, i32, vp, i64, i32, i32, i32, i64]
+        lib.ppd_oracle_kv_land.restype = i32
+        lib.ppd_oracle_transfer_delay.argtypes = [ctypes.c_double] * 4
+        lib.ppd_oracle_transfer_delay.restype = ctypes.c_double
         _lib = lib
     return _lib
 
@@ -58,6 +62,26 @@ def kv_append(k, v, pool, slot_mapping, Hkv, D, P, num_pages):
     rc = _load().ppd_oracle_kv_append(_ptr(k), _ptr(v), _ptr(pool), _ptr(slot_mapping), T, Hkv, D, P, num_pages)
     if rc != 0:
         raise ValueError("oracle kv_append: slot outside the pool")
+
+
+def kv_land(k, v, pools, layer_stride, layers, slot_mapping, Hkv, D, P, num_pages):
+    """In-place landing of k, v ([layers, T, Hkv, D] uint16) into `layers` pools laid out layer_stride apart."""
+    k = np.ascontiguousarray(k, dtype=np.uint16)
+    v = np.ascontiguousarray(v, dtype=np.uint16)
+    slot_mapping = np.ascontiguousarray(slot_mapping, dtype=np.int64)
+    T = slot_mapping.shape[0]
+    assert k.shape == (layers, T, Hkv, D) and v.shape == k.shape
+    assert pools.dtype == np.uint16 and pools.flags.c_contiguous
+    assert layer_stride >= pool_elems(num_pages, Hkv, D, P) and pools.size >= layer_stride * (layers - 1) + pool_elems(
+        num_pages, Hkv, D, P)
+    rc = _load().ppd_oracle_kv_land(_ptr(k), _ptr(v), _ptr(pools), layer_stride, layers, _ptr(slot_mapping), T, Hkv, D,
+                                    P, num_pages)
+    if rc != 0:
+        raise ValueError("oracle kv_land: slot outside the pool")
+
+
+def transfer_delay(n_tokens, s_kv_bytes, beta_target, t_fast):
+    return float(_load().ppd_oracle_transfer_delay(float(n_tokens), float(s_kv_bytes), float(beta_target), float(t_fast)))
 
 
 def mixed_attention(q, pool, page_tables, L, n, Hq, Hkv, D, P, num_pages, scale, row_mask=None, threads=None):

@@ -66,6 +66,26 @@ int ppd_oracle_kv_append(const uint16_t *k, const uint16_t *v, uint16_t *pool, c
     return 0;
 }
 
+/* KV landing: the same append for every layer of a transferred request (paper section 4.2: KV moves to the
+ * decode node on turn 1; appendix "Bandwidth Simulation": the footprint is tokens x bytes-per-token over all
+ * layers).  k, v: [layers][T][Hkv][D]; pool of layer l starts layer_stride elements after that of layer l-1. */
+int ppd_oracle_kv_land(const uint16_t *k, const uint16_t *v, uint16_t *pools, int64_t layer_stride, int layers,
+                       const int64_t *slot_mapping, int64_t T, int Hkv, int D, int P, int64_t num_pages) {
+    for (int l = 0; l < layers; ++l) {
+        int rc = ppd_oracle_kv_append(k + (int64_t)l * T * Hkv * D, v + (int64_t)l * T * Hkv * D,
+                                      pools + (int64_t)l * layer_stride, slot_mapping, T, Hkv, D, P, num_pages);
+        if (rc != 0) return rc;
+    }
+    return 0;
+}
+
+/* Injected delay that emulates a slower interconnect (paper appendix "Bandwidth Simulation", the equation for
+ * the simulated delay): max(0, B / beta_target - t_fast) with B = n_tokens * s_kv. */
+double ppd_oracle_transfer_delay(double n_tokens, double s_kv_bytes, double beta_target, double t_fast) {
+    double d = n_tokens * s_kv_bytes / beta_target - t_fast;
+    return d > 0.0 ? d : 0.0;
+}
+
 /* Mixed-batch attention.  q, out: [T][Hq][D] with the rows of sequence i starting at sum_{j<i} n_j.
  * row_mask (may be NULL): compute only rows with row_mask[r] != 0, leave the others untouched.
  * out is fp32 (rounded once from the double result).  Returns 0, or a negative code for an invalid

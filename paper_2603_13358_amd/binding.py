@@ -39,7 +39,8 @@ class PlanStats(ctypes.Structure):
         return {f: getattr(self, f) for f, _ in self._fields_ if f != "reserved"}
 
 
-EXPORTS = ["ppd_create", "ppd_destroy", "ppd_last_error", "ppd_set_option", "ppd_kv_append", "ppd_mixed_attention",
+EXPORTS = ["ppd_create", "ppd_destroy", "ppd_last_error", "ppd_set_option", "ppd_kv_append", "ppd_kv_land",
+           "ppd_transfer_delay_s", "ppd_mixed_attention",
            "ppd_get_plan_stats", "ppd_plan_build", "ppd_device_error_flags", "ppd_last_kernel_ms", "ppd_debug_counters",
            "ppd_version"]
 
@@ -64,6 +65,9 @@ def load_library():
     lib.ppd_last_error.restype = ctypes.c_char_p
     lib.ppd_set_option.argtypes = [vp, ctypes.c_char_p, i64]
     lib.ppd_kv_append.argtypes = [vp, vp, vp, vp, vp, i64, vp]
+    lib.ppd_kv_land.argtypes = [vp, vp, vp, vp, i64, i32, vp, i64, vp]
+    lib.ppd_transfer_delay_s.argtypes = [i64, i64, ctypes.c_double, ctypes.c_double]
+    lib.ppd_transfer_delay_s.restype = ctypes.c_double
     lib.ppd_mixed_attention.argtypes = [vp, vp, vp, vp, i32, vp, vp, i32, ctypes.c_float, vp, vp]
     lib.ppd_get_plan_stats.argtypes = [vp, ctypes.POINTER(PlanStats)]
     lib.ppd_plan_build.argtypes = [ctypes.POINTER(Shape), vp, vp, i32, i32, i32, i32, i32, i32,
@@ -74,7 +78,7 @@ def load_library():
     lib.ppd_version.argtypes = []
     lib.ppd_version.restype = ctypes.c_char_p
     for name in EXPORTS:
-        if name not in ("ppd_last_error", "ppd_version"):
+        if name not in ("ppd_last_error", "ppd_version", "ppd_transfer_delay_s"):
             getattr(lib, name).restype = i32
     _lib = lib
     return lib
@@ -126,6 +130,18 @@ def ppd_kv_append(ctx, k, v, kv_pages, slot_mapping, T=None, stream=None):
         T = int(slot_mapping.shape[0])
     _check(load_library().ppd_kv_append(ctx, _dev_ptr(k), _dev_ptr(v), _dev_ptr(kv_pages), _dev_ptr(slot_mapping),
                                         int(T), stream), ctx)
+
+
+def ppd_kv_land(ctx, k, v, kv_pages, layer_stride_elems, num_layers, slot_mapping, T=None, stream=None):
+    if T is None:
+        T = int(slot_mapping.shape[0])
+    _check(load_library().ppd_kv_land(ctx, _dev_ptr(k), _dev_ptr(v), _dev_ptr(kv_pages), int(layer_stride_elems),
+                                      int(num_layers), _dev_ptr(slot_mapping), int(T), stream), ctx)
+
+
+def ppd_transfer_delay_s(n_tokens, kv_bytes_per_token, beta_target_bytes_per_s, t_fast_s):
+    return float(load_library().ppd_transfer_delay_s(int(n_tokens), int(kv_bytes_per_token),
+                                                     float(beta_target_bytes_per_s), float(t_fast_s)))
 
 
 def ppd_mixed_attention(ctx, q, kv_pages, page_tables, L, n, scale, out, max_pages=None, stream=None):
@@ -198,6 +214,9 @@ class Context:
 
     def kv_append(self, k, v, kv_pages, slot_mapping, stream=None):
         ppd_kv_append(self.handle, k, v, kv_pages, slot_mapping, stream=stream)
+
+    def kv_land(self, k, v, kv_pages, layer_stride_elems, num_layers, slot_mapping, stream=None):
+        ppd_kv_land(self.handle, k, v, kv_pages, layer_stride_elems, num_layers, slot_mapping, stream=stream)
 
     def mixed_attention(self, q, kv_pages, page_tables, L, n, scale, out, stream=None):
         ppd_mixed_attention(self.handle, q, kv_pages, page_tables, L, n, scale, out, stream=stream)

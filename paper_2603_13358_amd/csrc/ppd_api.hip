@@ -192,9 +192,35 @@ ppd_status ppd_kv_append(ppd_ctx* ctx, const void* k, const void* v, void* kv_pa
     PPD_HIP(ctx, hipSetDevice(ctx->device));
     int rc = ppd::launch_kv_append(static_cast<const uint16_t*>(k), static_cast<const uint16_t*>(v),
                                    static_cast<uint16_t*>(kv_pages), slot_mapping, T, ctx->shape.num_kv_heads,
-                                   ctx->shape.head_dim, ctx->shape.num_pages, ctx->d_counters + 9, stream);
+                                   ctx->shape.head_dim, ctx->shape.num_pages, 1, 0, ctx->d_counters + 9, stream);
     if (rc != 0) return hip_fail(ctx, (hipError_t)rc, "launch kv_append");
     return PPD_OK;
+}
+
+ppd_status ppd_kv_land(ppd_ctx* ctx, const void* k, const void* v, void* kv_pages, int64_t layer_stride_elems,
+                       int32_t num_layers, const int64_t* slot_mapping, int64_t T, void* stream) {
+    if (!ctx) return PPD_ERR_NULL;
+    if (T < 0 || T >= (int64_t(1) << 31)) return fail(ctx, PPD_ERR_RANGE, "T out of range");
+    if (num_layers < 0 || num_layers > 65535) return fail(ctx, PPD_ERR_RANGE, "num_layers must be in [0, 65535]");
+    if (T == 0 || num_layers == 0) return PPD_OK;
+    if (!k || !v || !kv_pages || !slot_mapping) return fail(ctx, PPD_ERR_NULL, "k / v / kv_pages / slot_mapping is NULL");
+    const int64_t pool_elems = 2LL * ctx->shape.num_kv_heads * ppd::kPage * ctx->shape.head_dim * ctx->shape.num_pages;
+    if (num_layers > 1 && layer_stride_elems < pool_elems)
+        return fail(ctx, PPD_ERR_RANGE, "layer_stride_elems is smaller than one pool: layers would overlap");
+    PPD_HIP(ctx, hipSetDevice(ctx->device));
+    int rc = ppd::launch_kv_append(static_cast<const uint16_t*>(k), static_cast<const uint16_t*>(v),
+                                   static_cast<uint16_t*>(kv_pages), slot_mapping, T, ctx->shape.num_kv_heads,
+                                   ctx->shape.head_dim, ctx->shape.num_pages, num_layers, layer_stride_elems,
+                                   ctx->d_counters + 9, stream);
+    if (rc != 0) return hip_fail(ctx, (hipError_t)rc, "launch kv_land");
+    return PPD_OK;
+}
+
+double ppd_transfer_delay_s(int64_t n_tokens, int64_t kv_bytes_per_token, double beta_target_bytes_per_s,
+                            double t_fast_s) {
+    if (n_tokens < 0 || kv_bytes_per_token < 0 || !(beta_target_bytes_per_s > 0.0)) return -1.0;
+    const double d = (double)n_tokens * (double)kv_bytes_per_token / beta_target_bytes_per_s - t_fast_s;
+    return d > 0.0 ? d : 0.0;
 }
 
 ppd_status ppd_mixed_attention(ppd_ctx* ctx, const void* q, const void* kv_pages, const int32_t* page_tables,

@@ -100,6 +100,7 @@ struct MergeParams {
 int launch_mixed(const KParams& p, int head_dim, int grid, void* stream);
 int launch_merge(const MergeParams& p, void* stream);
 int launch_kv_append(const uint16_t* k, const uint16_t* v, uint16_t* pool, const int64_t* slots, int64_t T,
-                     int Hkv, int D, int64_t num_pages, uint32_t* err_flags, void* stream);
+                     int Hkv, int D, int64_t num_pages, int layers, int64_t pool_layer_stride, uint32_t* err_flags,
+                     void* stream);
 
 }  // namespace ppd

@@ -705,7 +705,8 @@ __global__ __launch_bounds__(kSmallThreads) void ppd_merge_kernel(const MergePar
 }
 
 // ---------------------------------------------------------------------------------------------------
-// Paged KV append.  One workgroup moves 8 consecutive tokens of the batch for one KV head.
+// Paged KV append (and, with several layers in one launch, the landing of transferred KV).  One workgroup
+// moves 8 consecutive tokens of the batch for one KV head of one layer.
 // K: 16-byte granules (8 d of one token), lanes ordered token-minor so that tokens in consecutive slots
 //    write 128 contiguous bytes.  V: a granule is 8 tokens of one d; when the 8 tokens fill one aligned
 //    granule (the common case for prefill) each thread writes it whole, otherwise element by element.
@@ -715,7 +716,11 @@ __global__ __launch_bounds__(kSmallThreads) void ppd_kv_append_kernel(const uint
                                                                  uint16_t* __restrict__ pool,
                                                                  const int64_t* __restrict__ slots, int64_t T,
                                                                  int Hkv, int D, int64_t num_pages,
-                                                                 uint32_t* err_flags) {
+                                                                 int64_t pool_layer_stride, uint32_t* err_flags) {
+    // blockIdx.z = layer: source layers are contiguous [layer][T][Hkv][D], pools pool_layer_stride apart
+    k += (int64_t)blockIdx.z * T * Hkv * D;
+    v += (int64_t)blockIdx.z * T * Hkv * D;
+    pool += (int64_t)blockIdx.z * pool_layer_stride;
     const int tid = threadIdx.x;
     const int hh = blockIdx.y;
     const int64_t t0 = (int64_t)blockIdx.x * 8;
@@ -727,7 +732,7 @@ __global__ __launch_bounds__(kSmallThreads) void ppd_kv_append_kernel(const uint
     for (int i = 0; i < 8; ++i) {
         int64_t s = i < nt ? slots[t0 + i] : -1;
         if (s >= num_pages * kPage) {
-            if (tid == 0 && hh == 0) atomicOr(err_flags, 1u);
+            if (tid == 0 && hh == 0 && blockIdx.z == 0) atomicOr(err_flags, 1u);
             s = -1;
         }
         sl[i] = s;
@@ -809,10 +814,12 @@ int launch_merge(const MergeParams& p, void* stream) {
 }
 
 int launch_kv_append(const uint16_t* k, const uint16_t* v, uint16_t* pool, const int64_t* slots, int64_t T, int Hkv,
-                     int D, int64_t num_pages, uint32_t* err_flags, void* stream) {
+                     int D, int64_t num_pages, int layers, int64_t pool_layer_stride, uint32_t* err_flags,
+                     void* stream) {
     const int64_t blocks = (T + 7) / 8;
-    hipLaunchKernelGGL(ppd_kv_append_kernel, dim3((unsigned)blocks, (unsigned)Hkv), dim3(kSmallThreads), 0,
-                       static_cast<hipStream_t>(stream), k, v, pool, slots, T, Hkv, D, num_pages, err_flags);
+    hipLaunchKernelGGL(ppd_kv_append_kernel, dim3((unsigned)blocks, (unsigned)Hkv, (unsigned)layers),
+                       dim3(kSmallThreads), 0, static_cast<hipStream_t>(stream), k, v, pool, slots, T, Hkv, D, num_pages,
+                       pool_layer_stride, err_flags);
     return (int)hipGetLastError();
 }
 

@@ -239,3 +239,39 @@ def test_chunked_append_prefill_equals_one_shot():
         done += chunk
     assert ctx.device_error_flags() == 0
     ctx.close()
+
+
+def test_kv_land_all_layers_bit_exact():
+    import torch
+    import oracle
+    import paper_2603_13358_amd as ppd
+    from gpu_helpers import from_dev_u16, to_dev_u16
+    from helpers import SENTINEL
+    b = si.make_batch("land", L=[333, 40, 1000], n=[1, 1, 1], Hq=32, Hkv=8, D=128, seed=51, slack_pages=4)
+    layers, pe = 4, oracle.pool_elems(b.num_pages, b.Hkv, b.D, b.P)
+    stride = pe + 4096
+    rng = np.random.default_rng(6)
+    _, _, slots = b.cached_part()
+    slots = slots.copy()
+    slots[7] = -1                                   # a skipped token
+    T = len(slots)
+    k = si.normal_bf16(rng, (layers, T, b.Hkv, b.D))
+    v = si.normal_bf16(rng, (layers, T, b.Hkv, b.D))
+    total = stride * (layers - 1) + pe
+    ref = np.full(total, SENTINEL, np.uint16)
+    oracle.kv_land(k, v, ref, stride, layers, slots, b.Hkv, b.D, b.P, b.num_pages)
+    dev = torch.device("cuda:0")
+    ctx = ppd.Context(b.Hq, b.Hkv, b.D, b.num_pages)
+    fill = int(np.array([SENTINEL], np.uint16).view(np.int16)[0])
+    pools = torch.full((total,), fill, dtype=torch.int16, device=dev)
+    ctx.kv_land(to_dev_u16(k, torch, dev), to_dev_u16(v, torch, dev), pools, stride, layers,
+                torch.from_numpy(slots).to(dev))
+    torch.cuda.synchronize()
+    assert ctx.device_error_flags() == 0
+    assert np.array_equal(from_dev_u16(pools), ref)
+    with pytest.raises(ppd.PPDError) as e:
+        ctx.kv_land(pools, pools, pools, pe - 1, 2, torch.from_numpy(slots).to(dev))
+    assert e.value.status == -3
+    assert abs(ppd.ppd_transfer_delay_s(5115, 131072, 25e9, 0.0045) -
+               oracle.transfer_delay(5115, 131072, 25e9, 0.0045)) < 1e-15
+    ctx.close()

@@ -194,3 +194,55 @@ def test_kv_footprint_arithmetic():
     # cost of append-prefill is O(n(L+n)): exactly 4*Hq*D flops per visible (row, key) pair
     one = si.make_batch("f", L=[100], n=[10], Hq=2, Hkv=1, D=64, seed=0, with_data=False)
     assert one.attention_flops() == 4 * 2 * 64 * (10 * 100 + 55)
+
+
+def _golden_transfer():
+    import os
+    vals = {}
+    path = os.path.join(os.path.dirname(os.path.abspath(__file__)), "golden", "kv_transfer_numbers.txt")
+    for line in open(path):
+        if line.startswith("#") or not line.strip():
+            continue
+        parts = line.split()
+        vals[parts[0]] = float(parts[1])
+    return vals
+
+
+def test_transfer_delay_model_against_the_papers_numbers():
+    """The injected-delay equation of the appendix "Bandwidth Simulation" and the figures printed next to it."""
+    g = _golden_transfer()
+    B = g["p90_context_tokens"] * g["s_kv_bytes_per_token"]
+    assert B == g["footprint_bytes"]
+    t_nv = g["time_nvlink_ms"] * 1e-3
+    # with t_fast = 0 the delay is the plain transfer time B / beta: the paper's ~27 ms at 25 GB/s
+    assert abs(oracle.transfer_delay(g["p90_context_tokens"], g["s_kv_bytes_per_token"], g["ib_hdr_bytes_per_s"], 0.0) * 1e3
+               - g["time_ib_hdr_ms"]) < 0.5
+    # ~67 ms over 100GbE corresponds to 10 GB/s
+    assert abs(oracle.transfer_delay(g["p90_context_tokens"], g["s_kv_bytes_per_token"], 10e9, 0.0) * 1e3
+               - g["time_100gbe_ms"]) < 0.5
+    # the injected delay subtracts the NVLink time already spent and never goes negative
+    d = oracle.transfer_delay(g["p90_context_tokens"], g["s_kv_bytes_per_token"], g["ib_hdr_bytes_per_s"], t_nv)
+    assert abs(d - (B / 25e9 - t_nv)) < 1e-12 and 0.022 < d < 0.023
+    assert oracle.transfer_delay(g["p90_context_tokens"], g["s_kv_bytes_per_token"], 1e12, t_nv) == 0.0
+    # delay is linear in tokens above the break-even point
+    d2 = oracle.transfer_delay(2 * g["p90_context_tokens"], g["s_kv_bytes_per_token"], g["ib_hdr_bytes_per_s"], t_nv)
+    assert abs((d2 + t_nv) - 2 * (d + t_nv)) < 1e-12
+
+
+def test_kv_land_is_one_append_per_layer():
+    b = si.cfg1_tiny(1)
+    layers, pe = 3, oracle.pool_elems(b.num_pages, b.Hkv, b.D, b.P)
+    stride = pe + 640                       # padding between the layers' pools must stay untouched
+    rng = np.random.default_rng(5)
+    k0, v0, slots = b.cached_part()
+    T = len(slots)
+    k = si.normal_bf16(rng, (layers, T, b.Hkv, b.D))
+    v = si.normal_bf16(rng, (layers, T, b.Hkv, b.D))
+    pools = np.full(stride * (layers - 1) + pe, SENTINEL, np.uint16)
+    oracle.kv_land(k, v, pools, stride, layers, slots, b.Hkv, b.D, b.P, b.num_pages)
+    for l in range(layers):
+        ref = np.full(pe, SENTINEL, np.uint16)
+        oracle.kv_append(k[l], v[l], ref, slots, b.Hkv, b.D, b.P, b.num_pages)
+        assert np.array_equal(pools[l * stride:l * stride + pe], ref)
+        if l + 1 < layers:
+            assert (pools[l * stride + pe:(l + 1) * stride] == SENTINEL).all()
