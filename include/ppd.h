@@ -182,6 +182,35 @@ ppd_status ppd_last_kernel_ms(ppd_ctx *ctx, float *ms);
  * 16..63 afterwards. */
 ppd_status ppd_debug_counters(ppd_ctx *ctx, void *stream, uint32_t *out64, int32_t clear);
 
+/* ---- PPD routing decision (host only; paper section 3 score equation, section 5 algorithm "PPD Dynamic
+ * Routing", appendix "Decision-Engine Discretization") ----
+ * Grid: 3 context classes (accumulated context <= 512, <= 4096, larger) x 9 workload types (input/output token
+ * ratio classes, given by their centre ratios) x 10 QPS levels (0.5, 1, 2, 4, 6, 8, 10, 12, 16, 20).
+ * Cell index = (context_class * 9 + ratio_class) * 10 + qps_level. */
+#define PPD_ROUTE_CTX_CLASSES 3
+#define PPD_ROUTE_RATIO_CLASSES 9
+#define PPD_ROUTE_QPS_LEVELS 10
+#define PPD_ROUTE_CELLS (PPD_ROUTE_CTX_CLASSES * PPD_ROUTE_RATIO_CLASSES * PPD_ROUTE_QPS_LEVELS)
+
+/* S = w_ttft * delta_ttft - w_tpot * delta_tpot: delta_ttft is the relative TTFT improvement, delta_tpot the
+ * relative TPOT degradation of processing the turn locally on the decode node instead of through a prefill node. */
+double ppd_route_score(double w_ttft, double w_tpot, double delta_ttft, double delta_tpot);
+
+/* Offline phase: x_table[cell] = 1 if S > 0 else 0, from measured delta_ttft / delta_tpot per cell
+ * (HOST double [PPD_ROUTE_CELLS] each; x_table HOST uint8 [PPD_ROUTE_CELLS]).  Weights must be >= 0. */
+ppd_status ppd_route_table_build(const double *delta_ttft, const double *delta_tpot, double w_ttft, double w_tpot,
+                                 uint8_t *x_table);
+
+/* Nearest grid cell of a request (n_in new input tokens, n_out expected output tokens, n_ctx accumulated context,
+ * current system QPS); the ratio class is the nearest of ratio_centers (HOST double [9], all > 0) on a
+ * logarithmic scale.  Returns the cell index or -1 for invalid arguments. */
+int32_t ppd_route_cell(const double *ratio_centers, int64_t n_in, int64_t n_out, int64_t n_ctx, double qps);
+
+/* Online phase: turn 1 always returns 0 (prefill-node path: no cached KV yet); later turns return the table
+ * entry of the request's nearest cell (1 = run the append-prefill on the decode node).  -1 for invalid arguments. */
+int32_t ppd_route_decide(const uint8_t *x_table, const double *ratio_centers, int32_t turn, int64_t n_in,
+                         int64_t n_out, int64_t n_ctx, double qps);
+
 /* Library version, "major.minor". */
 const char *ppd_version(void);
 

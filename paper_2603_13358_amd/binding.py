@@ -42,7 +42,7 @@ class PlanStats(ctypes.Structure):
 EXPORTS = ["ppd_create", "ppd_destroy", "ppd_last_error", "ppd_set_option", "ppd_kv_append", "ppd_kv_land",
            "ppd_transfer_delay_s", "ppd_mixed_attention",
            "ppd_get_plan_stats", "ppd_plan_build", "ppd_device_error_flags", "ppd_last_kernel_ms", "ppd_debug_counters",
-           "ppd_version"]
+           "ppd_route_score", "ppd_route_table_build", "ppd_route_cell", "ppd_route_decide", "ppd_version"]
 
 
 def lib_path():
@@ -75,10 +75,16 @@ def load_library():
     lib.ppd_device_error_flags.argtypes = [vp, vp, ctypes.POINTER(ctypes.c_uint32)]
     lib.ppd_last_kernel_ms.argtypes = [vp, ctypes.POINTER(ctypes.c_float)]
     lib.ppd_debug_counters.argtypes = [vp, vp, ctypes.POINTER(ctypes.c_uint32), i32]
+    dbl = ctypes.c_double
+    lib.ppd_route_score.argtypes = [dbl, dbl, dbl, dbl]
+    lib.ppd_route_score.restype = dbl
+    lib.ppd_route_table_build.argtypes = [vp, vp, dbl, dbl, vp]
+    lib.ppd_route_cell.argtypes = [vp, i64, i64, i64, dbl]
+    lib.ppd_route_decide.argtypes = [vp, vp, i32, i64, i64, i64, dbl]
     lib.ppd_version.argtypes = []
     lib.ppd_version.restype = ctypes.c_char_p
     for name in EXPORTS:
-        if name not in ("ppd_last_error", "ppd_version", "ppd_transfer_delay_s"):
+        if name not in ("ppd_last_error", "ppd_version", "ppd_transfer_delay_s", "ppd_route_score"):
             getattr(lib, name).restype = i32
     _lib = lib
     return lib
@@ -176,6 +182,40 @@ def ppd_debug_counters(ctx, stream=None, clear=False):
     buf = (ctypes.c_uint32 * 64)()
     _check(load_library().ppd_debug_counters(ctx, stream, buf, 1 if clear else 0), ctx)
     return [int(x) for x in buf]
+
+
+ROUTE_CELLS = 3 * 9 * 10
+
+
+def ppd_route_score(w_ttft, w_tpot, delta_ttft, delta_tpot):
+    return float(load_library().ppd_route_score(w_ttft, w_tpot, delta_ttft, delta_tpot))
+
+
+def ppd_route_table_build(delta_ttft, delta_tpot, w_ttft, w_tpot):
+    """Returns the uint8 [270] decision table for per-cell measured deltas (float64 [270] each)."""
+    a = np.ascontiguousarray(delta_ttft, dtype=np.float64).reshape(-1)
+    b = np.ascontiguousarray(delta_tpot, dtype=np.float64).reshape(-1)
+    assert a.size == ROUTE_CELLS and b.size == ROUTE_CELLS
+    table = np.zeros(ROUTE_CELLS, np.uint8)
+    status = load_library().ppd_route_table_build(a.ctypes.data, b.ctypes.data, float(w_ttft), float(w_tpot),
+                                                  table.ctypes.data)
+    if status != 0:
+        raise PPDError(status, "ppd_route_table_build")
+    return table
+
+
+def ppd_route_cell(ratio_centers, n_in, n_out, n_ctx, qps):
+    c = np.ascontiguousarray(ratio_centers, dtype=np.float64)
+    assert c.size == 9
+    return int(load_library().ppd_route_cell(c.ctypes.data, int(n_in), int(n_out), int(n_ctx), float(qps)))
+
+
+def ppd_route_decide(x_table, ratio_centers, turn, n_in, n_out, n_ctx, qps):
+    t = np.ascontiguousarray(x_table, dtype=np.uint8)
+    c = np.ascontiguousarray(ratio_centers, dtype=np.float64)
+    assert t.size == ROUTE_CELLS and c.size == 9
+    return int(load_library().ppd_route_decide(t.ctypes.data, c.ctypes.data, int(turn), int(n_in), int(n_out),
+                                               int(n_ctx), float(qps)))
 
 
 def ppd_plan_build(num_q_heads, num_kv_heads, head_dim, page_size, num_pages, L, n, narrow_chunk=0, mfma_chunk=0,

@@ -6,7 +6,7 @@ import sys
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libppd.so")
-SOURCES = ["ppd_api.hip", "ppd_kernels.hip", "ppd_plan.cpp"]
+SOURCES = ["ppd_api.hip", "ppd_kernels.hip", "ppd_plan.cpp", "ppd_route.cpp"]
 HEADERS = ["ppd_internal.h", os.path.join("..", "..", "include", "ppd.h")]
 
 # Packed-FP32 instructions are switched off for all device code (the host pass does not know the feature
