@@ -108,7 +108,9 @@ const char *ppd_last_error(const ppd_ctx *ctx);
  * "grid" (workgroups, 0 = automatic), "force_kind" (-1 automatic, 1 = route every sequence through the
  * MFMA row-block path; used to test that n = 1 append-prefill equals decode), "pref_mode" (0..3: which
  * kind of tile a workgroup takes first -- 0 MFMA tiles for all, 1 alternating per group of 8 workgroups,
- * 2 lower half of the grid MFMA / upper half narrow (default), 3 narrow tiles for all), "timing" (1 = record HIP
+ * 2 split by physical compute unit (default), 3 narrow tiles for all), "narrow_cus" (pref_mode 2: how many of
+ * the 32 compute units of an XCD take narrow tiles first; -1 = sized by the planner's cost model so that both
+ * kinds finish together), "timing" (1 = record HIP
  * events on the call's stream right before and after the mixed-attention kernel, see ppd_last_kernel_ms). */
 ppd_status ppd_set_option(ppd_ctx *ctx, const char *key, int64_t value);
 

@@ -174,6 +174,9 @@ ppd_status ppd_set_option(ppd_ctx* ctx, const char* key, int64_t value) {
     } else if (k == "pref_mode") {
         if (value < 0 || value > 3) return fail(ctx, PPD_ERR_RANGE, "pref_mode must be in [0, 3]");
         ctx->opts.pref_mode = (int32_t)value;
+    } else if (k == "narrow_cus") {
+        if (value < -1 || value > 32) return fail(ctx, PPD_ERR_RANGE, "narrow_cus must be in [-1, 32]");
+        ctx->opts.narrow_cus = (int32_t)value;
     } else if (k == "timing") {
         ctx->timing = value != 0;
         ctx->timed = false;
@@ -329,6 +332,7 @@ ppd_status ppd_mixed_attention(ppd_ctx* ctx, const void* q, const void* kv_pages
     kp.n_items = (int32_t)plan.items.size();
     std::memcpy(kp.queue_begin, plan.queue_begin, sizeof kp.queue_begin);
     kp.pref_mode = ctx->opts.pref_mode;
+    kp.narrow_cus = plan.narrow_cus;
     kp.max_pages = max_pages;
     kp.Hq = ctx->shape.num_q_heads;
     kp.Hkv = ctx->shape.num_kv_heads;

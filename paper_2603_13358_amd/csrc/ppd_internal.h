@@ -46,6 +46,7 @@ constexpr int kNarrowQueue = kXcds;  // index of the narrow-tile queue
 
 struct Plan {
     int32_t queue_begin[kXcds + 2];  // items [queue_begin[q], queue_begin[q+1]) belong to queue q
+    int32_t narrow_cus = 16;         // of the 32 compute units of an XCD, how many take narrow tiles first
     std::vector<ppd_work_item> items;
     std::vector<MergeGroup> groups;
     std::vector<MergeUnit> units;
@@ -59,6 +60,7 @@ struct PlanOptions {
     int32_t force_kind = -1;
     int32_t num_cus = 256;
     int32_t pref_mode = 2;
+    int32_t narrow_cus = -1;  // -1: from the cost model
 };
 
 // Returns PPD_OK or an error code with a message in `err` (may be null).
@@ -80,6 +82,7 @@ struct KParams {
     int64_t page_stride;  // elements per page = 2 * Hkv * 16 * D
     int32_t n_items;
     int32_t pref_mode;    // how a workgroup picks its preferred queue (see ppd_mixed_kernel)
+    int32_t narrow_cus;   // pref_mode 2: compute units per XCD (of 32) that take narrow tiles first
     int32_t max_pages;
     int32_t Hq, Hkv, G, lgG;
     float scale_log2e;

@@ -605,14 +605,22 @@ __global__ __launch_bounds__(kThreads, 2) void ppd_mixed_kernel(const KParams P)
     const int tid = threadIdx.x;
     // Nine queues in one list: MFMA row-block tiles in eight queues, one per XCD (tiles that read the same K/V
     // sit in the same queue, next to each other, so the workgroups of one XCD find them in their L2), and one
-    // queue of narrow tiles; each longest-first.  A workgroup prefers one kind -- lower half of the grid MFMA
-    // tiles, upper half narrow tiles -- so that HBM-bound and MFMA-bound tiles run side by side on different
-    // compute units, takes MFMA tiles from its own XCD's queue first, and steals from the other queues when
-    // its own run dry.
+    // queue of narrow tiles; each longest-first.  A workgroup prefers one kind, chosen by the compute
+    // unit it runs on (narrow_cus of the 32 units of every XCD take narrow tiles, spread evenly over the shader
+    // engines; the planner sizes the split so that both kinds finish together): the two workgroups that share
+    // a unit then run the same kind, and HBM-bound and MFMA-bound tiles run side by side on different units.
+    // It takes MFMA tiles from its own XCD's queue first, and steals from the other queues when its own run dry.
     int pref;
     switch (P.pref_mode) {
         case 1: pref = (blockIdx.x >> 3) & 1; break;
-        case 2: pref = blockIdx.x >= (gridDim.x >> 1) ? 1 : 0; break;
+        case 2: {
+            // HW_REG_HW_ID: cu_id in bits 11:8, se_id in bits 15:13 (eight active units per shader engine, ids
+            // 0..8 with one gap, so the low three bits tell them apart)
+            const unsigned hw = __builtin_amdgcn_s_getreg((15 << 11) | (0 << 6) | 4);
+            const int unit = (int)(((hw >> 8) & 7) << 2 | ((hw >> 13) & 3));
+            pref = unit < P.narrow_cus ? 1 : 0;
+            break;
+        }
         case 3: pref = 1; break;
         default: pref = 0; break;
     }
@@ -622,7 +630,11 @@ __global__ __launch_bounds__(kThreads, 2) void ppd_mixed_kernel(const KParams P)
         if (tid == 0) {
             int idx = -1;
 #pragma unroll
+#ifdef PPD_DIAG_NO_CROSS_KIND  // diagnostic builds only: a workgroup never takes the other kind's tiles
+            for (int attempt = 0; attempt < 1 && idx < 0; ++attempt) {
+#else
             for (int attempt = 0; attempt < 2 && idx < 0; ++attempt) {
+#endif
                 const bool want_narrow = (attempt == 0) == (pref == 1);
                 if (want_narrow) {
                     if (!(dry & (1u << kNarrowQueue))) {
@@ -683,22 +695,65 @@ __global__ __launch_bounds__(kSmallThreads) void ppd_merge_kernel(const MergePar
     if (col >= ncols) return;
     const float* base = M.partials + g.part_off;
     const int64_t ml_off = (int64_t)ncols * D + col * 2;
-    float mm = NEG_INF;
-    for (int j = 0; j < g.nsplit; ++j) mm = fmaxf(mm, base[g.part_stride * j + ml_off]);
-    float o0 = 0.f, o1 = 0.f, l = 0.f;
     const int d = lane * 2;
-    for (int j = 0; j < g.nsplit; ++j) {
-        const float* pp = base + g.part_stride * j;
-        const float mj = pp[ml_off];
-        const float f = mj == NEG_INF ? 0.f : fast_exp2((mj - mm) * M.scale_log2e);
-        l += f * pp[ml_off + 1];
-        if (d < D) {
-            const f32x2 v = *reinterpret_cast<const f32x2*>(pp + (int64_t)col * D + d);
-            o0 += f * v[0];
-            o1 += f * v[1];
+    const bool live = d < D;
+    const int64_t v_off = (int64_t)col * D + (live ? d : 0);
+    // The wave moves little data, so its time is the chain of dependent loads: four splits are loaded at a
+    // time, all loads of a batch issued before the first use.
+    float mm = NEG_INF;
+    float o0 = 0.f, o1 = 0.f, l = 0.f;
+    if (g.nsplit <= 4) {
+        float m4[4], l4[4];
+        f32x2 v4[4];
+#pragma unroll
+        for (int t = 0; t < 4; ++t) {
+            const float* pp = base + g.part_stride * (t < g.nsplit ? t : 0);
+            m4[t] = pp[ml_off];
+            l4[t] = pp[ml_off + 1];
+            v4[t] = *reinterpret_cast<const f32x2*>(pp + v_off);
+        }
+#pragma unroll
+        for (int t = 0; t < 4; ++t)
+            if (t < g.nsplit) mm = fmaxf(mm, m4[t]);
+#pragma unroll
+        for (int t = 0; t < 4; ++t) {
+            if (t < g.nsplit) {
+                const float f = m4[t] == NEG_INF ? 0.f : fast_exp2((m4[t] - mm) * M.scale_log2e);
+                l += f * l4[t];
+                o0 += f * v4[t][0];
+                o1 += f * v4[t][1];
+            }
+        }
+    } else {
+        for (int j0 = 0; j0 < g.nsplit; j0 += 4) {
+            float m4[4];
+#pragma unroll
+            for (int t = 0; t < 4; ++t) m4[t] = base[g.part_stride * (j0 + t < g.nsplit ? j0 + t : j0) + ml_off];
+#pragma unroll
+            for (int t = 0; t < 4; ++t) mm = fmaxf(mm, m4[t]);
+        }
+        for (int j0 = 0; j0 < g.nsplit; j0 += 4) {
+            float m4[4], l4[4];
+            f32x2 v4[4];
+#pragma unroll
+            for (int t = 0; t < 4; ++t) {
+                const float* pp = base + g.part_stride * (j0 + t < g.nsplit ? j0 + t : j0);
+                m4[t] = pp[ml_off];
+                l4[t] = pp[ml_off + 1];
+                v4[t] = *reinterpret_cast<const f32x2*>(pp + v_off);
+            }
+#pragma unroll
+            for (int t = 0; t < 4; ++t) {
+                if (j0 + t < g.nsplit) {
+                    const float f = m4[t] == NEG_INF ? 0.f : fast_exp2((m4[t] - mm) * M.scale_log2e);
+                    l += f * l4[t];
+                    o0 += f * v4[t][0];
+                    o1 += f * v4[t][1];
+                }
+            }
         }
     }
-    if (d < D) {
+    if (live) {
         const int64_t orow = (int64_t)(g.grow0 + (col >> M.lgG)) * M.Hq + g.kvh * M.G + (col & (M.G - 1));
         *reinterpret_cast<uint32_t*>(M.out + orow * D + d) = pack_bf16(o0 / l, o1 / l);
     }

@@ -209,6 +209,30 @@ ppd_status build_plan(const ppd_shape& s, const int32_t* L, const int32_t* n, in
     }
     plan->queue_begin[kNarrowQueue + 1] = (int32_t)plan->items.size();
 
+    // Split of the compute units between the two kinds when both are present.  Two workgroups share a compute
+    // unit; an MFMA tile next to a narrow tile on the same unit runs far below half the unit's MFMA rate, so
+    // the split is by physical unit: narrow_cus of the 32 units of every XCD take narrow tiles first, the others
+    // MFMA tiles.  Narrow tiles are bound by the bytes a unit keeps in flight (about 45 GB/s each), MFMA tiles
+    // by compute (about 2.3 us per 64-key tile of a row block on half a unit): size the split so that both
+    // kinds finish together; whoever finishes first steals from the other anyway.
+    {
+        double narrow_bytes = 0, mfma_us = 0;
+        for (auto& k : keyed) {
+            const double toks = (double)(k.it.kv_end - k.it.kv_begin);
+            if (k.it.kind == 0) narrow_bytes += toks * kv_tok_bytes_head;
+            else mfma_us += std::ceil(toks / kTileTokens) * 2.3 / kWgPerCu;
+        }
+        int cus = 16;
+        if (narrow_bytes == 0) cus = 0;
+        else if (mfma_us == 0) cus = 32;
+        else {
+            const double narrow_cu_us = narrow_bytes / 45e3;  // CU-microseconds at 45 GB/s per unit
+            cus = (int)std::lround(32.0 * narrow_cu_us / (narrow_cu_us + mfma_us));
+            cus = std::min(std::max(cus, 2), 20);             // HBM saturates well before all units stream
+        }
+        plan->narrow_cus = o.narrow_cus >= 0 ? std::min(o.narrow_cus, 32) : cus;
+    }
+
     ppd_plan_stats& st = plan->stats;
     st.n_items = (int64_t)plan->items.size();
     st.n_narrow = n_narrow;
