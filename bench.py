@@ -295,12 +295,12 @@ def run_sweeps(torch, seed, steps, options):
     length, with 4 concurrent prefills, and with the append-prefill fed in token-budgeted chunks."""
     import synthetic_inputs as si
 
-    def time_batch(L, n):
-        b = si.make_batch("sweep", L=L, n=n, Hq=32, Hkv=8, D=128, seed=seed, slack_pages=16, with_data=False)
+    def time_batch(L, n, Hq=32, Hkv=8, want_batch=False):
+        b = si.make_batch("sweep", L=L, n=n, Hq=Hq, Hkv=Hkv, D=128, seed=seed, slack_pages=16, with_data=False)
         r = Runner(b, torch, seed, options)
         ms = r.time_steps(steps, 2)
         r.close()
-        return ms * 1e3
+        return (ms * 1e3, b) if want_batch else ms * 1e3
 
     def trio(dec_L, ap_L, ap_n, n_prefill=1):
         dec_L = list(dec_L)
@@ -328,6 +328,18 @@ def run_sweeps(torch, seed, steps, options):
                                "decode_step_slowdown": float(np.mean(per_step)) / base - 1.0,
                                "total_us_until_prefill_done": float(np.sum(per_step))}
     out["chunked_append_prefill"] = {"decode_only_us": base, "by_chunk_tokens": chunked}
+    # head shapes of the three models the paper serves (section 5.1), one attention layer each: 128 decodes at
+    # 8192 context (HBM-bound), 8 append-prefills of 512 tokens over 8192 (MFMA-bound), and both together
+    shapes = {"llama3_8b_32q_8kv": (32, 8), "qwen2.5_14b_40q_8kv": (40, 8), "qwen3_30b_a3b_32q_4kv": (32, 4)}
+    by_shape = {}
+    for name, (Hq, Hkv) in shapes.items():
+        dec_us, bd = time_batch([8192] * 128, [1] * 128, Hq, Hkv, True)
+        ap_us, ba = time_batch([8192] * 8, [512] * 8, Hq, Hkv, True)
+        mix_us = time_batch([8192] * 136, [1] * 128 + [512] * 8, Hq, Hkv)
+        by_shape[name] = {"decode_step_us": dec_us, "decode_hbm_gbs": bd.kv_read_bytes() / dec_us / 1e3,
+                          "append_prefill_step_us": ap_us, "append_prefill_tflops": ba.attention_flops() / ap_us / 1e6,
+                          "mixed_step_us": mix_us, "decode_step_slowdown": mix_us / dec_us - 1.0}
+    out["model_head_shapes_ctx8192"] = by_shape
     return out
 
 

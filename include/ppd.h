@@ -54,7 +54,7 @@ typedef enum {
     PPD_ERR_HIP = -6        /* a HIP runtime call failed (see ppd_last_error) */
 } ppd_status;
 
-/* Supported: head_dim in {64, 128}; page_size == 16; num_q_heads = G * num_kv_heads with G in {1,2,4,8};
+/* Supported: head_dim in {64, 128}; page_size == 16; num_q_heads = G * num_kv_heads with 1 <= G <= 8;
  * num_pages >= 1. */
 typedef struct {
     int32_t num_q_heads;

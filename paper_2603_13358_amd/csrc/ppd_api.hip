@@ -68,12 +68,6 @@ ppd_status hip_fail(ppd_ctx* ctx, hipError_t e, const char* what) {
         if (e_ != hipSuccess) return hip_fail((ctx), e_, #call);   \
     } while (0)
 
-int ilog2(int v) {
-    int l = 0;
-    while ((1 << l) < v) ++l;
-    return l;
-}
-
 // Grows a device buffer (contents are not kept).  Waits for the stream first: the old buffer may be in use.
 ppd_status grow_device(ppd_ctx* ctx, void** ptr, size_t* have, size_t need, hipStream_t st) {
     if (need <= *have) return PPD_OK;
@@ -337,7 +331,7 @@ ppd_status ppd_mixed_attention(ppd_ctx* ctx, const void* q, const void* kv_pages
     kp.Hq = ctx->shape.num_q_heads;
     kp.Hkv = ctx->shape.num_kv_heads;
     kp.G = G;
-    kp.lgG = ilog2(G);
+    kp.invG = 65536 / G + 1;
     kp.scale_log2e = scale_log2e;
     if (ctx->timing) PPD_HIP(ctx, hipEventRecord(ctx->ev_begin, hs));
     int rc = ppd::launch_mixed(kp, ctx->shape.head_dim, plan.stats.grid, stream);
@@ -357,7 +351,7 @@ ppd_status ppd_mixed_attention(ppd_ctx* ctx, const void* q, const void* kv_pages
         mp.n_units = (int32_t)plan.units.size();
         mp.Hq = kp.Hq;
         mp.G = G;
-        mp.lgG = kp.lgG;
+        mp.invG = kp.invG;
         mp.D = ctx->shape.head_dim;
         mp.scale_log2e = scale_log2e;
         rc = ppd::launch_merge(mp, stream);

@@ -84,7 +84,7 @@ struct KParams {
     int32_t pref_mode;    // how a workgroup picks its preferred queue (see ppd_mixed_kernel)
     int32_t narrow_cus;   // pref_mode 2: compute units per XCD (of 32) that take narrow tiles first
     int32_t max_pages;
-    int32_t Hq, Hkv, G, lgG;
+    int32_t Hq, Hkv, G, invG;  // invG = 65536 / G + 1: col / G == (col * invG) >> 16
     float scale_log2e;
 };
 
@@ -95,7 +95,7 @@ struct MergeParams {
     const float* partials;
     uint16_t* out;
     int32_t n_groups;
-    int32_t Hq, G, lgG, D;
+    int32_t Hq, G, invG, D;
     float scale_log2e;
 };
 

@@ -54,6 +54,9 @@ __device__ __forceinline__ uint32_t pack_bf16(float a, float b) {
 __device__ __forceinline__ bf16x8 as_bf16x8(u32x4 v) { return __builtin_bit_cast(bf16x8, v); }
 
 __device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
+// Query row of a column of a row block (columns are row-major over the G query heads of the group): col / G
+// with inv = 65536 / G + 1, exact for col < 4096 and G <= 16.
+__device__ __forceinline__ int col_row(int col, int inv) { return (int)(((unsigned)col * (unsigned)inv) >> 16); }
 
 __device__ __forceinline__ float xor_shuffle(float v, int mask) { return __shfl_xor(v, mask, 64); }
 
@@ -149,15 +152,15 @@ __device__ __forceinline__ void mfma_item(const KParams& P, const ppd_work_item&
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int h = lane >> 5;
     const int l32 = lane & 31;
-    const int G = P.G, lg = P.lgG;
+    const int G = P.G;
     const int ncols = it.nrows * G;
     const int col = wave * 32 + l32;
     const int colc = col < ncols ? col : ncols - 1;
-    const int jrow = colc >> lg;
-    const int head = it.kvh * G + (colc & (G - 1));
+    const int jrow = col_row(colc, P.invG);
+    const int head = it.kvh * G + (colc - jrow * G);
     const int limit = it.L + it.row0 + jrow;  // last key position this column may see
     const bool wave_active = wave * 32 < ncols;
-    const int wmin_limit = it.L + it.row0 + (((wave * 32) < ncols ? wave * 32 : ncols - 1) >> lg);
+    const int wmin_limit = it.L + it.row0 + col_row((wave * 32) < ncols ? wave * 32 : ncols - 1, P.invG);
 
     // Q^T operand: column = lane % 32, d = ks*16 + (lane/32)*8 .. +8
     bf16x8 qreg[KS];
@@ -417,11 +420,11 @@ __device__ __forceinline__ void narrow_item(const KParams& P, const ppd_work_ite
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int c16 = lane & 15;
     const int g4 = lane >> 4;
-    const int G = P.G, lg = P.lgG;
+    const int G = P.G;
     const int ncols = it.nrows * G;
     const int colc = c16 < ncols ? c16 : ncols - 1;
-    const int jrow = colc >> lg;
-    const int head = it.kvh * G + (colc & (G - 1));
+    const int jrow = col_row(colc, P.invG);
+    const int head = it.kvh * G + (colc - jrow * G);
     const int limit = it.L + it.row0 + jrow;
     const int min_limit = it.L + it.row0;
 
@@ -580,7 +583,8 @@ __device__ __forceinline__ void narrow_item(const KParams& P, const ppd_work_ite
             l += f * all[w * WSTRIDE + kNarrowCols * HD + col * 2 + 1];
         }
         if (it.part_off < 0) {
-            const int64_t orow = (int64_t)(it.grow0 + (col >> lg)) * P.Hq + it.kvh * G + (col & (G - 1));
+            const int crow = col_row(col, P.invG);
+            const int64_t orow = (int64_t)(it.grow0 + crow) * P.Hq + it.kvh * G + (col - crow * G);
             const float val = o / l;
             const float other = __shfl_xor(val, 1, 64);  // d and d^1 sit in neighbouring lanes
             if ((d & 1) == 0) *reinterpret_cast<uint32_t*>(P.out + orow * HD + d) = pack_bf16(val, other);
@@ -754,7 +758,8 @@ __global__ __launch_bounds__(kSmallThreads) void ppd_merge_kernel(const MergePar
         }
     }
     if (live) {
-        const int64_t orow = (int64_t)(g.grow0 + (col >> M.lgG)) * M.Hq + g.kvh * M.G + (col & (M.G - 1));
+        const int crow = col_row(col, M.invG);
+        const int64_t orow = (int64_t)(g.grow0 + crow) * M.Hq + g.kvh * M.G + (col - crow * M.G);
         *reinterpret_cast<uint32_t*>(M.out + orow * D + d) = pack_bf16(o0 / l, o1 / l);
     }
 }

@@ -18,7 +18,7 @@ ppd_status validate_shape(const ppd_shape* s, const char** err) {
     static const char* kNull = "shape is NULL";
     static const char* kDim = "head_dim must be 64 or 128";
     static const char* kPageSz = "page_size must be 16";
-    static const char* kHeads = "num_q_heads must be G * num_kv_heads with G in {1,2,4,8}, num_kv_heads >= 1";
+    static const char* kHeads = "num_q_heads must be G * num_kv_heads with 1 <= G <= 8, num_kv_heads >= 1";
     static const char* kPages = "num_pages must be >= 1 and the pool below 2^40 elements";
     const char* dummy;
     if (!err) err = &dummy;
@@ -29,7 +29,7 @@ ppd_status validate_shape(const ppd_shape* s, const char** err) {
         *err = kHeads; return PPD_ERR_SHAPE;
     }
     int G = s->num_q_heads / s->num_kv_heads;
-    if (G != 1 && G != 2 && G != 4 && G != 8) { *err = kHeads; return PPD_ERR_SHAPE; }
+    if (G < 1 || G > 8) { *err = kHeads; return PPD_ERR_SHAPE; }
     if (s->num_kv_heads > 1024) { *err = kHeads; return PPD_ERR_SHAPE; }
     if (s->num_pages < 1 || s->num_pages > (int64_t(1) << 40) / (2LL * s->num_kv_heads * kPage * s->head_dim)) {
         *err = kPages; return PPD_ERR_SHAPE;

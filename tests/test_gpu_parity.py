@@ -39,8 +39,11 @@ def test_cfg1_peaky_queries():
     _compare(si.cfg1_tiny(0, q_std=4.0))
 
 
-@pytest.mark.parametrize("Hq,Hkv,D", [(32, 8, 128), (8, 8, 128), (8, 4, 64), (8, 1, 128), (16, 2, 64)])
+@pytest.mark.parametrize("Hq,Hkv,D", [(32, 8, 128), (8, 8, 128), (8, 4, 64), (8, 1, 128), (16, 2, 64),
+                                      (40, 8, 128), (32, 4, 128), (6, 2, 64), (12, 2, 128), (7, 1, 64)])
 def test_shapes_and_ragged_lengths(Hq, Hkv, D):
+    """Group sizes G = Hq/Hkv from 1 to 8, powers of two or not (40/8 and 32/4 are the head shapes of the other
+    two models the paper serves, section 5.1)."""
     L = [0, 0, 1, 15, 16, 17, 63, 64, 65, 300, 1000, 129]
     n = [1, 130, 1, 1, 3, 40, 2, 1, 70, 5, 1, 260]
     _compare(si.make_batch("ragged", L=L, n=n, Hq=Hq, Hkv=Hkv, D=D, seed=21, slack_pages=7))
@@ -51,6 +54,13 @@ def test_split_chunks_and_merge():
     b = si.make_batch("splits", L=[700, 0, 1500, 333], n=[1, 200, 90, 2], Hq=32, Hkv=8, D=128, seed=22, slack_pages=3)
     _compare(b, options={"narrow_chunk": 64, "mfma_chunk": 64})
     _compare(b, options={"narrow_chunk": 256, "mfma_chunk": 128, "grid": 3})
+
+
+def test_split_chunks_and_merge_group_of_five():
+    """G = 5: row blocks of 51 rows (255 of 256 columns), narrow tiles up to 3 rows, split and merged."""
+    b = si.make_batch("splits5", L=[700, 0, 1500, 333, 64], n=[1, 200, 90, 2, 3], Hq=40, Hkv=8, D=128, seed=24,
+                      slack_pages=3)
+    _compare(b, options={"narrow_chunk": 256, "mfma_chunk": 512})
 
 
 def test_decode_batch_scaled():

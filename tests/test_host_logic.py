@@ -91,7 +91,7 @@ def replay(items, L, n, Hkv, G, D):
                                   {"force_kind": 1}, {"grid": 7}])
 def test_plan_covers_every_pair_once(opts):
     rng = np.random.default_rng(3)
-    for Hq, Hkv, D in [(32, 8, 128), (8, 2, 64), (8, 8, 128), (8, 1, 64)]:
+    for Hq, Hkv, D in [(32, 8, 128), (8, 2, 64), (8, 8, 128), (8, 1, 64), (40, 8, 128), (6, 2, 64), (7, 1, 128)]:
         L = rng.integers(0, 3000, size=24)
         n = np.where(rng.random(24) < 0.5, 1, rng.integers(1, 400, size=24))
         L[0], n[0] = 0, 1
@@ -142,7 +142,7 @@ def test_plan_rejects_bad_arguments():
         with pytest.raises(ppd.PPDError) as e:
             ppd.ppd_plan_build(32, 8, 128, 16, 64, L, n)
         assert e.value.status == code
-    for shape in [(32, 8, 100, 16, 64), (32, 8, 128, 8, 64), (32, 5, 128, 16, 64), (64, 2, 128, 16, 64),
+    for shape in [(32, 8, 100, 16, 64), (32, 8, 128, 8, 64), (32, 5, 128, 16, 64), (64, 2, 128, 16, 64), (9, 1, 128, 16, 64),
                   (32, 8, 128, 16, 0)]:
         with pytest.raises(ppd.PPDError) as e:
             ppd.ppd_plan_build(*shape, [5], [1])
