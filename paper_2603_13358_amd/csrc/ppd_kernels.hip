@@ -20,6 +20,7 @@ typedef float f32x4 __attribute__((ext_vector_type(4)));
 typedef float f32x16 __attribute__((ext_vector_type(16)));
 typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+typedef short s16x4 __attribute__((ext_vector_type(4)));
 
 #define NEG_INF (-__builtin_inff())
 
@@ -39,7 +40,23 @@ typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
             for (int k_ = 0; k_ < 6; ++k_)                                                                 \
                 atomicAdd(reinterpret_cast<unsigned long long*>((P).counters + 16) + k_, (unsigned long long)tick_sum_[k_]); \
     } while (0)
+// Start and end of every workgroup on the chip-wide 100 MHz clock: sums 12..15 = max of (2^62 - start), max of
+// end, sum of starts, sum of ends.
+#define PPD_WG_SPAN_BEGIN() const long long wg_t0_ = wall_clock64()
+#define PPD_WG_SPAN_END(P)                                                                          \
+    do {                                                                                            \
+        if (threadIdx.x == 0) {                                                                     \
+            const long long t1_ = wall_clock64();                                                   \
+            unsigned long long* c_ = reinterpret_cast<unsigned long long*>((P).counters + 16);     \
+            atomicMax(c_ + 12, (unsigned long long)((1LL << 62) - wg_t0_));                         \
+            atomicMax(c_ + 13, (unsigned long long)t1_);                                            \
+            atomicAdd(c_ + 14, (unsigned long long)wg_t0_);                                         \
+            atomicAdd(c_ + 15, (unsigned long long)t1_);                                            \
+        }                                                                                           \
+    } while (0)
 #else
+#define PPD_WG_SPAN_BEGIN() do {} while (0)
+#define PPD_WG_SPAN_END(P) do {} while (0)
 #define PPD_TICK_DECL() do {} while (0)
 #define PPD_TICK(k) do {} while (0)
 #define PPD_TICK_FLUSH(P) do {} while (0)
@@ -406,8 +423,8 @@ __device__ __forceinline__ void mfma_item(const KParams& P, const ppd_work_item&
 // ---------------------------------------------------------------------------------------------------
 // Narrow tile: rows*G <= 16 query columns (decode: 1 row x G heads).  HBM-bound: each of the waves
 // streams its own share of the key range straight from the pool into MFMA operand registers
-// (v_mfma_f32_16x16x32_bf16; 32 tokens = 2 pages per step, one step prefetched), then the waves'
-// (o, m, l) are combined through LDS.
+// (v_mfma_f32_16x16x32_bf16 for S^T, v_mfma_f32_16x16x16_bf16 for O^T; one page per step, three steps
+// prefetched), then the waves' (o, m, l) are combined through LDS.
 // ---------------------------------------------------------------------------------------------------
 template <int HD>
 __device__ __forceinline__ void narrow_item(const KParams& P, const ppd_work_item& it, char* smem) {
@@ -441,9 +458,9 @@ __device__ __forceinline__ void narrow_item(const KParams& P, const ppd_work_ite
 
     const int32_t* pt_row = P.page_tables + (int64_t)it.seq * P.max_pages;
     const int last_page = (it.kv_total - 1) >> 4;
-    const int nsteps = (it.kv_end - it.kv_begin + 31) >> 5;
+    const int nsteps = (it.kv_end - it.kv_begin + kPage - 1) >> 4;  // one page per step
     const int s_lo = wave * nsteps / kWaves, s_hi = (wave + 1) * nsteps / kWaves;
-    const int wave_first_page = (it.kv_begin >> 4) + s_lo * 2;
+    const int wave_first_page = (it.kv_begin >> 4) + s_lo;
     const int64_t head_off = (int64_t)it.kvh * (kPage * HD);
     const int64_t v_off = (int64_t)P.Hkv * (kPage * HD);
 
@@ -457,63 +474,50 @@ __device__ __forceinline__ void narrow_item(const KParams& P, const ppd_work_ite
     int ids_cur = 0, ids_nxt = 0;
     auto load_ids = [&](int batch) { return load_page_id(pt_row, wave_first_page + batch * 64 + lane, last_page); };
     struct StepRegs {
-        u32x4 k[2][KS];  // K operand of the step's two pages
-        u32x4 v[DBN];    // V^T operand, one per 16-row d block
+        u32x4 k[KS];    // K operand of the page: 16 tokens x 32 d per k-step
+        u32x2 v[DBN];   // V^T operand: 4 tokens of one d, one per 16-row d block
     };
-    StepRegs ra, rb;
+    StepRegs r0, r1, r2, r3;
     const int my_steps = s_hi - s_lo;
     auto issue_step = [&](int k, StepRegs& r) {  // k = step index relative to s_lo
-        if ((k & 31) == 0 && k > 0) {
+        if ((k & 63) == 0 && k > 0) {
             ids_cur = ids_nxt;
-            if (k + 32 < my_steps) ids_nxt = load_ids(k / 32 + 1);
+            if (k + 64 < my_steps) ids_nxt = load_ids(k / 64 + 1);
         }
-        const int li = (2 * k) & 63;
-        const int64_t pa = checked_page(P, __builtin_amdgcn_readlane(ids_cur, li));
-        const int64_t pb = checked_page(P, __builtin_amdgcn_readlane(ids_cur, li + 1));
+        const int64_t pa = checked_page(P, __builtin_amdgcn_readlane(ids_cur, k & 63));
         const uint16_t* ka = P.pool + pa * P.page_stride + head_off;
-        const uint16_t* kb = P.pool + pb * P.page_stride + head_off;
 #pragma unroll
-        for (int ks = 0; ks < KS; ++ks) {
-            r.k[0][ks] = *reinterpret_cast<const u32x4*>(ka + (ks * 4 + g4) * 128 + c16 * 8);
-            r.k[1][ks] = *reinterpret_cast<const u32x4*>(kb + (ks * 4 + g4) * 128 + c16 * 8);
-        }
+        for (int ks = 0; ks < KS; ++ks) r.k[ks] = *reinterpret_cast<const u32x4*>(ka + (ks * 4 + g4) * 128 + c16 * 8);
         const int voff = ((g4 >> 1) * HD + c16) * 8 + (g4 & 1) * 4;
 #pragma unroll
-        for (int db = 0; db < DBN; ++db) {
-            const u32x2 a = *reinterpret_cast<const u32x2*>(ka + v_off + voff + db * 128);
-            const u32x2 b = *reinterpret_cast<const u32x2*>(kb + v_off + voff + db * 128);
-            r.v[db] = u32x4{a[0], a[1], b[0], b[1]};
-        }
+        for (int db = 0; db < DBN; ++db) r.v[db] = *reinterpret_cast<const u32x2*>(ka + v_off + voff + db * 128);
     };
     auto compute_step = [&](int k, StepRegs& r) {
-        f32x4 sa = {0.f, 0.f, 0.f, 0.f}, sb = {0.f, 0.f, 0.f, 0.f};
+        f32x4 sa = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-        for (int ks = 0; ks < KS; ++ks) {
-            sa = __builtin_amdgcn_mfma_f32_16x16x32_bf16(as_bf16x8(r.k[0][ks]), qreg[ks], sa, 0, 0, 0);
-            sb = __builtin_amdgcn_mfma_f32_16x16x32_bf16(as_bf16x8(r.k[1][ks]), qreg[ks], sb, 0, 0, 0);
-        }
-        // sa[i]: token 4*g4 + i of the step's first page; sb[i]: same of its second page
-        const int t0 = it.kv_begin + (s_lo + k) * 32;
-        const bool masked = t0 + 31 > min_limit || t0 + 32 > it.kv_end;
+        for (int ks = 0; ks < KS; ++ks)
+            sa = __builtin_amdgcn_mfma_f32_16x16x32_bf16(as_bf16x8(r.k[ks]), qreg[ks], sa, 0, 0, 0);
+        // sa[i]: token 4*g4 + i of the page
+        const int t0 = it.kv_begin + (s_lo + k) * kPage;
+        const bool masked = t0 + kPage - 1 > min_limit || t0 + kPage > it.kv_end;
         if (masked) {
 #pragma unroll
             for (int i = 0; i < 4; ++i) {
-                const int pa = t0 + 4 * g4 + i, pb = pa + 16;
+                const int pa = t0 + 4 * g4 + i;
                 if (pa > limit || pa >= it.kv_end) sa[i] = NEG_INF;
-                if (pb > limit || pb >= it.kv_end) sb[i] = NEG_INF;
             }
-            if (t0 + 32 > it.kv_total) {  // rows of the last page that were never written
+            if (t0 + kPage > it.kv_total) {  // rows of the last page that were never written
 #pragma unroll
                 for (int db = 0; db < DBN; ++db) {
 #pragma unroll
-                    for (int e = 0; e < 8; ++e) {
-                        const int pos = t0 + (e >> 2) * 16 + 4 * g4 + (e & 3);
+                    for (int e = 0; e < 4; ++e) {
+                        const int pos = t0 + 4 * g4 + e;
                         if (pos >= it.kv_total) r.v[db][e >> 1] &= (e & 1) ? 0x0000FFFFu : 0xFFFF0000u;
                     }
                 }
             }
         }
-        float mx = fmaxf(fmaxf(fmaxf(sa[0], sa[1]), fmaxf(sa[2], sa[3])), fmaxf(fmaxf(sb[0], sb[1]), fmaxf(sb[2], sb[3])));
+        float mx = fmaxf(fmaxf(sa[0], sa[1]), fmaxf(sa[2], sa[3]));
         mx = fmaxf(mx, xor_shuffle(mx, 16));
         mx = max_halves(mx);
         const float m_new = fmaxf(m_run, mx);
@@ -526,31 +530,39 @@ __device__ __forceinline__ void narrow_item(const KParams& P, const ppd_work_ite
             m_run = m_new;
         }
         const float mc = m_run == NEG_INF ? 0.f : m_run * c;
-        float p[8];
+        float p[4];
 #pragma unroll
-        for (int i = 0; i < 4; ++i) {
-            p[i] = fast_exp2(__builtin_fmaf(sa[i], c, -mc));
-            p[4 + i] = fast_exp2(__builtin_fmaf(sb[i], c, -mc));
-        }
-        l_run += ((p[0] + p[1]) + (p[2] + p[3])) + ((p[4] + p[5]) + (p[6] + p[7]));
-        const u32x4 pw = {pack_bf16(p[0], p[1]), pack_bf16(p[2], p[3]), pack_bf16(p[4], p[5]), pack_bf16(p[6], p[7])};
-        const bf16x8 pb8 = as_bf16x8(pw);
+        for (int i = 0; i < 4; ++i) p[i] = fast_exp2(__builtin_fmaf(sa[i], c, -mc));
+        l_run += (p[0] + p[1]) + (p[2] + p[3]);
+        const u32x2 pw = {pack_bf16(p[0], p[1]), pack_bf16(p[2], p[3])};
+        const s16x4 pb4 = __builtin_bit_cast(s16x4, pw);
 #pragma unroll
         for (int db = 0; db < DBN; ++db)
-            oacc[db] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(as_bf16x8(r.v[db]), pb8, oacc[db], 0, 0, 0);
+            oacc[db] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(__builtin_bit_cast(s16x4, r.v[db]), pb4, oacc[db], 0, 0, 0);
     };
 
+    // three pages (24 KiB at D = 128) are in flight while one is being computed; the four register sets rotate
     if (my_steps > 0) {
         ids_cur = load_ids(0);
-        if (my_steps > 32) ids_nxt = load_ids(1);
-        issue_step(0, ra);
+        if (my_steps > 64) ids_nxt = load_ids(1);
+        issue_step(0, r0);
+        if (1 < my_steps) issue_step(1, r1);
+        if (2 < my_steps) issue_step(2, r2);
     }
-    for (int k = 0; k < my_steps; k += 2) {  // one step always in flight; registers alternate ra / rb
-        if (k + 1 < my_steps) issue_step(k + 1, rb);
-        compute_step(k, ra);
+    for (int k = 0; k < my_steps; k += 4) {
+        if (k + 3 < my_steps) issue_step(k + 3, r3);
+        compute_step(k, r0);
         if (k + 1 < my_steps) {
-            if (k + 2 < my_steps) issue_step(k + 2, ra);
-            compute_step(k + 1, rb);
+            if (k + 4 < my_steps) issue_step(k + 4, r0);
+            compute_step(k + 1, r1);
+        }
+        if (k + 2 < my_steps) {
+            if (k + 5 < my_steps) issue_step(k + 5, r1);
+            compute_step(k + 2, r2);
+        }
+        if (k + 3 < my_steps) {
+            if (k + 6 < my_steps) issue_step(k + 6, r2);
+            compute_step(k + 3, r3);
         }
     }
     l_run += xor_shuffle(l_run, 16);
@@ -604,6 +616,7 @@ __global__ __launch_bounds__(kThreads, 2) void ppd_mixed_kernel(const KParams P)
     // Dynamic LDS: kStages stages of 4 pages of K and as many of V for the MFMA path (96 KiB at HD = 128 with
     // three stages); the narrow path's combine buffer (kWaves * 16 * (HD+2) floats) uses the front of it.
     extern __shared__ __attribute__((aligned(16))) char smem[];
+    PPD_WG_SPAN_BEGIN();
     __shared__ int s_next_slot;
     volatile int* s_next = &s_next_slot;
     const int tid = threadIdx.x;
@@ -672,6 +685,7 @@ __global__ __launch_bounds__(kThreads, 2) void ppd_mixed_kernel(const KParams P)
         else
             mfma_item<HD>(P, it, smem);
     }
+    PPD_WG_SPAN_END(P);
     if (tid == 0) {
         // the last workgroup to run out of work re-arms the cursors for the next launch
         const unsigned done = atomicAdd(&P.counters[10], 1u);
