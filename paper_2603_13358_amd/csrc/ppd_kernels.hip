@@ -11,6 +11,10 @@
 
 #include "ppd_internal.h"
 
+#ifndef PPD_PINGPONG
+#define PPD_PINGPONG 1  // 0: all waves take the loop barrier at the same place; 1: waves 4..7 late; 2: odd waves late
+#endif
+
 namespace ppd {
 
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
@@ -159,6 +163,7 @@ __device__ __forceinline__ void mfma_item(const KParams& P, const ppd_work_item&
     constexpr int GPP = PB / 16;               // 16-byte granules per block
     constexpr int KBYTES = 4 * PB;             // one stage: 4 pages of K (or of V)
     constexpr int NS = kStages;
+    constexpr int NSV = kStages + (PPD_PINGPONG ? 1 : 0);  // the late half of the waves reads V one barrier later
     constexpr int VRING = NS * KBYTES;         // LDS: K ring at 0, V ring behind it
     constexpr int ROUNDS = 4 * GPP / kThreads; // granules of K (and of V) each thread moves per tile
     constexpr int KS = HD / 16;                // k-steps of S^T = K Q^T
@@ -198,7 +203,7 @@ __device__ __forceinline__ void mfma_item(const KParams& P, const ppd_work_item&
     // caps a row-block tile at kMaxMfmaChunk keys); a tile reads its four ids with one broadcast LDS read.  Nothing in
     // the loop then depends on a page-table load, so no wait on the memory counter is needed there.
     struct TilePages { int p[4]; };
-    int* lds_ids = reinterpret_cast<int*>(smem + 2 * NS * KBYTES);
+    int* lds_ids = reinterpret_cast<int*>(smem + (NS + NSV) * KBYTES);
     for (int i = tid; i < ntiles * 4; i += kThreads)
         lds_ids[i] = (int)checked_page(P, load_page_id(pt_row, first_page + i, last_page));
     auto tile_pages = [&](int ti) {
@@ -303,15 +308,40 @@ __device__ __forceinline__ void mfma_item(const KParams& P, const ppd_work_item&
     if (wave_active) qk_tile(0, s_cur);
     lds_barrier();  // K stage 0 is overwritten by the first iteration's loads
     int st_cur = 0;   // ti % NS
+    int sv_cur = 0;   // ti % NSV: V stage of tile ti
+    // Two waves share a SIMD.  Left alone they run the same instruction mix in lockstep (both issue MFMAs,
+    // then both issue exponentials) and each pipe idles half of the time.  The "late" half of the waves
+    // takes the loop's barrier in the middle of its iteration instead of at the end, which locks it half an
+    // iteration behind the other half: one wave's S^T MFMAs then run next to the other's exponentials.  The late
+    // waves read V(ti) after the barrier at which the early waves start loading V(ti + NS), hence one more V stage.
+#if PPD_PINGPONG == 2
+    const bool late = (wave & 1) != 0;
+#elif PPD_PINGPONG == 1
+    const bool late = wave >= kWaves / 2;
+#else
+    const bool late = false;
+#endif
 
     PPD_TICK_DECL();
     for (int ti = 0; ti < ntiles; ++ti) {
         const int st_nxt = st_cur + 1 == NS ? 0 : st_cur + 1;            // (ti + 1) % NS
-        const int st_prv = st_cur == 0 ? NS - 1 : st_cur - 1;            // (ti + NS - 1) % NS
+        const int sv_nxt = sv_cur + 1 == NSV ? 0 : sv_cur + 1;           // (ti + 1) % NSV
+        const int sv_far = (sv_cur + NS - 1) % NSV;                       // (ti + NS - 1) % NSV
         const bool full_issue = ti + NS < ntiles;
-        if (ti + NS - 1 < ntiles) load_block(tile_pages(ti + NS - 1), VRING + st_prv * KBYTES, v_off);
+        if (ti + NS - 1 < ntiles) load_block(tile_pages(ti + NS - 1), VRING + sv_far * KBYTES, v_off);
         if (full_issue) load_block(tile_pages(ti + NS), st_cur * KBYTES, 0);
         PPD_TICK(0);
+        // K(ti+2) and V(ti+1) must have landed before the barrier; with NS = 3 the loads issued in this iteration
+        // may stay in flight
+        auto close_iteration = [&]() {
+            if (NS == 3 && full_issue)
+                wait_older_loads();
+            else
+                wait_all_loads();
+            if (ti + 1 < ntiles) fix_v_tail(ti + 1, VRING + sv_nxt * KBYTES);
+            lds_barrier();
+        };
+        float mc = 0.f;
         if (wave_active) {
             const int tile_base = it.kv_begin + ti * kTileTokens;
             if (tile_base + kTileTokens - 1 > wmin_limit) {  // causal boundary crosses this tile
@@ -340,12 +370,15 @@ __device__ __forceinline__ void mfma_item(const KParams& P, const ppd_work_item&
                     for (int i = 0; i < 16; ++i) oacc[db][i] *= alpha;
                 m_run = m_new;
             }
-            const float mc = m_run == NEG_INF ? 0.f : m_run * c;
+            mc = m_run == NEG_INF ? 0.f : m_run * c;
             PPD_TICK(1);
             // S^T of the next tile (matrix pipe) next to the exponentials of this one (vector pipe)
             if (ti + 1 < ntiles) qk_tile(st_nxt, s_nxt);
             PPD_TICK(2);
-            const char* vb = smem + st_cur * KBYTES + v_lane_off;
+        }
+        if (late) close_iteration();
+        if (wave_active) {
+            const char* vb = smem + sv_cur * KBYTES + v_lane_off;
             float psum = 0.f;
 #pragma unroll
             for (int tb = 0; tb < 2; ++tb)
@@ -373,15 +406,9 @@ __device__ __forceinline__ void mfma_item(const KParams& P, const ppd_work_item&
             for (int tb = 0; tb < 2; ++tb) s_cur[tb] = s_nxt[tb];
         }
         PPD_TICK(3);
-        // K(ti+2) and V(ti+1) must have landed; with NS = 3 the loads issued in this iteration may stay in flight
-        if (NS == 3 && full_issue)
-            wait_older_loads();
-        else
-            wait_all_loads();
-        if (ti + 1 < ntiles) fix_v_tail(ti + 1, VRING + st_nxt * KBYTES);
+        if (!late) close_iteration();
         st_cur = st_nxt;
-        PPD_TICK(4);
-        lds_barrier();
+        sv_cur = sv_nxt;
         PPD_TICK(5);
     }
     PPD_TICK_FLUSH(P);
@@ -858,7 +885,8 @@ __global__ __launch_bounds__(kSmallThreads) void ppd_kv_append_kernel(const uint
 
 // ---------------------------------------------------------------------------------------------------
 static size_t mixed_lds_bytes(int head_dim) {
-    const size_t rings = (size_t)2 * kStages * 4 * kPage * head_dim * 2 + (kMaxMfmaChunk / kPage) * 4;  // + page ids of one row-block tile
+    const size_t rings = (size_t)(2 * kStages + (PPD_PINGPONG ? 1 : 0)) * 4 * kPage * head_dim * 2 +
+                         (kMaxMfmaChunk / kPage) * 4;  // + page ids of one row-block tile
     const size_t combine = (size_t)kWaves * kNarrowCols * (head_dim + 2) * sizeof(float);
     return rings > combine ? rings : combine;
 }
