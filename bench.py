@@ -360,11 +360,23 @@ def main():
     ap.add_argument("--landing", action="store_true", help="time the multi-layer KV landing of one request and exit")
     ap.add_argument("--sweeps", action="store_true",
                     help="interference sweeps (batch size, context, 4 prefills, chunked append-prefill) and exit")
+    ap.add_argument("--read-probe", action="store_true",
+                    help="run the stand-alone read-bandwidth probe (contiguous and paged pattern) and exit")
     ap.add_argument("--copy-probe", action="store_true",
                     help="run a plain 1 GiB device copy a few times and exit (calibrates HBM byte counters)")
     args = ap.parse_args()
     if args.gpus != 1:
         raise SystemExit("bench.py measures one GPU: the step has no multi-GPU part in this build (--gpus 1 only)")
+    if args.read_probe:
+        # a child process of its own: nothing in this process has touched the GPU yet
+        import subprocess
+        from paper_2603_13358_amd.build import PROBE_BIN, build_probe
+        if not os.path.exists(PROBE_BIN):
+            build_probe()
+        res = subprocess.run([PROBE_BIN], stdout=subprocess.PIPE, text=True, check=True)
+        lines = [json.loads(l) for l in res.stdout.splitlines() if l.startswith("{")]
+        print(json.dumps({"workload": "read_probe", "hbm_peak_GBs": HBM_PEAK_GBS, "patterns": lines}))
+        return
     import torch
     if not torch.cuda.is_available():
         raise SystemExit("bench.py needs an MI355X: the library has no CPU path")

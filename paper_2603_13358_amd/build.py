@@ -39,7 +39,25 @@ def build_lib(force=True, verbose=False):
     return LIB
 
 
+PROBE_SRC = os.path.join(CSRC, "probes", "read_probe.hip")
+PROBE_BIN = os.path.join(HERE, "read_probe")
+
+
+def build_probe(force=True):
+    """Compiles the stand-alone read-bandwidth probe (bench.py --read-probe runs it)."""
+    if not force and os.path.exists(PROBE_BIN) and os.path.getmtime(PROBE_BIN) >= os.path.getmtime(PROBE_SRC):
+        return PROBE_BIN
+    hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
+    cmd = [hipcc, "--offload-arch=gfx950", "-O3", "-std=c++17", "-Xclang", "-target-feature", "-Xclang",
+           "-packed-fp32-ops", PROBE_SRC, "-o", PROBE_BIN]
+    res = subprocess.run(cmd, stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True)
+    if res.returncode != 0:
+        raise RuntimeError("hipcc failed:\n" + res.stdout)
+    return PROBE_BIN
+
+
 if __name__ == "__main__":
     build_lib(force=True, verbose=True)
     print("built", LIB)
+    print("built", build_probe())
     sys.exit(0)

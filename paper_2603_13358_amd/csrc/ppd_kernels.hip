@@ -506,6 +506,8 @@ __device__ __forceinline__ void narrow_item(const KParams& P, const ppd_work_ite
     };
     StepRegs r0, r1, r2, r3;
     const int my_steps = s_hi - s_lo;
+    // K and V are read once: non-temporal loads (no reuse to keep in the caches) stream ~12 % faster than plain
+    // ones on this pattern.
     auto issue_step = [&](int k, StepRegs& r) {  // k = step index relative to s_lo
         if ((k & 63) == 0 && k > 0) {
             ids_cur = ids_nxt;
@@ -514,10 +516,12 @@ __device__ __forceinline__ void narrow_item(const KParams& P, const ppd_work_ite
         const int64_t pa = checked_page(P, __builtin_amdgcn_readlane(ids_cur, k & 63));
         const uint16_t* ka = P.pool + pa * P.page_stride + head_off;
 #pragma unroll
-        for (int ks = 0; ks < KS; ++ks) r.k[ks] = *reinterpret_cast<const u32x4*>(ka + (ks * 4 + g4) * 128 + c16 * 8);
+        for (int ks = 0; ks < KS; ++ks)
+            r.k[ks] = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(ka + (ks * 4 + g4) * 128 + c16 * 8));
         const int voff = ((g4 >> 1) * HD + c16) * 8 + (g4 & 1) * 4;
 #pragma unroll
-        for (int db = 0; db < DBN; ++db) r.v[db] = *reinterpret_cast<const u32x2*>(ka + v_off + voff + db * 128);
+        for (int db = 0; db < DBN; ++db)
+            r.v[db] = __builtin_nontemporal_load(reinterpret_cast<const u32x2*>(ka + v_off + voff + db * 128));
     };
     auto compute_step = [&](int k, StepRegs& r) {
         f32x4 sa = {0.f, 0.f, 0.f, 0.f};

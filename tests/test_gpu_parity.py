@@ -63,6 +63,18 @@ def test_split_chunks_and_merge_group_of_five():
     _compare(b, options={"narrow_chunk": 256, "mfma_chunk": 512})
 
 
+@pytest.mark.parametrize("options", [{"pref_mode": 0}, {"pref_mode": 1}, {"pref_mode": 3}, {"narrow_cus": 0},
+                                     {"narrow_cus": 5}, {"narrow_cus": 32}, {"grid": 1}, {"grid": 40, "narrow_cus": 16}])
+def test_scheduling_options_do_not_change_the_result(options):
+    """Which workgroup takes which tile (kind preference, split of the compute units, grid size) is scheduling
+    only: same tiles, same partials, bitwise the same output."""
+    b = si.make_batch("sched", L=[900, 0, 2500, 333, 64, 4000, 17], n=[1, 150, 70, 2, 3, 1, 1], Hq=32, Hkv=8, D=128,
+                      seed=25, slack_pages=3)
+    base, _ = _compare(b, options={"narrow_chunk": 512, "mfma_chunk": 512})
+    out, _ = _compare(b, options=dict(options, narrow_chunk=512, mfma_chunk=512))
+    assert np.array_equal(out, base)
+
+
 def test_decode_batch_scaled():
     _compare(si.cfg2_decode(0, B=12, Lmin=100, Lmax=3000))
 
