@@ -246,10 +246,13 @@ __device__ __forceinline__ void mfma_item(const KParams& P, const ppd_work_item&
     // Loads retire in order: waiting until at most `newer` are outstanding guarantees everything issued
     // before those has landed in LDS.
     auto wait_all_loads = [&]() { asm volatile("s_waitcnt vmcnt(0)" ::: "memory"); };
-    auto wait_older_loads = [&]() {  // all but the 2*ROUNDS loads of the current iteration
-        if (ROUNDS == 1) asm volatile("s_waitcnt vmcnt(2)" ::: "memory");
-        if (ROUNDS == 2) asm volatile("s_waitcnt vmcnt(4)" ::: "memory");
-        if (ROUNDS == 4) asm volatile("s_waitcnt vmcnt(8)" ::: "memory");
+    // all but the loads of the last NS - 2 iterations (2*ROUNDS each): K(ti+2) and V(ti+1) were issued before those
+    auto wait_older_loads = [&]() {
+        constexpr int kKeep = (NS - 2) * 2 * ROUNDS;
+        static_assert(kKeep < 64, "the memory counter has six bits");
+        // s_waitcnt immediate on gfx9: vmcnt in bits 3:0 and 15:14, expcnt (7 = no wait) in 6:4, lgkmcnt (15) in 11:8
+        __builtin_amdgcn_s_waitcnt((kKeep & 15) | ((kKeep >> 4) << 14) | (7 << 4) | (15 << 8));
+        asm volatile("" ::: "memory");
     };
 
     f32x16 oacc[DB];
@@ -334,7 +337,7 @@ __device__ __forceinline__ void mfma_item(const KParams& P, const ppd_work_item&
         // K(ti+2) and V(ti+1) must have landed before the barrier; with NS = 3 the loads issued in this iteration
         // may stay in flight
         auto close_iteration = [&]() {
-            if (NS == 3 && full_issue)
+            if (full_issue)  // then the last NS - 2 iterations all issued their full share
                 wait_older_loads();
             else
                 wait_all_loads();
@@ -816,6 +819,10 @@ __global__ __launch_bounds__(kSmallThreads) void ppd_merge_kernel(const MergePar
 //    write 128 contiguous bytes.  V: a granule is 8 tokens of one d; when the 8 tokens fill one aligned
 //    granule (the common case for prefill) each thread writes it whole, otherwise element by element.
 // ---------------------------------------------------------------------------------------------------
+// source and pool are each touched once: non-temporal loads and stores (the landing of a whole request runs 7 %
+// faster with them)
+#define APPEND_LOAD(p) __builtin_nontemporal_load(p)
+#define APPEND_STORE(v, p) __builtin_nontemporal_store(v, p)
 __global__ __launch_bounds__(kSmallThreads) void ppd_kv_append_kernel(const uint16_t* __restrict__ k,
                                                                  const uint16_t* __restrict__ v,
                                                                  uint16_t* __restrict__ pool,
@@ -857,8 +864,8 @@ __global__ __launch_bounds__(kSmallThreads) void ppd_kv_append_kernel(const uint
 #pragma unroll
         for (int i = 1; i < 8; ++i) s = tok == i ? sl[i] : s;
         if (s < 0) continue;
-        const u32x4 val = *reinterpret_cast<const u32x4*>(k + (t0 + tok) * HD + hh * D + c * 8);
-        *reinterpret_cast<u32x4*>(pool + (s >> 4) * S + koff + c * (kPage * 8) + (int)(s & 15) * 8) = val;
+        const u32x4 val = APPEND_LOAD(reinterpret_cast<const u32x4*>(k + (t0 + tok) * HD + hh * D + c * 8));
+        APPEND_STORE(val, reinterpret_cast<u32x4*>(pool + (s >> 4) * S + koff + c * (kPage * 8) + (int)(s & 15) * 8));
     }
     // V: work unit = d
     if (aligned) {
@@ -868,11 +875,11 @@ __global__ __launch_bounds__(kSmallThreads) void ppd_kv_append_kernel(const uint
             uint32_t w[4];
 #pragma unroll
             for (int e = 0; e < 4; ++e) {
-                const uint32_t lo = v[(t0 + 2 * e) * HD + hh * D + d];
-                const uint32_t hi = v[(t0 + 2 * e + 1) * HD + hh * D + d];
+                const uint32_t lo = APPEND_LOAD(v + (t0 + 2 * e) * HD + hh * D + d);
+                const uint32_t hi = APPEND_LOAD(v + (t0 + 2 * e + 1) * HD + hh * D + d);
                 w[e] = lo | (hi << 16);
             }
-            *reinterpret_cast<u32x4*>(pool + page * S + voff + half * (D * 8) + d * 8) = u32x4{w[0], w[1], w[2], w[3]};
+            APPEND_STORE((u32x4{w[0], w[1], w[2], w[3]}), reinterpret_cast<u32x4*>(pool + page * S + voff + half * (D * 8) + d * 8));
         }
     } else {
         for (int u = tid; u < D * 8; u += kSmallThreads) {
