@@ -140,10 +140,11 @@ __device__ __forceinline__ u32x4 zero_unwritten(u32x4 v, int first, int kv_total
 // staging registers), each in a ring of kStages stages.  The loop is software-pipelined: iteration i
 // computes S^T of tile i+1 while it runs the softmax and the PV product of tile i, so that matrix and
 // vector instructions of one wave are independent of each other and can overlap.  With NS = kStages:
-//   iteration i:  loads K(i+NS) -> Kring[i % NS], V(i+NS-1) -> Vring[(i+NS-1) % NS]
-//                 reads K(i+1) from Kring[(i+1) % NS], V(i) from Vring[i % NS]
+//   iteration i:  loads K(i+NS) -> Kring[i % NS], V(i+NS-1) -> Vring[(i+NS-1) % NSV]
+//                 reads K(i+1) from Kring[(i+1) % NS], V(i) from Vring[i % NSV]
 //   one barrier per iteration, after K(i+2) and V(i+1) have landed (loads issued NS-2 iterations later may
-//   still be in flight).
+//   still be in flight).  The upper half of the waves takes that barrier in the middle of its iteration (see
+//   the loop), and the V ring has one stage more than the K ring (NSV = NS + 1) to allow it.
 // ---------------------------------------------------------------------------------------------------
 // 16 bytes per lane from global memory straight into LDS: lane i of the wave writes lds_base + 16*i
 // (lds_base is wave-uniform and travels in M0).  Written as inline asm so that the compiler's wait-count pass
