@@ -150,11 +150,12 @@ __device__ __forceinline__ u32x4 zero_unwritten(u32x4 v, int first, int kv_total
 // (lds_base is wave-uniform and travels in M0).  Written as inline asm so that the compiler's wait-count pass
 // does not see an LDS write it would have to order every later LDS read behind (it would drain the memory
 // counter before the first operand read of each tile); completion is awaited explicitly with s_waitcnt vmcnt.
-__device__ __forceinline__ void lds_direct_load16(const void* gsrc, const char* lds_base) {
+// The global address is a wave-uniform base (scalar register pair) plus a 32-bit byte offset per lane.
+__device__ __forceinline__ void lds_direct_load16(const void* gbase, uint32_t lane_off, const char* lds_base) {
     const uint32_t lds_off = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) const char*)lds_base;
-    asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, off"
+    asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1"
                  :
-                 : "v"(gsrc), "s"(__builtin_amdgcn_readfirstlane(lds_off))
+                 : "v"(lane_off), "s"(gbase), "s"(__builtin_amdgcn_readfirstlane(lds_off))
                  : "memory", "m0");
 }
 
@@ -203,31 +204,33 @@ __device__ __forceinline__ void mfma_item(const KParams& P, const ppd_work_item&
     // Page ids of the whole key range go to LDS once, checked, before the loop (at most 2048: the planner
     // caps a row-block tile at kMaxMfmaChunk keys); a tile reads its four ids with one broadcast LDS read.  Nothing in
     // the loop then depends on a page-table load, so no wait on the memory counter is needed there.
-    struct TilePages { int p[4]; };
+    // Granule gid = r*256 + tid ... of the tile's 4 page blocks goes to LDS byte gid*16 of the stage: a wave writes
+    // 1 KiB contiguous per round, which is what a wave-wide LDS-direct load does.  The page a wave reads in
+    // round r is wave-uniform, s = r * (kThreads / GPP) + (wave * 64) / GPP, and the lane's offset inside the
+    // page block is the same in every round: the load's address is a scalar base plus a per-lane constant.
+    constexpr int PAGES_PER_ROUND = kThreads / GPP;
+    static_assert(kThreads % GPP == 0 && ROUNDS * PAGES_PER_ROUND == 4, "one round covers whole page blocks");
+    const int page_sel = (wave * 64) / GPP;
+    const uint32_t lane_off = (uint32_t)(tid % GPP) * 16u;
+    struct TilePages { int p[ROUNDS]; };  // the pages this wave loads from, one per round
     int* lds_ids = reinterpret_cast<int*>(smem + (NS + NSV) * KBYTES);
     for (int i = tid; i < ntiles * 4; i += kThreads)
         lds_ids[i] = (int)checked_page(P, load_page_id(pt_row, first_page + i, last_page));
     auto tile_pages = [&](int ti) {
-        const u32x4 v = *reinterpret_cast<const u32x4*>(lds_ids + ti * 4);
         TilePages t;
 #pragma unroll
-        for (int s = 0; s < 4; ++s) t.p[s] = __builtin_amdgcn_readfirstlane((int)v[s]);
+        for (int r = 0; r < ROUNDS; ++r)
+            t.p[r] = __builtin_amdgcn_readfirstlane(lds_ids[ti * 4 + r * PAGES_PER_ROUND + page_sel]);
         return t;
     };
     // Workgroup barrier for LDS traffic only: unlike __syncthreads() it does not drain the memory counter, so
     // LDS-direct loads of later tiles stay in flight across it.
     auto lds_barrier = [&]() { asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory"); };
-    // Granule gid = r*256 + tid of the tile's 4 page blocks goes to LDS byte gid*16 of the stage: a wave
-    // writes 1 KiB contiguous per round, which is what a wave-wide LDS-direct load does.  The page a thread
-    // reads in round r is the same for its whole wave: s = (r*kThreads + wave*64) / GPP.
     auto load_block = [&](const TilePages& t, int lds_byte, int64_t kv_off) {
 #pragma unroll
         for (int r = 0; r < ROUNDS; ++r) {
-            const int within = (r * kThreads + tid) % GPP;
-            const int s = (r * kThreads + wave * 64) / GPP;
-            const int page = s == 0 ? t.p[0] : s == 1 ? t.p[1] : s == 2 ? t.p[2] : t.p[3];
-            const uint16_t* src = P.pool + (int64_t)page * P.page_stride + head_off + kv_off + within * 8;
-            lds_direct_load16(src, smem + lds_byte + r * (kThreads * 16) + wave * 1024);
+            const uint16_t* base = P.pool + (int64_t)t.p[r] * P.page_stride + head_off + kv_off;
+            lds_direct_load16(base, lane_off, smem + lds_byte + r * (kThreads * 16) + wave * 1024);
         }
     };
     // V rows of positions >= kv_total were never written: zero them in LDS (each thread fixes the granules it
