@@ -124,6 +124,7 @@ ppd_status ppd_create(const ppd_shape* shape, int32_t device, ppd_ctx** out) {
     }
     ctx->num_cus = prop.multiProcessorCount > 0 ? prop.multiProcessorCount : 256;
     ctx->opts.num_cus = ctx->num_cus;
+    if ((e = (hipError_t)ppd::prepare_mixed_kernels()) != hipSuccess) return bail(e, "hipFuncSetAttribute");
     if ((e = hipMalloc((void**)&ctx->d_counters, 256)) != hipSuccess) return bail(e, "hipMalloc(counters)");
     if ((e = hipMemset(ctx->d_counters, 0, 256)) != hipSuccess) return bail(e, "hipMemset(counters)");
     for (auto& s : ctx->staging)

@@ -100,6 +100,7 @@ struct MergeParams {
 };
 
 // Launchers (defined in ppd_kernels.hip); stream is a hipStream_t.
+int prepare_mixed_kernels();
 int launch_mixed(const KParams& p, int head_dim, int grid, void* stream);
 int launch_merge(const MergeParams& p, void* stream);
 int launch_kv_append(const uint16_t* k, const uint16_t* v, uint16_t* pool, const int64_t* slots, int64_t T,

@@ -906,18 +906,19 @@ static size_t mixed_lds_bytes(int head_dim) {
     return rings > combine ? rings : combine;
 }
 
+// More than 64 KiB of dynamic LDS has to be allowed per kernel, on the device that is current (ppd_create calls
+// this once per context, with the context's device current).
+int prepare_mixed_kernels() {
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&ppd_mixed_kernel<128>),
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)mixed_lds_bytes(128));
+    if (e == hipSuccess)
+        e = hipFuncSetAttribute(reinterpret_cast<const void*>(&ppd_mixed_kernel<64>),
+                                hipFuncAttributeMaxDynamicSharedMemorySize, (int)mixed_lds_bytes(64));
+    return (int)e;
+}
+
 int launch_mixed(const KParams& p, int head_dim, int grid, void* stream) {
     hipStream_t st = static_cast<hipStream_t>(stream);
-    static bool attr_set = false;
-    if (!attr_set) {  // more than 64 KiB of dynamic LDS has to be allowed once per kernel
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&ppd_mixed_kernel<128>),
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)mixed_lds_bytes(128));
-        if (e == hipSuccess)
-            e = hipFuncSetAttribute(reinterpret_cast<const void*>(&ppd_mixed_kernel<64>),
-                                    hipFuncAttributeMaxDynamicSharedMemorySize, (int)mixed_lds_bytes(64));
-        if (e != hipSuccess) return (int)e;
-        attr_set = true;
-    }
     if (head_dim == 128)
         hipLaunchKernelGGL(ppd_mixed_kernel<128>, dim3(grid), dim3(kThreads), mixed_lds_bytes(128), st, p);
     else
