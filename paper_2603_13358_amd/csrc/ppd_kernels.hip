@@ -12,7 +12,7 @@
 #include "ppd_internal.h"
 
 #ifndef PPD_PINGPONG
-#define PPD_PINGPONG 1  // 0: all waves take the loop barrier at the same place; 1: waves 4..7 late; 2: odd waves late
+#define PPD_PINGPONG 1  // 0: all waves take the loop barrier at the end of the iteration; 1: waves 4..7 mid-iteration
 #endif
 
 namespace ppd {
@@ -137,14 +137,11 @@ __device__ __forceinline__ u32x4 zero_unwritten(u32x4 v, int first, int kv_total
 // MFMA row-block tile: up to kMfmaCols query columns (rows x G heads of one KV head) against keys
 // [kv_begin, kv_end).  kWaves waves x 32 columns; key tiles of 64 tokens (4 pages); v_mfma_f32_32x32x16_bf16 for
 // both products.  K and V tiles go from the pool straight into LDS (global_load_lds, 16 bytes per lane, no
-// staging registers), each in a ring of kStages stages.  The loop is software-pipelined: iteration i
-// computes S^T of tile i+1 while it runs the softmax and the PV product of tile i, so that matrix and
-// vector instructions of one wave are independent of each other and can overlap.  With NS = kStages:
-//   iteration i:  loads K(i+NS) -> Kring[i % NS], V(i+NS-1) -> Vring[(i+NS-1) % NSV]
-//                 reads K(i+1) from Kring[(i+1) % NS], V(i) from Vring[i % NSV]
-//   one barrier per iteration, after K(i+2) and V(i+1) have landed (loads issued NS-2 iterations later may
-//   still be in flight).  The upper half of the waves takes that barrier in the middle of its iteration (see
-//   the loop), and the V ring has one stage more than the K ring (NSV = NS + 1) to allow it.
+// staging registers), each in a ring.  With NS = kStages tiles of prefetch distance and rings of NS + 1 stages:
+//   iteration i:  loads K(i+NS) -> Kring[(i+NS) % (NS+1)], V(i+NS-1) -> Vring[(i+NS-1) % (NS+1)]
+//                 vector phase on S^T(i); matrix phase reads V(i) and K(i+1)
+//   one barrier per iteration, after K(i+2) and V(i+1) have landed (loads issued in the last NS-2 iterations may
+//   still be in flight); half of the waves take it between their two phases (see the loop).
 // ---------------------------------------------------------------------------------------------------
 // 16 bytes per lane from global memory straight into LDS: lane i of the wave writes lds_base + 16*i
 // (lds_base is wave-uniform and travels in M0).  Written as inline asm so that the compiler's wait-count pass
@@ -166,7 +163,8 @@ __device__ __forceinline__ void mfma_item(const KParams& P, const ppd_work_item&
     constexpr int KBYTES = 4 * PB;             // one stage: 4 pages of K (or of V)
     constexpr int NS = kStages;
     constexpr int NSV = kStages + (PPD_PINGPONG ? 1 : 0);  // the late half of the waves reads V one barrier later
-    constexpr int VRING = NS * KBYTES;         // LDS: K ring at 0, V ring behind it
+    constexpr int NSK = kStages + (PPD_PINGPONG ? 1 : 0);  // ... and K as well
+    constexpr int VRING = NSK * KBYTES;        // LDS: K ring at 0, V ring behind it
     constexpr int ROUNDS = 4 * GPP / kThreads; // granules of K (and of V) each thread moves per tile
     constexpr int KS = HD / 16;                // k-steps of S^T = K Q^T
     constexpr int DB = HD / 32;                // 32-row d blocks of O^T
@@ -213,7 +211,7 @@ __device__ __forceinline__ void mfma_item(const KParams& P, const ppd_work_item&
     const int page_sel = (wave * 64) / GPP;
     const uint32_t lane_off = (uint32_t)(tid % GPP) * 16u;
     struct TilePages { int p[ROUNDS]; };  // the pages this wave loads from, one per round
-    int* lds_ids = reinterpret_cast<int*>(smem + (NS + NSV) * KBYTES);
+    int* lds_ids = reinterpret_cast<int*>(smem + (NSK + NSV) * KBYTES);
     for (int i = tid; i < ntiles * 4; i += kThreads)
         lds_ids[i] = (int)checked_page(P, load_page_id(pt_row, first_page + i, last_page));
     auto tile_pages = [&](int ti) {
@@ -284,7 +282,11 @@ __device__ __forceinline__ void mfma_item(const KParams& P, const ppd_work_item&
         for (int ks = 0; ks < KS; ++ks)
 #pragma unroll
             for (int tb = 0; tb < 2; ++tb) {
+#ifdef PPD_DIAG_NO_LDS_OPERANDS  // timing diagnostics only: wrong results
+                bf16x8 a = qreg[(ks + tb) % KS];
+#else
                 bf16x8 a = as_bf16x8(*reinterpret_cast<const u32x4*>(kb + tb * 2 * PB + ks * 512));
+#endif
                 sacc[tb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, qreg[ks], sacc[tb], 0, 0, 0);
             }
     };
@@ -311,32 +313,37 @@ __device__ __forceinline__ void mfma_item(const KParams& P, const ppd_work_item&
     for (int t = 0; t < NS - 1; ++t)
         if (t < ntiles) fix_v_tail(t, VRING + t * KBYTES);
     lds_barrier();
-    f32x16 s_cur[2], s_nxt[2];
+    f32x16 s_cur[2];
     if (wave_active) qk_tile(0, s_cur);
-    lds_barrier();  // K stage 0 is overwritten by the first iteration's loads
+    lds_barrier();  // with rings of NS stages the first iteration's loads overwrite K stage 0
     int st_cur = 0;   // ti % NS
     int sv_cur = 0;   // ti % NSV: V stage of tile ti
-    // Two waves share a SIMD.  Left alone they run the same instruction mix in lockstep (both issue MFMAs,
-    // then both issue exponentials) and each pipe idles half of the time.  The "late" half of the waves
-    // takes the loop's barrier in the middle of its iteration instead of at the end, which locks it half an
-    // iteration behind the other half: one wave's S^T MFMAs then run next to the other's exponentials.  The late
-    // waves read V(ti) after the barrier at which the early waves start loading V(ti + NS), hence one more V stage.
-#if PPD_PINGPONG == 2
-    const bool late = (wave & 1) != 0;
-#elif PPD_PINGPONG == 1
-    const bool late = wave >= kWaves / 2;
+    // Two waves share a SIMD, and a wave issues in order.  An iteration is a vector phase (mask, max, rescale, the
+    // tile's exponentials, packed to bf16) followed by a matrix phase (O^T += V^T P^T of this tile, then S^T of the
+    // next tile into the registers the probabilities have left), each pure, so that one wave's matrix phase can
+    // run under the other's vector phase.  Left alone the two waves would run the same phase at the same time
+    // (the loop barrier aligns them); the "late" half of the waves therefore takes the barrier between its two
+    // phases instead of at the end of the iteration, which locks it half an iteration behind the other half.
+    // A late wave reads V(ti) and K(ti+1) after the barrier at which the early waves start loading V(ti+NS) and
+    // K(ti+1+NS): one more stage in each ring (measured: +4.5 % with the shift, -9 % with pure phases alone).
+#if PPD_PINGPONG
+    const bool late = wave >= kWaves / 2;  // waves w and w + 4 share a SIMD
 #else
     const bool late = false;
 #endif
 
+    u32x4 pw[4];  // the tile's probabilities as bf16, B operand of the four 16-key steps of the PV product
     PPD_TICK_DECL();
     for (int ti = 0; ti < ntiles; ++ti) {
-        const int st_nxt = st_cur + 1 == NS ? 0 : st_cur + 1;            // (ti + 1) % NS
+        const int st_nxt = st_cur + 1 == NSK ? 0 : st_cur + 1;           // (ti + 1) % NSK
+        const int st_far = (st_cur + NS) % NSK;                           // (ti + NS) % NSK
         const int sv_nxt = sv_cur + 1 == NSV ? 0 : sv_cur + 1;           // (ti + 1) % NSV
         const int sv_far = (sv_cur + NS - 1) % NSV;                       // (ti + NS - 1) % NSV
         const bool full_issue = ti + NS < ntiles;
+#ifndef PPD_DIAG_NO_LOOP_LOADS  // timing diagnostics only: the tiles after the first NS read stale LDS
         if (ti + NS - 1 < ntiles) load_block(tile_pages(ti + NS - 1), VRING + sv_far * KBYTES, v_off);
-        if (full_issue) load_block(tile_pages(ti + NS), st_cur * KBYTES, 0);
+        if (full_issue) load_block(tile_pages(ti + NS), st_far * KBYTES, 0);
+#endif
         PPD_TICK(0);
         // K(ti+2) and V(ti+1) must have landed before the barrier; with NS = 3 the loads issued in this iteration
         // may stay in flight
@@ -346,7 +353,9 @@ __device__ __forceinline__ void mfma_item(const KParams& P, const ppd_work_item&
             else
                 wait_all_loads();
             if (ti + 1 < ntiles) fix_v_tail(ti + 1, VRING + sv_nxt * KBYTES);
-            lds_barrier();
+#ifndef PPD_DIAG_NO_LOOP_BARRIER  // timing diagnostics only: the waves then race on the K/V tiles' contents (values
+            lds_barrier();        // only: every address comes from the page ids staged and checked before the loop)
+#endif
         };
         float mc = 0.f;
         if (wave_active) {
@@ -379,39 +388,41 @@ __device__ __forceinline__ void mfma_item(const KParams& P, const ppd_work_item&
             }
             mc = m_run == NEG_INF ? 0.f : m_run * c;
             PPD_TICK(1);
-            // S^T of the next tile (matrix pipe) next to the exponentials of this one (vector pipe)
-            if (ti + 1 < ntiles) qk_tile(st_nxt, s_nxt);
-            PPD_TICK(2);
-        }
-        if (late) close_iteration();
-        if (wave_active) {
-            const char* vb = smem + sv_cur * KBYTES + v_lane_off;
+            // Vector phase: all exponentials of this tile, packed to bf16 at once.  Nothing for the matrix pipe in
+            // it, and nothing for the vector pipe in the matrix phase below, so that the late waves (half an
+            // iteration behind) run their matrix phase under this vector phase and the other way round.
             float psum = 0.f;
 #pragma unroll
-            for (int tb = 0; tb < 2; ++tb)
+            for (int s = 0; s < 4; ++s)
 #pragma unroll
-                for (int i = 0; i < 16; ++i) {
-                    const float p = fast_exp2(__builtin_fmaf(s_cur[tb][i], c, -mc));
-                    s_cur[tb][i] = p;
-                    psum += p;
+                for (int e = 0; e < 4; ++e) {
+                    const int i0 = (s & 1) * 8 + 2 * e;
+                    const float p0 = fast_exp2(__builtin_fmaf(s_cur[s >> 1][i0], c, -mc));
+                    const float p1 = fast_exp2(__builtin_fmaf(s_cur[s >> 1][i0 + 1], c, -mc));
+                    psum += p0 + p1;
+                    pw[s][e] = pack_bf16(p0, p1);
                 }
             l_run += psum;
+            PPD_TICK(2);
+        }
+        __builtin_amdgcn_sched_barrier(0);
+        if (late) close_iteration();
+        if (wave_active) {
+            // Matrix phase: O^T += V^T P^T of this tile, then S^T of the next one into the registers the
+            // probabilities have left.
+            const char* vb = smem + sv_cur * KBYTES + v_lane_off;
 #pragma unroll
             for (int s = 0; s < 4; ++s) {
-                u32x4 pw;
-#pragma unroll
-                for (int e = 0; e < 4; ++e)
-                    pw[e] = pack_bf16(s_cur[s >> 1][(s & 1) * 8 + 2 * e], s_cur[s >> 1][(s & 1) * 8 + 2 * e + 1]);
-                const bf16x8 pb = as_bf16x8(pw);
+                const bf16x8 pb = as_bf16x8(pw[s]);
 #pragma unroll
                 for (int db = 0; db < DB; ++db) {
                     bf16x8 a = as_bf16x8(*reinterpret_cast<const u32x4*>(vb + s * PB + db * 512));
                     oacc[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, pb, oacc[db], 0, 0, 0);
                 }
             }
-#pragma unroll
-            for (int tb = 0; tb < 2; ++tb) s_cur[tb] = s_nxt[tb];
+            if (ti + 1 < ntiles) qk_tile(st_nxt, s_cur);
         }
+        __builtin_amdgcn_sched_barrier(0);
         PPD_TICK(3);
         if (!late) close_iteration();
         st_cur = st_nxt;
@@ -900,7 +911,7 @@ __global__ __launch_bounds__(kSmallThreads) void ppd_kv_append_kernel(const uint
 
 // ---------------------------------------------------------------------------------------------------
 static size_t mixed_lds_bytes(int head_dim) {
-    const size_t rings = (size_t)(2 * kStages + (PPD_PINGPONG ? 1 : 0)) * 4 * kPage * head_dim * 2 +
+    const size_t rings = (size_t)(2 * kStages + (PPD_PINGPONG ? 1 : 0) + (PPD_PINGPONG ? 1 : 0)) * 4 * kPage * head_dim * 2 +
                          (kMaxMfmaChunk / kPage) * 4;  // + page ids of one row-block tile
     const size_t combine = (size_t)kWaves * kNarrowCols * (head_dim + 2) * sizeof(float);
     return rings > combine ? rings : combine;
