@@ -31,6 +31,9 @@ typedef short s16x4 __attribute__((ext_vector_type(4)));
 // Optional phase timing of the MFMA tile loop (build with -DPPD_PHASE_TIMING): shader-clock cycles of wave 0
 // of every workgroup, summed per phase into counters[16..27] as six 64-bit sums.  Off in the product build.
 #ifdef PPD_PHASE_TIMING
+#ifndef PPD_TICK_WAVE
+#define PPD_TICK_WAVE 0  // the wave whose loop phases are timed
+#endif
 #define PPD_TICK_DECL() long long tick_last_ = clock64(); long long tick_sum_[6] = {0, 0, 0, 0, 0, 0}
 #define PPD_TICK(k)                              \
     do {                                         \
@@ -40,7 +43,7 @@ typedef short s16x4 __attribute__((ext_vector_type(4)));
     } while (0)
 #define PPD_TICK_FLUSH(P)                                                                                  \
     do {                                                                                                   \
-        if (threadIdx.x == 0)                                                                              \
+        if (threadIdx.x == PPD_TICK_WAVE * 64)                                                             \
             for (int k_ = 0; k_ < 6; ++k_)                                                                 \
                 atomicAdd(reinterpret_cast<unsigned long long*>((P).counters + 16) + k_, (unsigned long long)tick_sum_[k_]); \
     } while (0)
@@ -214,13 +217,20 @@ __device__ __forceinline__ void mfma_item(const KParams& P, const ppd_work_item&
     int* lds_ids = reinterpret_cast<int*>(smem + (NSK + NSV) * KBYTES);
     for (int i = tid; i < ntiles * 4; i += kThreads)
         lds_ids[i] = (int)checked_page(P, load_page_id(pt_row, first_page + i, last_page));
-    auto tile_pages = [&](int ti) {
-        TilePages t;
+    struct RawPages { int p[ROUNDS]; };  // the same ids as they come from LDS (vector registers)
+    auto tile_pages_raw = [&](int ti) {
+        RawPages t;
 #pragma unroll
-        for (int r = 0; r < ROUNDS; ++r)
-            t.p[r] = __builtin_amdgcn_readfirstlane(lds_ids[ti * 4 + r * PAGES_PER_ROUND + page_sel]);
+        for (int r = 0; r < ROUNDS; ++r) t.p[r] = lds_ids[ti * 4 + r * PAGES_PER_ROUND + page_sel];
         return t;
     };
+    auto to_scalar = [&](const RawPages& v) {
+        TilePages t;
+#pragma unroll
+        for (int r = 0; r < ROUNDS; ++r) t.p[r] = __builtin_amdgcn_readfirstlane(v.p[r]);
+        return t;
+    };
+    auto tile_pages = [&](int ti) { return to_scalar(tile_pages_raw(ti)); };
     // Workgroup barrier for LDS traffic only: unlike __syncthreads() it does not drain the memory counter, so
     // LDS-direct loads of later tiles stay in flight across it.
     auto lds_barrier = [&]() { asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory"); };
@@ -333,6 +343,8 @@ __device__ __forceinline__ void mfma_item(const KParams& P, const ppd_work_item&
 #endif
 
     u32x4 pw[4];  // the tile's probabilities as bf16, B operand of the four 16-key steps of the PV product
+    TilePages tp_v = tile_pages(NS - 1 < ntiles ? NS - 1 : ntiles - 1);  // pages of the loads the first iteration issues
+    TilePages tp_k = tile_pages(NS < ntiles ? NS : ntiles - 1);
     PPD_TICK_DECL();
     for (int ti = 0; ti < ntiles; ++ti) {
         const int st_nxt = st_cur + 1 == NSK ? 0 : st_cur + 1;           // (ti + 1) % NSK
@@ -341,9 +353,14 @@ __device__ __forceinline__ void mfma_item(const KParams& P, const ppd_work_item&
         const int sv_far = (sv_cur + NS - 1) % NSV;                       // (ti + NS - 1) % NSV
         const bool full_issue = ti + NS < ntiles;
 #ifndef PPD_DIAG_NO_LOOP_LOADS  // timing diagnostics only: the tiles after the first NS read stale LDS
-        if (ti + NS - 1 < ntiles) load_block(tile_pages(ti + NS - 1), VRING + sv_far * KBYTES, v_off);
-        if (full_issue) load_block(tile_pages(ti + NS), st_far * KBYTES, 0);
+        if (ti + NS - 1 < ntiles) load_block(tp_v, VRING + sv_far * KBYTES, v_off);
+        if (full_issue) load_block(tp_k, st_far * KBYTES, 0);
 #endif
+        // The V tile of the next iteration is this iteration's K tile; the ids of its K tile are read from LDS
+        // now and turned into scalars at the end of the iteration: under the other waves' operand reads that
+        // small LDS read takes hundreds of cycles, which nothing waits for this way.
+        tp_v = tp_k;
+        const RawPages tp_raw = tile_pages_raw(ti + 1 + NS < ntiles ? ti + 1 + NS : ntiles - 1);
         PPD_TICK(0);
         // K(ti+2) and V(ti+1) must have landed before the barrier; with NS = 3 the loads issued in this iteration
         // may stay in flight
@@ -407,6 +424,7 @@ __device__ __forceinline__ void mfma_item(const KParams& P, const ppd_work_item&
         }
         __builtin_amdgcn_sched_barrier(0);
         if (late) close_iteration();
+        PPD_TICK(4);
         if (wave_active) {
             // Matrix phase: O^T += V^T P^T of this tile, then S^T of the next one into the registers the
             // probabilities have left.
@@ -425,6 +443,7 @@ __device__ __forceinline__ void mfma_item(const KParams& P, const ppd_work_item&
         __builtin_amdgcn_sched_barrier(0);
         PPD_TICK(3);
         if (!late) close_iteration();
+        tp_k = to_scalar(tp_raw);
         st_cur = st_nxt;
         sv_cur = sv_nxt;
         PPD_TICK(5);
