@@ -27,7 +27,10 @@ def build_lib(force=True, verbose=False):
     if not force and not is_stale():
         return LIB
     hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
-    cmd = [hipcc] + FLAGS + [os.path.join(CSRC, f) for f in SOURCES] + ["-o", LIB]
+    # PPD_EXTRA_HIPCC_FLAGS: e.g. "-DPPD_PHASE_TIMING" or the timing-diagnostic switches (-DPPD_DIAG_...) of
+    # ppd_kernels.hip; a library built with a PPD_DIAG_ switch computes wrong results on purpose
+    extra = os.environ.get("PPD_EXTRA_HIPCC_FLAGS", "").split()
+    cmd = [hipcc] + FLAGS + extra + [os.path.join(CSRC, f) for f in SOURCES] + ["-o", LIB]
     if verbose:
         print(" ".join(cmd), flush=True)
     res = subprocess.run(cmd, stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True)

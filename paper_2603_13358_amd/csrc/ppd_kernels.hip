@@ -343,6 +343,10 @@ __device__ __forceinline__ void mfma_item(const KParams& P, const ppd_work_item&
 #endif
 
     u32x4 pw[4];  // the tile's probabilities as bf16, B operand of the four 16-key steps of the PV product
+#ifdef PPD_DIAG_NO_VECTOR_PHASE
+#pragma unroll
+    for (int s = 0; s < 4; ++s) pw[s] = __builtin_bit_cast(u32x4, qreg[s]);  // defined, so the PV MFMAs stay
+#endif
     TilePages tp_v = tile_pages(NS - 1 < ntiles ? NS - 1 : ntiles - 1);  // pages of the loads the first iteration issues
     TilePages tp_k = tile_pages(NS < ntiles ? NS : ntiles - 1);
     PPD_TICK_DECL();
@@ -365,17 +369,23 @@ __device__ __forceinline__ void mfma_item(const KParams& P, const ppd_work_item&
         // K(ti+2) and V(ti+1) must have landed before the barrier; with NS = 3 the loads issued in this iteration
         // may stay in flight
         auto close_iteration = [&]() {
+#ifndef PPD_DIAG_NO_LOAD_WAIT  // timing diagnostics only: tiles may be read before they have landed (values only)
             if (full_issue)  // then the last NS - 2 iterations all issued their full share
                 wait_older_loads();
             else
                 wait_all_loads();
+#endif
             if (ti + 1 < ntiles) fix_v_tail(ti + 1, VRING + sv_nxt * KBYTES);
 #ifndef PPD_DIAG_NO_LOOP_BARRIER  // timing diagnostics only: the waves then race on the K/V tiles' contents (values
             lds_barrier();        // only: every address comes from the page ids staged and checked before the loop)
 #endif
         };
         float mc = 0.f;
+#ifdef PPD_DIAG_NO_VECTOR_PHASE  // timing diagnostics only: no softmax at all, wrong results
+        if (false) {
+#else
         if (wave_active) {
+#endif
             const int tile_base = it.kv_begin + ti * kTileTokens;
             if (tile_base + kTileTokens - 1 > wmin_limit) {  // causal boundary crosses this tile
 #pragma unroll
@@ -414,8 +424,13 @@ __device__ __forceinline__ void mfma_item(const KParams& P, const ppd_work_item&
 #pragma unroll
                 for (int e = 0; e < 4; ++e) {
                     const int i0 = (s & 1) * 8 + 2 * e;
+#ifdef PPD_DIAG_NO_EXP  // timing diagnostics only: wrong results
+                    const float p0 = __builtin_fmaf(s_cur[s >> 1][i0], c, -mc);
+                    const float p1 = __builtin_fmaf(s_cur[s >> 1][i0 + 1], c, -mc);
+#else
                     const float p0 = fast_exp2(__builtin_fmaf(s_cur[s >> 1][i0], c, -mc));
                     const float p1 = fast_exp2(__builtin_fmaf(s_cur[s >> 1][i0 + 1], c, -mc));
+#endif
                     psum += p0 + p1;
                     pw[s][e] = pack_bf16(p0, p1);
                 }
@@ -439,6 +454,9 @@ __device__ __forceinline__ void mfma_item(const KParams& P, const ppd_work_item&
                 }
             }
             if (ti + 1 < ntiles) qk_tile(st_nxt, s_cur);
+#ifdef PPD_DIAG_NO_VECTOR_PHASE
+            asm volatile("" ::"v"(s_cur[0]), "v"(s_cur[1]));  // nobody reads S^T in this build: keep its MFMAs
+#endif
         }
         __builtin_amdgcn_sched_barrier(0);
         PPD_TICK(3);
