@@ -23,7 +23,8 @@ constexpr int kStages = PPD_STAGES;          // LDS ring depth of the K and of t
 constexpr int kWgPerCu = kWaves == 8 ? 1 : 2;  // resident workgroups per compute unit (256 VGPRs per wave)
 constexpr int kTileTokens = 64;      // key tile of the MFMA path; every split boundary is a multiple of it
 constexpr int kMaxMfmaChunk = 32768;  // keys per MFMA row-block tile at most (its 2048 page ids are staged in LDS)
-constexpr int kSmallThreads = 256;   // block size of the append and merge kernels
+constexpr int kSmallThreads = 256;
+constexpr int kMergeCols = 16;    // columns of a merge group one block of the merge kernel takes   // block size of the append and merge kernels
 
 // One merge group: a row block whose key range was split over `nsplit` tiles with consecutive partials.
 struct MergeGroup {

@@ -786,81 +786,89 @@ __global__ __launch_bounds__(kThreads, 2) void ppd_mixed_kernel(const KParams P)
 
 // ---------------------------------------------------------------------------------------------------
 // Log-sum-exp merge of split partials: out = sum_j o_j 2^{(m_j - m*) c} / sum_j l_j 2^{(m_j - m*) c},
-// splits taken in index order (deterministic).  One wave per (merge group, column): block b takes the 4
-// columns starting at units[b].col0 of group units[b].group.
+// splits taken in index order (deterministic).  Block b takes the kMergeCols columns starting at units[b].col0 of
+// group units[b].group, each wave kMergeCols / 4 of them.  A wave moves little data, so its time is its chain of
+// dependent loads: the loads of all its columns (four splits at a time) are issued before the first use.
 // ---------------------------------------------------------------------------------------------------
 __global__ __launch_bounds__(kSmallThreads) void ppd_merge_kernel(const MergeParams M) {
+    constexpr int CPW = kMergeCols / (kSmallThreads / 64);  // columns per wave
     const MergeUnit u = M.units[blockIdx.x];
     const MergeGroup g = M.groups[u.group];
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int ncols = g.nrows * M.G;
     const int D = M.D;
-    const int col = u.col0 + wave;
-    if (col >= ncols) return;
-    const float* base = M.partials + g.part_off;
-    const int64_t ml_off = (int64_t)ncols * D + col * 2;
     const int d = lane * 2;
     const bool live = d < D;
-    const int64_t v_off = (int64_t)col * D + (live ? d : 0);
-    // The wave moves little data, so its time is the chain of dependent loads: four splits are loaded at a
-    // time, all loads of a batch issued before the first use.
-    float mm = NEG_INF;
-    float o0 = 0.f, o1 = 0.f, l = 0.f;
-    if (g.nsplit <= 4) {
-        float m4[4], l4[4];
-        f32x2 v4[4];
+    const float* base = M.partials + g.part_off;
+    float o0[CPW], o1[CPW], l[CPW];
 #pragma unroll
-        for (int t = 0; t < 4; ++t) {
-            const float* pp = base + g.part_stride * (t < g.nsplit ? t : 0);
-            m4[t] = pp[ml_off];
-            l4[t] = pp[ml_off + 1];
-            v4[t] = *reinterpret_cast<const f32x2*>(pp + v_off);
-        }
-#pragma unroll
-        for (int t = 0; t < 4; ++t)
-            if (t < g.nsplit) mm = fmaxf(mm, m4[t]);
-#pragma unroll
-        for (int t = 0; t < 4; ++t) {
-            if (t < g.nsplit) {
-                const float f = m4[t] == NEG_INF ? 0.f : fast_exp2((m4[t] - mm) * M.scale_log2e);
-                l += f * l4[t];
-                o0 += f * v4[t][0];
-                o1 += f * v4[t][1];
-            }
-        }
-    } else {
-        for (int j0 = 0; j0 < g.nsplit; j0 += 4) {
-            float m4[4];
-#pragma unroll
-            for (int t = 0; t < 4; ++t) m4[t] = base[g.part_stride * (j0 + t < g.nsplit ? j0 + t : j0) + ml_off];
-#pragma unroll
-            for (int t = 0; t < 4; ++t) mm = fmaxf(mm, m4[t]);
-        }
-        for (int j0 = 0; j0 < g.nsplit; j0 += 4) {
+    for (int c = 0; c < CPW; ++c) {
+        const int colr = u.col0 + wave * CPW + c;
+        const int col = colr < ncols ? colr : ncols - 1;  // columns past the end redo the last one and store nothing
+        const int64_t ml_off = (int64_t)ncols * D + col * 2;
+        const int64_t v_off = (int64_t)col * D + (live ? d : 0);
+        float mm = NEG_INF;
+        o0[c] = o1[c] = l[c] = 0.f;
+        if (g.nsplit <= 4) {
             float m4[4], l4[4];
             f32x2 v4[4];
 #pragma unroll
             for (int t = 0; t < 4; ++t) {
-                const float* pp = base + g.part_stride * (j0 + t < g.nsplit ? j0 + t : j0);
+                const float* pp = base + g.part_stride * (t < g.nsplit ? t : 0);
                 m4[t] = pp[ml_off];
                 l4[t] = pp[ml_off + 1];
                 v4[t] = *reinterpret_cast<const f32x2*>(pp + v_off);
             }
 #pragma unroll
+            for (int t = 0; t < 4; ++t)
+                if (t < g.nsplit) mm = fmaxf(mm, m4[t]);
+#pragma unroll
             for (int t = 0; t < 4; ++t) {
-                if (j0 + t < g.nsplit) {
+                if (t < g.nsplit) {
                     const float f = m4[t] == NEG_INF ? 0.f : fast_exp2((m4[t] - mm) * M.scale_log2e);
-                    l += f * l4[t];
-                    o0 += f * v4[t][0];
-                    o1 += f * v4[t][1];
+                    l[c] += f * l4[t];
+                    o0[c] += f * v4[t][0];
+                    o1[c] += f * v4[t][1];
+                }
+            }
+        } else {
+            for (int j0 = 0; j0 < g.nsplit; j0 += 4) {
+                float m4[4];
+#pragma unroll
+                for (int t = 0; t < 4; ++t) m4[t] = base[g.part_stride * (j0 + t < g.nsplit ? j0 + t : j0) + ml_off];
+#pragma unroll
+                for (int t = 0; t < 4; ++t) mm = fmaxf(mm, m4[t]);
+            }
+            for (int j0 = 0; j0 < g.nsplit; j0 += 4) {
+                float m4[4], l4[4];
+                f32x2 v4[4];
+#pragma unroll
+                for (int t = 0; t < 4; ++t) {
+                    const float* pp = base + g.part_stride * (j0 + t < g.nsplit ? j0 + t : j0);
+                    m4[t] = pp[ml_off];
+                    l4[t] = pp[ml_off + 1];
+                    v4[t] = *reinterpret_cast<const f32x2*>(pp + v_off);
+                }
+#pragma unroll
+                for (int t = 0; t < 4; ++t) {
+                    if (j0 + t < g.nsplit) {
+                        const float f = m4[t] == NEG_INF ? 0.f : fast_exp2((m4[t] - mm) * M.scale_log2e);
+                        l[c] += f * l4[t];
+                        o0[c] += f * v4[t][0];
+                        o1[c] += f * v4[t][1];
+                    }
                 }
             }
         }
     }
-    if (live) {
-        const int crow = col_row(col, M.invG);
-        const int64_t orow = (int64_t)(g.grow0 + crow) * M.Hq + g.kvh * M.G + (col - crow * M.G);
-        *reinterpret_cast<uint32_t*>(M.out + orow * D + d) = pack_bf16(o0 / l, o1 / l);
+#pragma unroll
+    for (int c = 0; c < CPW; ++c) {
+        const int col = u.col0 + wave * CPW + c;
+        if (live && col < ncols) {
+            const int crow = col_row(col, M.invG);
+            const int64_t orow = (int64_t)(g.grow0 + crow) * M.Hq + g.kvh * M.G + (col - crow * M.G);
+            *reinterpret_cast<uint32_t*>(M.out + orow * D + d) = pack_bf16(o0[c] / l[c], o1[c] / l[c]);
+        }
     }
 }
 

@@ -101,7 +101,7 @@ ppd_status build_plan(const ppd_shape& s, const int32_t* L, const int32_t* n, in
         }
     }
     const int slots = o.grid > 0 ? o.grid : kWgPerCu * o.num_cus;  // resident workgroups
-    const double per_item = cost_total / (4.0 * slots);     // aim for ~4 tiles per resident workgroup
+    const double per_item = cost_total / (3.0 * slots);     // aim for ~3 tiles per resident workgroup
     // Narrow tiles: every split costs a partial and, above all, a gap in the workgroup's stream of loads (claim,
     // page ids, first loads: ~8 us), so key ranges stay whole unless the batch is too small to occupy the chip:
     // measured over batch sizes 1..512 and contexts 4K..32K, ~100 tiles or more per launch and no tile shorter
@@ -140,7 +140,7 @@ ppd_status build_plan(const ppd_shape& s, const int32_t* L, const int32_t* n, in
                     group = (int)plan->groups.size();
                     base = part_floats;
                     plan->groups.push_back(MergeGroup{(int32_t)(grow + r0), nrows, h, nsplit, base, stride});
-                    for (int c0 = 0; c0 < nrows * G; c0 += kSmallThreads / 64) plan->units.push_back(MergeUnit{group, c0});
+                    for (int c0 = 0; c0 < nrows * G; c0 += kMergeCols) plan->units.push_back(MergeUnit{group, c0});
                     part_floats += stride * nsplit;
                 }
                 for (int sp = 0; sp < nsplit; ++sp) {
