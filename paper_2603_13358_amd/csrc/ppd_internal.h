@@ -19,7 +19,7 @@ constexpr int kNarrowCols = 16;      // a narrow tile holds rows*G <= 16 query c
 constexpr int kWaves = PPD_WAVES;            // waves per workgroup of the mixed kernel
 constexpr int kThreads = 64 * kWaves;
 constexpr int kMfmaCols = 32 * kWaves;       // an MFMA row-block tile holds up to 32 query columns per wave
-constexpr int kStages = PPD_STAGES;          // LDS ring depth of the K and of the V tiles
+constexpr int kStages = PPD_STAGES;          // prefetch distance of the K tiles (V: one less); the LDS rings have one stage more
 constexpr int kWgPerCu = kWaves == 8 ? 1 : 2;  // resident workgroups per compute unit (256 VGPRs per wave)
 constexpr int kTileTokens = 64;      // key tile of the MFMA path; every split boundary is a multiple of it
 constexpr int kMaxMfmaChunk = 32768;  // keys per MFMA row-block tile at most (its 2048 page ids are staged in LDS)

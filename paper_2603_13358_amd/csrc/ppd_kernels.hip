@@ -654,7 +654,7 @@ __device__ __forceinline__ void narrow_item(const KParams& P, const ppd_work_ite
     l_run += xor_shuffle(l_run, 16);
     l_run = sum_halves(l_run);
 
-    // combine the four waves: O^T register i of block db is d = db*16 + 4*g4 + i of column c16
+    // combine the waves: O^T register i of block db is d = db*16 + 4*g4 + i of column c16
     float* wbuf = reinterpret_cast<float*>(smem) + wave * WSTRIDE;
 #pragma unroll
     for (int db = 0; db < DBN; ++db)
@@ -699,8 +699,9 @@ __device__ __forceinline__ void narrow_item(const KParams& P, const ppd_work_ite
 
 template <int HD>
 __global__ __launch_bounds__(kThreads, 2) void ppd_mixed_kernel(const KParams P) {
-    // Dynamic LDS: kStages stages of 4 pages of K and as many of V for the MFMA path (96 KiB at HD = 128 with
-    // three stages); the narrow path's combine buffer (kWaves * 16 * (HD+2) floats) uses the front of it.
+    // Dynamic LDS: rings of kStages + 1 stages of 4 pages of K and as many of V, then the page ids of a tile's key
+    // range, for the MFMA path (136 KiB at HD = 128); the narrow path's combine buffer (kWaves * 16 * (HD+2)
+    // floats) uses the front of it.
     extern __shared__ __attribute__((aligned(16))) char smem[];
     PPD_WG_SPAN_BEGIN();
     __shared__ int s_next_slot;
