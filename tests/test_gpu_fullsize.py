@@ -14,8 +14,8 @@ pytestmark = pytest.mark.gpu
 def _run_and_check(name, seq_ids_fn, rows_per_seq=4):
     import torch
     import bench
-    b = bench.make_shapes(name, 0)
-    print("workload", name, "B", b.B, "T", b.T, flush=True)
+    b = bench.make_shapes(name, 0) if isinstance(name, str) else name
+    print("workload", b.name, "B", b.B, "T", b.T, flush=True)
     r = bench.Runner(b, torch, 0)
     w = r.w
     seqs = seq_ids_fn(b)
@@ -86,6 +86,16 @@ def test_cfg4_full_prefill_variant_full_size():
         dec = sorted([i for i in range(b.B) if b.n[i] == 1], key=lambda i: int(b.L[i]))
         return [dec[len(dec) // 2], full[0]]
     _run_and_check("cfg4_mixed_full", pick, rows_per_seq=5)
+
+
+def test_mixed_batch_with_group_of_five_heads():
+    """40 query heads over 8 KV heads (G = 5, the head shape of the second model the paper serves, section 5.1):
+    64 decodes at 1K-8K context and 3 append-prefills in one step."""
+    rng = np.random.default_rng(77)
+    L = np.concatenate([rng.integers(1024, 8193, size=64), rng.integers(4096, 16385, size=3)])
+    n = np.concatenate([np.ones(64, np.int64), rng.integers(200, 700, size=3)])
+    b = si.make_batch("mixed_g5", L=L, n=n, Hq=40, Hkv=8, D=128, seed=7, slack_pages=64, with_data=False)
+    _run_and_check(b, lambda b: [0, 63, 64, 66], rows_per_seq=4)
 
 
 def test_long_context_single_sequences():
