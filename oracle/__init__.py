@@ -24,22 +24,27 @@ def build(force=False):
     return _LIB
 
 
+def _bind(path):
+    """ctypes handle of an oracle build with the argument types set."""
+    lib = ctypes.CDLL(path)
+    vp, i32, i64 = ctypes.c_void_p, ctypes.c_int32, ctypes.c_int64
+    lib.ppd_oracle_kv_append.argtypes = [vp, vp, vp, vp, i64, i32, i32, i32, i64]
+    lib.ppd_oracle_kv_append.restype = i32
+    lib.ppd_oracle_mixed_attention.argtypes = [vp, vp, vp, i32, vp, vp, i32, i32, i32, i32, i32, i64,
+                                               ctypes.c_float, vp, vp]
+    lib.ppd_oracle_mixed_attention.restype = i32
+    lib.ppd_oracle_kv_land.argtypes = [vp, vp, vp, i64, i32, vp, i64, i32, i32, i32, i64]
+    lib.ppd_oracle_kv_land.restype = i32
+    lib.ppd_oracle_transfer_delay.argtypes = [ctypes.c_double] * 4
+    lib.ppd_oracle_transfer_delay.restype = ctypes.c_double
+    return lib
+
+
 def _load():
     global _lib
     if _lib is None:
         build()
-        lib = ctypes.CDLL(_LIB)
-        vp, i32, i64 = ctypes.c_void_p, ctypes.c_int32, ctypes.c_int64
-        lib.ppd_oracle_kv_append.argtypes = [vp, vp, vp, vp, i64, i32, i32, i32, i64]
-        lib.ppd_oracle_kv_append.restype = i32
-        lib.ppd_oracle_mixed_attention.argtypes = [vp, vp, vp, i32, vp, vp, i32, i32, i32, i32, i32, i64,
-                                                   ctypes.c_float, vp, vp]
-        lib.ppd_oracle_mixed_attention.restype = i32
-        lib.ppd_oracle_kv_land.argtypes = [vp, vp, vp, i64, i32, vp, i64, i32, i32, i32, i64]
-        lib.ppd_oracle_kv_land.restype = i32
-        lib.ppd_oracle_transfer_delay.argtypes = [ctypes.c_double] * 4
-        lib.ppd_oracle_transfer_delay.restype = ctypes.c_double
-        _lib = lib
+        _lib = _bind(_LIB)
     return _lib
 
 
