@@ -877,8 +877,14 @@ __global__ __launch_bounds__(kSmallThreads) void ppd_merge_kernel(const MergePar
 // Paged KV append (and, with several layers in one launch, the landing of transferred KV).  One workgroup
 // moves 8 consecutive tokens of the batch for one KV head of one layer.
 // K: 16-byte granules (8 d of one token), lanes ordered token-minor so that tokens in consecutive slots
-//    write 128 contiguous bytes.  V: a granule is 8 tokens of one d; when the 8 tokens fill one aligned
-//    granule (the common case for prefill) each thread writes it whole, otherwise element by element.
+//    write 128 contiguous bytes.
+// V: a granule is 8 tokens of one d, i.e. 8 consecutive slots starting at a multiple of 8.  The new tokens of a
+//    sequence sit in consecutive slots but start anywhere (at its cached length), so the workgroup's own 8
+//    tokens rarely fill one granule; run of 8 batch tokens that do ("octets") are found in a window of slots
+//    around the workgroup's tokens instead: the workgroup writes, as whole 16-byte granules, the octet that
+//    STARTS at one of its tokens (there is at most one; its tokens may reach into the next workgroup's range,
+//    which only reads them), and element by element those of its tokens that belong to no octet (heads and tails
+//    of runs, skipped neighbours).  Every token is written exactly once.
 // ---------------------------------------------------------------------------------------------------
 // source and pool are each touched once: non-temporal loads and stores (the landing of a whole request runs 7 %
 // faster with them)
@@ -897,58 +903,70 @@ __global__ __launch_bounds__(kSmallThreads) void ppd_kv_append_kernel(const uint
     const int tid = threadIdx.x;
     const int hh = blockIdx.y;
     const int64_t t0 = (int64_t)blockIdx.x * 8;
-    const int nt = (int)((T - t0) < 8 ? (T - t0) : 8);
-    // every thread reads the (at most) 8 slots itself: no LDS round trip, the loads are broadcast
-    int64_t sl[8];
-    bool aligned = nt == 8;
-#pragma unroll
-    for (int i = 0; i < 8; ++i) {
-        int64_t s = i < nt ? slots[t0 + i] : -1;
-        if (s >= num_pages * kPage) {
-            if (tid == 0 && hh == 0 && blockIdx.z == 0) atomicOr(err_flags, 1u);
-            s = -1;
-        }
-        sl[i] = s;
-    }
-    aligned = aligned && sl[0] >= 0 && (sl[0] & 7) == 0;
-#pragma unroll
-    for (int i = 1; i < 8; ++i) aligned = aligned && sl[i] == sl[0] + i;
+    // Window of slots: batch tokens t0-7 .. t0+14, one per lane (lane 7 holds token t0), in every wave; tokens
+    // outside the batch and slots outside the pool count as skipped.  What follows is a handful of wave-wide
+    // votes: the per-workgroup bookkeeping has to stay far below the cost of moving 8 tokens.
+    constexpr int kWin = 22;
+    const int lane = tid & 63;
+    const int64_t tw = t0 - 7 + lane;
+    int64_t ws = -1;
+    if (lane < kWin && tw >= 0 && tw < T) ws = slots[tw];
+    const bool outside = ws >= num_pages * kPage;
+    if (__ballot(outside && lane >= 7 && lane < 15) != 0 && tid == 0 && hh == 0 && blockIdx.z == 0)
+        atomicOr(err_flags, 1u);
+    if (outside) ws = -1;
+    // bit i of `runs`: entry i+1 holds the slot after entry i's; bit c of `octets`: the 8 tokens from entry c on
+    // sit in the 8 slots of one V granule, in order
+    const int64_t ws_next = __shfl_down(ws, 1);
+    const uint64_t runs = __ballot(lane < kWin - 1 && ws_next == ws + 1);
+    const uint64_t starts = __ballot(ws >= 0 && (ws & 7) == 0);
+    const uint32_t octets = (uint32_t)(starts & runs & (runs >> 1) & (runs >> 2) & (runs >> 3) & (runs >> 4) &
+                                       (runs >> 5) & (runs >> 6)) & 0x7FFFu;
+    // own tokens: which of them no octet covers (a token with slot s would be entry s % 8 of one), and the
+    // octet that starts at one of them
+    const int my_start = (ws >= 0 && lane >= 7) ? lane - (int)(ws & 7) : 0;
+    const uint32_t single =
+        (uint32_t)(__ballot(lane >= 7 && lane < 15 && ws >= 0 && !((octets >> my_start) & 1u)) >> 7) & 0xFFu;
+    const uint32_t own_octets = (octets >> 7) & 0xFFu;
+    const int oct_tok = own_octets ? __builtin_ctz(own_octets) : 0;
+    const int64_t oct_first = __shfl(ws, 7 + oct_tok);
+    const int64_t oct_slot = own_octets ? oct_first : -1;
     const int64_t S = 2LL * Hkv * kPage * D;
     const int HD = Hkv * D;
     const int64_t koff = (int64_t)hh * kPage * D;
     const int64_t voff = (int64_t)Hkv * kPage * D + koff;
-    // K: work unit = (granule c, token), token fastest
+    // K (lower half of the threads): work unit = (granule c, token), token fastest
+    constexpr int kHalf = kSmallThreads / 2;
     const int kunits = (D / 8) * 8;
-    for (int u = tid; u < kunits; u += kSmallThreads) {
+    for (int u = tid; u < kunits && tid < kHalf; u += kHalf) {
         const int tok = u & 7, c = u >> 3;
-        int64_t s = sl[0];
-#pragma unroll
-        for (int i = 1; i < 8; ++i) s = tok == i ? sl[i] : s;
+        const int64_t s = __shfl(ws, 7 + tok);  // every lane of the wave is here: D is a multiple of 64
         if (s < 0) continue;
         const u32x4 val = APPEND_LOAD(reinterpret_cast<const u32x4*>(k + (t0 + tok) * HD + hh * D + c * 8));
         APPEND_STORE(val, reinterpret_cast<u32x4*>(pool + (s >> 4) * S + koff + c * (kPage * 8) + (int)(s & 15) * 8));
     }
-    // V: work unit = d
-    if (aligned) {
-        const int64_t page = sl[0] >> 4;
-        const int half = (int)((sl[0] & 15) >> 3);
-        for (int d = tid; d < D; d += kSmallThreads) {
-            uint32_t w[4];
+    // V, whole granules (upper half of the threads, at the same time as K): work unit = d
+    if (oct_slot >= 0 && tid >= kHalf) {
+        const int64_t page = oct_slot >> 4;
+        const int half = (int)((oct_slot & 15) >> 3);
+        const uint16_t* src = v + (t0 + oct_tok) * HD + hh * D;
+        for (int d = tid - kHalf; d < D; d += kHalf) {
+            uint32_t g[4];
 #pragma unroll
             for (int e = 0; e < 4; ++e) {
-                const uint32_t lo = APPEND_LOAD(v + (t0 + 2 * e) * HD + hh * D + d);
-                const uint32_t hi = APPEND_LOAD(v + (t0 + 2 * e + 1) * HD + hh * D + d);
-                w[e] = lo | (hi << 16);
+                const uint32_t lo = APPEND_LOAD(src + (2 * e) * HD + d);
+                const uint32_t hi = APPEND_LOAD(src + (2 * e + 1) * HD + d);
+                g[e] = lo | (hi << 16);
             }
-            APPEND_STORE((u32x4{w[0], w[1], w[2], w[3]}), reinterpret_cast<u32x4*>(pool + page * S + voff + half * (D * 8) + d * 8));
+            APPEND_STORE((u32x4{g[0], g[1], g[2], g[3]}), reinterpret_cast<u32x4*>(pool + page * S + voff + half * (D * 8) + d * 8));
         }
-    } else {
+    }
+    // V, element by element: work unit = (token, d)
+    if (single) {
         for (int u = tid; u < D * 8; u += kSmallThreads) {
             const int tok = u / D, d = u % D;
-            int64_t s = sl[0];
-#pragma unroll
-            for (int i = 1; i < 8; ++i) s = tok == i ? sl[i] : s;
-            if (s < 0) continue;
+            const int64_t s = __shfl(ws, 7 + tok);  // before any lane drops out
+            if (!((single >> tok) & 1u)) continue;
             const int off = (int)(s & 15);
             pool[(s >> 4) * S + voff + (off >> 3) * (D * 8) + d * 8 + (off & 7)] = v[(t0 + tok) * HD + hh * D + d];
         }

@@ -172,6 +172,51 @@ def test_append_in_one_call_and_skipped_slots():
     ctx.close()
 
 
+@pytest.mark.parametrize("seed", [0, 1, 2, 3])
+def test_append_slot_patterns_bit_exact(seed):
+    """Runs of consecutive slots that start anywhere, whole aligned groups of 8, skipped tokens inside a run,
+    groups written back to front, isolated tokens, a batch that is not a multiple of 8 tokens long."""
+    import torch
+    import oracle
+    import paper_2603_13358_amd as ppd
+    from gpu_helpers import from_dev_u16, to_dev_u16
+    rng = np.random.default_rng(100 + seed)
+    Hkv, D, P, num_pages = (2, 64, 16, 96) if seed % 2 else (8, 128, 16, 96)
+    free = list(rng.permutation(num_pages * P // 8))           # aligned groups of 8 slots, each used at most once
+    slots = []
+    while len(slots) < 300 + 3 * seed:
+        kind = rng.integers(0, 5)
+        g = int(free.pop()) * 8
+        if kind == 0:                                          # a whole aligned group
+            slots += list(range(g, g + 8))
+        elif kind == 1:                                        # a run that starts inside a group and goes on in another
+            g2 = int(free.pop()) * 8
+            a = int(rng.integers(1, 8))
+            slots += list(range(g + a, g + 8)) + list(range(g2, g2 + int(rng.integers(1, 9))))
+        elif kind == 2:                                        # a group with one token skipped
+            run = list(range(g, g + 8))
+            run[int(rng.integers(0, 8))] = -1
+            slots += run
+        elif kind == 3:                                        # an isolated token
+            slots += [g + int(rng.integers(0, 8))]
+        else:                                                  # a group written back to front
+            slots += list(range(g + 7, g - 1, -1))
+    slots = np.asarray(slots, np.int64)
+    T = len(slots)
+    print("case append patterns seed", seed, "T", T, "Hkv", Hkv, "D", D, flush=True)
+    k = si.normal_bf16(rng, (T, Hkv, D))
+    v = si.normal_bf16(rng, (T, Hkv, D))
+    dev = torch.device("cuda:0")
+    ctx = ppd.Context(Hkv, Hkv, D, num_pages)
+    pool = torch.full((ctx.pool_elems(),), 0x1234, dtype=torch.int16, device=dev)
+    ctx.kv_append(to_dev_u16(k, torch, dev), to_dev_u16(v, torch, dev), pool, torch.from_numpy(slots).to(dev))
+    assert ctx.device_error_flags() == 0
+    ref = np.full(ctx.pool_elems(), 0x1234, np.uint16)
+    oracle.kv_append(k, v, ref, slots, Hkv, D, P, num_pages)
+    assert np.array_equal(from_dev_u16(pool), ref)
+    ctx.close()
+
+
 def test_bad_page_id_is_flagged_not_dereferenced():
     import torch
     import paper_2603_13358_amd as ppd
