@@ -429,6 +429,11 @@ def main():
         roofline = {"bound": "mfma", "achieved": b_flops / kernel_s / 1e12, "peak": MFMA_BF16_PEAK_TFLOPS,
                     "unit": "TFLOP/s"}
     roofline["frac"] = roofline["achieved"] / roofline["peak"]
+    # A mixed step has a memory-bound and a matrix-bound part that run on different compute units of the same
+    # launch: time at peak of each, and the kernel against the two in series (1.0 = each part at its own peak,
+    # no overlap between them; `frac` above is against the larger one alone, i.e. perfect overlap).
+    roofline["time_at_peak_us"] = {"hbm": t_hbm * 1e6, "mfma": t_mfma * 1e6}
+    roofline["frac_of_both_in_series"] = (t_hbm + t_mfma) / kernel_s
     roofline["traffic"] = measured_traffic(args.workload)
     roofline["kernel"] = "ppd_mixed_kernel<128>"
     roofline["kernel_ms"] = main_res["mixed_kernel_ms"]

@@ -15,6 +15,8 @@
  * Conventions
  *  - All tensor pointers are DEVICE pointers unless a parameter says HOST.  They are borrowed: the
  *    library neither frees them nor keeps them after the enqueued work has run.
+ *  - q, out, k, v and every page pool must start on a 16-byte boundary (the kernels move 16 bytes per lane);
+ *    slot_mapping on an 8-byte, page_tables on a 4-byte boundary.  Anything else is PPD_ERR_RANGE.
  *  - bf16 = the upper 16 bits of an IEEE binary32.  Arithmetic: bf16 inputs, fp32 accumulation and
  *    softmax, probabilities rounded to bf16 before the PV product, bf16 output (round to nearest even).
  *  - Both calls are asynchronous on `stream` (a hipStream_t passed as void*; NULL = the default stream);
@@ -48,7 +50,7 @@ typedef enum {
     PPD_OK = 0,
     PPD_ERR_NULL = -1,      /* a required pointer is NULL */
     PPD_ERR_SHAPE = -2,     /* unsupported head_dim / page_size / head counts */
-    PPD_ERR_RANGE = -3,     /* n_i < 1, L_i < 0, negative or non-finite scale, sizes out of range */
+    PPD_ERR_RANGE = -3,     /* n_i < 1, L_i < 0, negative or non-finite scale, sizes out of range, misaligned pointer */
     PPD_ERR_PAGETABLE = -4, /* max_pages < ceil((L_i + n_i) / P) for some sequence */
     PPD_ERR_WORKSPACE = -5, /* workspace allocation failed */
     PPD_ERR_HIP = -6        /* a HIP runtime call failed (see ppd_last_error) */

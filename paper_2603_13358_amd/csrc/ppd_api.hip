@@ -3,6 +3,7 @@
 
 #include <chrono>
 #include <cmath>
+#include <cstdint>
 #include <cstdio>
 #include <cstring>
 #include <string>
@@ -84,6 +85,9 @@ ppd_status grow_device(ppd_ctx* ctx, void** ptr, size_t* have, size_t need, hipS
     *have = want;
     return PPD_OK;
 }
+
+// The kernels move 16 bytes per lane: tensors and pools must start on a 16-byte boundary.
+bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
 
 }  // namespace
 
@@ -187,6 +191,8 @@ ppd_status ppd_kv_append(ppd_ctx* ctx, const void* k, const void* v, void* kv_pa
     if (T < 0 || T >= (int64_t(1) << 31)) return fail(ctx, PPD_ERR_RANGE, "T out of range");
     if (T == 0) return PPD_OK;
     if (!k || !v || !kv_pages || !slot_mapping) return fail(ctx, PPD_ERR_NULL, "k / v / kv_pages / slot_mapping is NULL");
+    if (!aligned16(k) || !aligned16(v) || !aligned16(kv_pages) || (reinterpret_cast<uintptr_t>(slot_mapping) & 7u))
+        return fail(ctx, PPD_ERR_RANGE, "k / v / kv_pages must be 16-byte aligned, slot_mapping 8-byte aligned");
     PPD_HIP(ctx, hipSetDevice(ctx->device));
     int rc = ppd::launch_kv_append(static_cast<const uint16_t*>(k), static_cast<const uint16_t*>(v),
                                    static_cast<uint16_t*>(kv_pages), slot_mapping, T, ctx->shape.num_kv_heads,
@@ -205,6 +211,10 @@ ppd_status ppd_kv_land(ppd_ctx* ctx, const void* k, const void* v, void* kv_page
     const int64_t pool_elems = 2LL * ctx->shape.num_kv_heads * ppd::kPage * ctx->shape.head_dim * ctx->shape.num_pages;
     if (num_layers > 1 && layer_stride_elems < pool_elems)
         return fail(ctx, PPD_ERR_RANGE, "layer_stride_elems is smaller than one pool: layers would overlap");
+    if (!aligned16(k) || !aligned16(v) || !aligned16(kv_pages) || (reinterpret_cast<uintptr_t>(slot_mapping) & 7u) ||
+        (num_layers > 1 && layer_stride_elems % 8 != 0))
+        return fail(ctx, PPD_ERR_RANGE,
+                    "k / v / kv_pages must be 16-byte aligned (layer_stride_elems a multiple of 8), slot_mapping 8-byte aligned");
     PPD_HIP(ctx, hipSetDevice(ctx->device));
     int rc = ppd::launch_kv_append(static_cast<const uint16_t*>(k), static_cast<const uint16_t*>(v),
                                    static_cast<uint16_t*>(kv_pages), slot_mapping, T, ctx->shape.num_kv_heads,
@@ -237,6 +247,8 @@ ppd_status ppd_mixed_attention(ppd_ctx* ctx, const void* q, const void* kv_pages
     if (!q || !kv_pages || !page_tables || !L || !n || !out)
         return fail(ctx, PPD_ERR_NULL, "q / kv_pages / page_tables / L / n / out is NULL");
     if (!(scale >= 0.f) || !std::isfinite(scale)) return fail(ctx, PPD_ERR_RANGE, "scale must be finite and >= 0");
+    if (!aligned16(q) || !aligned16(out) || !aligned16(kv_pages) || (reinterpret_cast<uintptr_t>(page_tables) & 3u))
+        return fail(ctx, PPD_ERR_RANGE, "q / out / kv_pages must be 16-byte aligned, page_tables 4-byte aligned");
     const char* msg = "";
     ppd_status st = PPD_OK;
     const bool same_opts = std::memcmp(&ctx->plan_opts, &ctx->opts, sizeof(ppd::PlanOptions)) == 0;

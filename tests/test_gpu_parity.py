@@ -75,6 +75,44 @@ def test_scheduling_options_do_not_change_the_result(options):
     assert np.array_equal(out, base)
 
 
+@pytest.mark.parametrize("seed", range(8))
+def test_random_mixed_batches(seed):
+    """Random batches: sequence count, head shape, the mix of decode / append-prefill / full-prefill rows, lengths
+    around page, tile and row-block boundaries, and split sizes all drawn from the seed."""
+    rng = np.random.default_rng(7000 + seed)
+    Hkv = int(rng.choice([1, 2, 4, 8]))
+    G = int(rng.integers(1, 9))
+    D = int(rng.choice([64, 128]))
+    B = int(rng.integers(1, 25))
+    L, n = [], []
+    budget = 4e6 / (G * Hkv / 8.0)                 # visible (row, key) pairs: keeps the oracle to a few seconds
+    for _ in range(B):
+        kind = rng.integers(0, 4)
+        if kind == 0:                              # decode
+            Li, ni = int(rng.integers(0, 5000)), 1
+        elif kind == 1:                            # a few new tokens (still a narrow tile for small G)
+            Li, ni = int(rng.integers(0, 3000)), int(rng.integers(2, 8))
+        elif kind == 2:                            # append-prefill, lengths near multiples of 64
+            Li = int(rng.integers(1, 40)) * 64 + int(rng.integers(-2, 3))
+            ni = int(rng.integers(1, 6)) * 64 // max(1, G // 2) + int(rng.integers(-2, 3))
+        else:                                      # full prefill
+            Li, ni = 0, int(rng.integers(1, 400))
+        ni = max(1, ni)
+        cost = ni * (Li + (ni + 1) / 2)
+        if cost > budget:
+            continue
+        budget -= cost
+        L.append(max(0, Li))
+        n.append(ni)
+    if not L:
+        L, n = [5], [1]
+    opts = {}
+    if rng.integers(0, 2):
+        opts = {"narrow_chunk": int(rng.choice([64, 256, 1024])), "mfma_chunk": int(rng.choice([64, 192, 512, 2048]))}
+    _compare(si.make_batch("random%d" % seed, L=L, n=n, Hq=G * Hkv, Hkv=Hkv, D=D, seed=7100 + seed,
+                           slack_pages=int(rng.integers(0, 9))), options=opts)
+
+
 def test_decode_batch_scaled():
     _compare(si.cfg2_decode(0, B=12, Lmin=100, Lmax=3000))
 
@@ -258,8 +296,21 @@ def test_host_argument_errors_enqueue_nothing():
     with pytest.raises(ppd.PPDError) as e:
         ppd.ppd_mixed_attention(ctx.handle, None, pool, pt, b.L, b.n, b.scale, out)
     assert e.value.status == -1
+    # tensors that do not start on a 16-byte boundary are rejected (views shifted by one element)
+    q_odd = torch.empty(q.numel() + 1, dtype=torch.int16, device=dev)[1:]
+    pool_odd = torch.empty(pool.numel() + 1, dtype=torch.int16, device=dev)[1:]
+    for args in [(q_odd, pool, out), (q, pool_odd, out), (q, pool, q_odd)]:
+        with pytest.raises(ppd.PPDError) as e:
+            ppd.ppd_mixed_attention(ctx.handle, args[0], args[1], pt, b.L, b.n, b.scale, args[2])
+        assert e.value.status == -3
+    kk, vv, slots = b.new_part()
+    with pytest.raises(ppd.PPDError) as e:
+        ppd.ppd_kv_append(ctx.handle, to_dev_u16(kk, torch, dev), to_dev_u16(vv, torch, dev), pool_odd,
+                          torch.from_numpy(slots.astype(np.int64)).to(dev))
+    assert e.value.status == -3
     torch.cuda.synchronize()
     assert bool((out == 7).all()), "a rejected call touched the output"
+    assert bool((pool == 0).all()), "a rejected call touched the pool"
     # empty batch and empty append are no-ops
     ppd.ppd_mixed_attention(ctx.handle, q, pool, pt, np.zeros(0, np.int32), np.zeros(0, np.int32), b.scale, out)
     ppd.ppd_kv_append(ctx.handle, None, None, pool, None, T=0)
