@@ -48,6 +48,53 @@ static void split_range(int64_t len, int64_t chunk, std::vector<int32_t>* bounds
     bounds->push_back((int32_t)len);
 }
 
+// Split size of the MFMA row-block tiles.  Every split costs a partial (fp32 o, m, l per column) that the tile
+// writes and a separate merge launch reads back; not splitting leaves few, long tiles that may not fill or balance
+// the workgroups.  The choice is made by estimate: for each candidate size, the row blocks of ONE KV head are cut
+// (all heads are alike), their tiles list-scheduled longest-first onto slots / Hkv workgroups at
+// kTileStartUs + kTileIterUs per 64 keys, and the cost of the partials added; candidates run from whole key ranges
+// downwards and stop once there are far more tiles than workgroups.  Constants fitted to measured launches
+// (append-prefill batches of 2..16 sequences, 256 workgroups): the estimate is within ~8 % of the kernel time
+// and ranks the candidates of one batch correctly.
+struct RowBlock { int64_t vis_end; int32_t nrows; };
+static int64_t choose_mfma_chunk(const std::vector<RowBlock>& blocks, int G, int Hkv, int D, double slots_for_mfma) {
+    constexpr double kTileStartUs = 16.0, kTileIterUs = 1.7;
+    constexpr double kMergeLaunchUs = 12.0, kPartialBytesPerUs = 2.5e6;
+    static const int64_t kCandidates[] = {32768, 24576, 16384, 12288, 8192, 6144, 4096, 3072, 2048, 1024, 512};
+    const int S = (int)std::max(1.0, std::floor(slots_for_mfma / Hkv + 0.5));
+    int64_t best_chunk = kCandidates[0];
+    double best = -1.0;
+    std::vector<double> tiles, load;
+    std::vector<int32_t> bounds;
+    for (int64_t c : kCandidates) {
+        tiles.clear();
+        double partial_bytes = 0;
+        for (const RowBlock& rb : blocks) {
+            split_range(rb.vis_end, c, &bounds);
+            const int nsplit = (int)bounds.size() - 1;
+            for (int k = 0; k < nsplit; ++k)
+                tiles.push_back(kTileStartUs + kTileIterUs * (double)((bounds[k + 1] - bounds[k] + kTileTokens - 1) / kTileTokens));
+            if (nsplit > 1) partial_bytes += (double)rb.nrows * G * (D + 2) * 4.0 * nsplit * Hkv;
+        }
+        std::sort(tiles.begin(), tiles.end(), std::greater<double>());
+        load.assign((size_t)S, 0.0);  // min-heap of workgroup finish times
+        auto later = [](double a, double b) { return a > b; };
+        for (double t : tiles) {
+            std::pop_heap(load.begin(), load.end(), later);
+            load.back() += t;
+            std::push_heap(load.begin(), load.end(), later);
+        }
+        const double makespan = *std::max_element(load.begin(), load.end());
+        const double est = makespan + (partial_bytes > 0 ? kMergeLaunchUs + partial_bytes / kPartialBytesPerUs : 0.0);
+        if (best < 0 || est < 0.99 * best) {  // a smaller chunk has to win clearly
+            best = est;
+            best_chunk = c;
+        }
+        if ((int64_t)tiles.size() > 16LL * S) break;  // plenty of tiles already: smaller pieces only add partials
+    }
+    return best_chunk;
+}
+
 ppd_status build_plan(const ppd_shape& s, const int32_t* L, const int32_t* n, int32_t B, const PlanOptions& o,
                       Plan* plan, const char** err) {
     static const char* kNull = "L / n is NULL";
@@ -87,21 +134,24 @@ ppd_status build_plan(const ppd_shape& s, const int32_t* L, const int32_t* n, in
     // Total cost in "token units": a narrow tile costs its tokens, an MFMA tile twice its tokens (rough
     // ratio of time per key at the rates the two paths reach; only the order of tiles depends on it).
     double cost_total = 0;
-    int64_t mfma_units = 0;  // (row block, KV head) pairs
     double narrow_tokens = 0;  // keys of the narrow tiles, counted once per KV head
+    std::vector<RowBlock> row_blocks;  // of one KV head
+    double mfma_iters = 0;             // 64-key steps of all row blocks of one KV head
     for (int i = 0; i < B; ++i) {
         if (is_narrow(i)) {
             cost_total += (double)Hkv * (L[i] + n[i]);
             narrow_tokens += (double)Hkv * (L[i] + n[i]);
         } else {
             for (int r0 = 0; r0 < n[i]; r0 += rows_per_block) {
-                cost_total += 2.0 * Hkv * (L[i] + std::min<int64_t>(n[i], r0 + rows_per_block));
-                mfma_units += Hkv;
+                const int nrows = std::min(rows_per_block, n[i] - r0);
+                const int64_t vis_end = (int64_t)L[i] + r0 + nrows;
+                cost_total += 2.0 * Hkv * vis_end;
+                row_blocks.push_back(RowBlock{vis_end, nrows});
+                mfma_iters += std::ceil((double)vis_end / kTileTokens);
             }
         }
     }
     const int slots = o.grid > 0 ? o.grid : kWgPerCu * o.num_cus;  // resident workgroups
-    const double per_item = cost_total / (3.0 * slots);     // aim for ~3 tiles per resident workgroup
     // Narrow tiles: every split costs a partial and, above all, a gap in the workgroup's stream of loads (claim,
     // page ids, first loads: ~8 us), so key ranges stay whole unless the batch is too small to occupy the chip:
     // measured over batch sizes 1..512 and contexts 4K..32K, ~100 tiles or more per launch and no tile shorter
@@ -109,14 +159,16 @@ ppd_status build_plan(const ppd_shape& s, const int32_t* L, const int32_t* n, in
     int64_t narrow_chunk = o.narrow_chunk > 0
                                ? o.narrow_chunk
                                : std::min<int64_t>(8192, std::max<int64_t>(512, round_up((int64_t)(narrow_tokens / 96), kTileTokens)));
-    int64_t mfma_chunk = o.mfma_chunk > 0
-                             ? o.mfma_chunk
-                             : std::min<int64_t>(12288, std::max<int64_t>(512, round_up((int64_t)(per_item / 2), kTileTokens)));
-    // Every split costs a partial (fp32 o, m, l per column) written and read back by the merge, a separate launch:
-    // by step time, chunks of up to 12288 keys beat 8192 on the append-prefill workloads (3-5 %) although the
-    // kernel itself balances slightly better with the shorter ones.  With many row blocks per workgroup the queue
-    // balances without splitting: keep each row block's key range whole.
-    if (o.mfma_chunk == 0 && mfma_units >= 16LL * slots) mfma_chunk = kMaxMfmaChunk;
+    int64_t mfma_chunk = o.mfma_chunk;
+    if (mfma_chunk == 0 && !row_blocks.empty()) {
+        // workgroups left to the MFMA tiles when narrow tiles run beside them (same two constants as the split
+        // of the compute units below: 45 GB/s per unit streaming, 2.3 us per 64 keys of a row block)
+        const double narrow_cu_us = narrow_tokens * kv_tok_bytes_head / 45e3;
+        const double mfma_cu_us = mfma_iters * Hkv * 2.3;
+        const double share = std::max(12.0 / 32.0, mfma_cu_us / (mfma_cu_us + narrow_cu_us));
+        mfma_chunk = choose_mfma_chunk(row_blocks, G, Hkv, D, slots * share);
+    }
+    if (mfma_chunk == 0) mfma_chunk = kMaxMfmaChunk;
 
     struct Keyed { double cost; ppd_work_item it; };
     std::vector<Keyed> keyed;
@@ -192,17 +244,33 @@ ppd_status build_plan(const ppd_shape& s, const int32_t* L, const int32_t* n, in
         }
     }
     std::stable_sort(shares.begin(), shares.end(), [](const Share& a, const Share& b) { return a.cost > b.cost; });
-    std::vector<ppd_work_item> queues[kXcds];
+    std::vector<size_t> members[kXcds];
     double load[kXcds] = {0};
-    for (auto& sh : shares) {
+    for (size_t k = 0; k < shares.size(); ++k) {
         int q = 0;
         for (int x = 1; x < kXcds; ++x)
             if (load[x] < load[q]) q = x;
-        load[q] += sh.cost;
-        for (auto& it : sh.items) {
-            it.queue = q;
-            queues[q].push_back(it);
-        }
+        load[q] += shares[k].cost;
+        members[q].push_back(k);
+    }
+    // Inside a queue the groups run longest TILE first (a group's tiles run side by side on different workgroups,
+    // so it is the length of one tile, not the sum over the group, that decides how late it may start): a single
+    // long tile of a short append-prefill must not wait behind groups of many short ones.
+    std::vector<ppd_work_item> queues[kXcds];
+    for (int q = 0; q < kXcds; ++q) {
+        auto longest = [&](size_t k) {
+            int32_t m = 0;
+            for (auto& it : shares[k].items) m = std::max(m, it.kv_end - it.kv_begin);
+            return m;
+        };
+        std::vector<std::pair<int32_t, size_t>> order;
+        for (size_t k : members[q]) order.emplace_back(longest(k), k);
+        std::stable_sort(order.begin(), order.end(), [](const std::pair<int32_t, size_t>& a, const std::pair<int32_t, size_t>& b) { return a.first > b.first; });
+        for (auto& o2 : order)
+            for (auto& it : shares[o2.second].items) {
+                it.queue = q;
+                queues[q].push_back(it);
+            }
     }
     std::stable_sort(narrow_items.begin(), narrow_items.end(), [](const Keyed& a, const Keyed& b) { return a.cost > b.cost; });
     plan->items.reserve(keyed.size());
