@@ -729,7 +729,23 @@ __global__ __launch_bounds__(kThreads, 2) void ppd_mixed_kernel(const KParams P)
         default: pref = 0; break;
     }
     const int xcd = (int)(__builtin_amdgcn_s_getreg((3 << 11) | (0 << 6) | 20) & (kXcds - 1));  // HW_REG_XCC_ID
-    unsigned dry = 0;  // bit q: queue q is exhausted (only thread 0 uses it)
+    // bit q: queue q is exhausted (only thread 0 uses it).  Queues that are empty by construction never cost an
+    // atomic; when a claim finds a queue exhausted, one batch of plain loads of all nine cursors tells which
+    // others are, instead of one failing atomic (a round trip to the L2 each, one after the other) per queue --
+    // that chain used to be the last ~10 us of every workgroup, and so of every launch.
+    unsigned dry = 0;
+#pragma unroll
+    for (int q = 0; q <= kNarrowQueue; ++q)
+        if (P.queue_begin[q + 1] == P.queue_begin[q]) dry |= 1u << q;
+    auto look_at_cursors = [&]() {
+        unsigned cur[kNarrowQueue + 1];
+#pragma unroll
+        for (int q = 0; q <= kNarrowQueue; ++q)
+            cur[q] = __hip_atomic_load(&P.counters[q], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+#pragma unroll
+        for (int q = 0; q <= kNarrowQueue; ++q)
+            if ((int)cur[q] >= P.queue_begin[q + 1] - P.queue_begin[q]) dry |= 1u << q;
+    };
     for (;;) {
         if (tid == 0) {
             int idx = -1;
@@ -745,8 +761,10 @@ __global__ __launch_bounds__(kThreads, 2) void ppd_mixed_kernel(const KParams P)
                         const int got = (int)atomicAdd(&P.counters[kNarrowQueue], 1u);
                         if (got < P.queue_begin[kNarrowQueue + 1] - P.queue_begin[kNarrowQueue])
                             idx = P.queue_begin[kNarrowQueue] + got;
-                        else
+                        else {
                             dry |= 1u << kNarrowQueue;
+                            if (dry != (2u << kNarrowQueue) - 1) look_at_cursors();
+                        }
                     }
                 } else {
                     for (int a = 0; a < kXcds && idx < 0; ++a) {
@@ -755,8 +773,10 @@ __global__ __launch_bounds__(kThreads, 2) void ppd_mixed_kernel(const KParams P)
                         const int got = (int)atomicAdd(&P.counters[q], 1u);
                         if (got < P.queue_begin[q + 1] - P.queue_begin[q])
                             idx = P.queue_begin[q] + got;
-                        else
+                        else {
                             dry |= 1u << q;
+                            if (dry != (2u << kNarrowQueue) - 1) look_at_cursors();
+                        }
                     }
                 }
             }
