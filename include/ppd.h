@@ -180,8 +180,8 @@ ppd_status ppd_device_error_flags(ppd_ctx *ctx, void *stream, uint32_t *flags);
  * the merge kernel are outside the bracket). */
 ppd_status ppd_last_kernel_ms(ppd_ctx *ctx, float *ms);
 
-/* Debugging aid: synchronises `stream` and copies the context's 64 device counter words (words 0..8 queue
- * cursors, 9 error flags, 10 finished workgroups, and -- in a build with -DPPD_PHASE_TIMING -- six 64-bit
+/* Debugging aid: synchronises `stream` and copies the context's 64 device counter words (word
+ * 9 error flags, 10 finished workgroups, and -- in a build with -DPPD_PHASE_TIMING -- six 64-bit
  * per-phase cycle sums of the MFMA tile loop in words 16..27) to HOST out64[64]; clear != 0 zeroes words
  * 16..63 afterwards. */
 ppd_status ppd_debug_counters(ppd_ctx *ctx, void *stream, uint32_t *out64, int32_t clear);

@@ -38,7 +38,7 @@ struct ppd_ctx {
     size_t d_items_bytes = 0;
     float* d_partials = nullptr;
     size_t d_partials_floats = 0;
-    uint32_t* d_counters = nullptr;  // 64 words: queue cursors, error flags, finished count, timing sums
+    uint32_t* d_counters = nullptr;  // kCounterWords words: error flags, finished count, timing sums; queue cursors
     Staging staging[kStagingSlots];
     int next_slot = 0;
     // the plan on the device stays valid while L, n and the planner options do not change (the layers of one
@@ -129,8 +129,9 @@ ppd_status ppd_create(const ppd_shape* shape, int32_t device, ppd_ctx** out) {
     ctx->num_cus = prop.multiProcessorCount > 0 ? prop.multiProcessorCount : 256;
     ctx->opts.num_cus = ctx->num_cus;
     if ((e = (hipError_t)ppd::prepare_mixed_kernels()) != hipSuccess) return bail(e, "hipFuncSetAttribute");
-    if ((e = hipMalloc((void**)&ctx->d_counters, 256)) != hipSuccess) return bail(e, "hipMalloc(counters)");
-    if ((e = hipMemset(ctx->d_counters, 0, 256)) != hipSuccess) return bail(e, "hipMemset(counters)");
+    const size_t counter_bytes = ppd::kCounterWords * sizeof(uint32_t);
+    if ((e = hipMalloc((void**)&ctx->d_counters, counter_bytes)) != hipSuccess) return bail(e, "hipMalloc(counters)");
+    if ((e = hipMemset(ctx->d_counters, 0, counter_bytes)) != hipSuccess) return bail(e, "hipMemset(counters)");
     for (auto& s : ctx->staging)
         if ((e = hipEventCreateWithFlags(&s.done, hipEventDisableTiming)) != hipSuccess) return bail(e, "hipEventCreate");
     if ((e = hipEventCreate(&ctx->ev_begin)) != hipSuccess) return bail(e, "hipEventCreate");

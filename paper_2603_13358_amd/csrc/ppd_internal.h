@@ -24,6 +24,12 @@ constexpr int kWgPerCu = kWaves == 8 ? 1 : 2;  // resident workgroups per comput
 constexpr int kTileTokens = 64;      // key tile of the MFMA path; every split boundary is a multiple of it
 constexpr int kMaxMfmaChunk = 32768;  // keys per MFMA row-block tile at most (its 2048 page ids are staged in LDS)
 constexpr int kSmallThreads = 256;
+// Device counters of a context: 64 words of flags and diagnostics, then the nine queue cursors, each in a
+// 128-byte line of its own (claims on different queues then do not queue up behind one another at one address
+// range of the memory side, where device-scope atomics execute).
+constexpr int kCursorBase = 64;    // word index of cursor 0
+constexpr int kCursorStride = 32;  // words between cursors
+constexpr int kCounterWords = kCursorBase + 9 * kCursorStride;
 constexpr int kMergeCols = 16;    // columns of a merge group one block of the merge kernel takes   // block size of the append and merge kernels
 
 // One merge group: a row block whose key range was split over `nsplit` tiles with consecutive partials.
@@ -77,7 +83,7 @@ struct KParams {
     const int32_t* page_tables;
     const ppd_work_item* items;
     float* partials;
-    uint32_t* counters;   // [0..8] queue cursors, [9] sticky error flags, [10] finished workgroups, [16..] timing
+    uint32_t* counters;   // [9] sticky error flags, [10] finished workgroups, [16..63] timing; queue cursors behind
     int32_t queue_begin[kXcds + 2];
     int64_t num_pages;
     int64_t page_stride;  // elements per page = 2 * Hkv * 16 * D

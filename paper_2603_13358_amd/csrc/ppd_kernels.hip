@@ -69,6 +69,17 @@ typedef short s16x4 __attribute__((ext_vector_type(4)));
 #define PPD_TICK_FLUSH(P) do {} while (0)
 #endif
 
+// Optional marks along the life of workgroup 0 (build with -DPPD_TILE_MARKS): the chip-wide 100 MHz clock at up
+// to 16 points, thread 0, into counters[48..63] (the last value written at a point wins).  Off in the product build.
+#ifdef PPD_TILE_MARKS
+#define PPD_MARK(P, k)                                                                     \
+    do {                                                                                   \
+        if (blockIdx.x == 0 && threadIdx.x == 0) (P).counters[48 + (k)] = (uint32_t)wall_clock64(); \
+    } while (0)
+#else
+#define PPD_MARK(P, k) do {} while (0)
+#endif
+
 __device__ __forceinline__ uint32_t pack_bf16(float a, float b) {
     f32x2 f = {a, b};
     bf16x2 r = __builtin_convertvector(f, bf16x2);  // round to nearest even
@@ -302,7 +313,9 @@ __device__ __forceinline__ void mfma_item(const KParams& P, const ppd_work_item&
     };
 
     // prologue: K(0..NS-1) and V(0..NS-2) are issued, K(0), K(1), V(0) must land; S^T of tile 0
+    PPD_MARK(P, 2);
     __syncthreads();  // page ids are in LDS
+    PPD_MARK(P, 3);
     {
 #pragma unroll
         for (int t = 0; t < NS; ++t) {
@@ -314,6 +327,7 @@ __device__ __forceinline__ void mfma_item(const KParams& P, const ppd_work_item&
         }
     }
     wait_all_loads();
+    PPD_MARK(P, 4);
     // The compiler does not count the asm loads; make it settle its own pending loads (the Q operand) here, or
     // it would place ever-decreasing memory-counter waits at their first use inside the loop and drain the
     // LDS-direct loads in flight there.
@@ -326,6 +340,7 @@ __device__ __forceinline__ void mfma_item(const KParams& P, const ppd_work_item&
     f32x16 s_cur[2];
     if (wave_active) qk_tile(0, s_cur);
     lds_barrier();  // with rings of NS stages the first iteration's loads overwrite K stage 0
+    PPD_MARK(P, 5);
     int st_cur = 0;   // ti % NS
     int sv_cur = 0;   // ti % NSV: V stage of tile ti
     // Two waves share a SIMD, and a wave issues in order.  An iteration is a vector phase (mask, max, rescale, the
@@ -467,6 +482,7 @@ __device__ __forceinline__ void mfma_item(const KParams& P, const ppd_work_item&
         PPD_TICK(5);
     }
     PPD_TICK_FLUSH(P);
+    PPD_MARK(P, 6);
 
     // epilogue: O^T register i of block db is d = db*32 + (i/4)*8 + h*4 + i%4 of column `col`
     const float l_tot = sum_halves(l_run);
@@ -704,6 +720,7 @@ __global__ __launch_bounds__(kThreads, 2) void ppd_mixed_kernel(const KParams P)
     // floats) uses the front of it.
     extern __shared__ __attribute__((aligned(16))) char smem[];
     PPD_WG_SPAN_BEGIN();
+    PPD_MARK(P, 0);
     __shared__ int s_next_slot;
     volatile int* s_next = &s_next_slot;
     const int tid = threadIdx.x;
@@ -741,7 +758,7 @@ __global__ __launch_bounds__(kThreads, 2) void ppd_mixed_kernel(const KParams P)
         unsigned cur[kNarrowQueue + 1];
 #pragma unroll
         for (int q = 0; q <= kNarrowQueue; ++q)
-            cur[q] = __hip_atomic_load(&P.counters[q], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            cur[q] = __hip_atomic_load(&P.counters[kCursorBase + q * kCursorStride], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 #pragma unroll
         for (int q = 0; q <= kNarrowQueue; ++q)
             if ((int)cur[q] >= P.queue_begin[q + 1] - P.queue_begin[q]) dry |= 1u << q;
@@ -758,7 +775,7 @@ __global__ __launch_bounds__(kThreads, 2) void ppd_mixed_kernel(const KParams P)
                 const bool want_narrow = (attempt == 0) == (pref == 1);
                 if (want_narrow) {
                     if (!(dry & (1u << kNarrowQueue))) {
-                        const int got = (int)atomicAdd(&P.counters[kNarrowQueue], 1u);
+                        const int got = (int)atomicAdd(&P.counters[kCursorBase + kNarrowQueue * kCursorStride], 1u);
                         if (got < P.queue_begin[kNarrowQueue + 1] - P.queue_begin[kNarrowQueue])
                             idx = P.queue_begin[kNarrowQueue] + got;
                         else {
@@ -770,7 +787,7 @@ __global__ __launch_bounds__(kThreads, 2) void ppd_mixed_kernel(const KParams P)
                     for (int a = 0; a < kXcds && idx < 0; ++a) {
                         const int q = (xcd + a) & (kXcds - 1);
                         if (dry & (1u << q)) continue;
-                        const int got = (int)atomicAdd(&P.counters[q], 1u);
+                        const int got = (int)atomicAdd(&P.counters[kCursorBase + q * kCursorStride], 1u);
                         if (got < P.queue_begin[q + 1] - P.queue_begin[q])
                             idx = P.queue_begin[q] + got;
                         else {
@@ -786,12 +803,15 @@ __global__ __launch_bounds__(kThreads, 2) void ppd_mixed_kernel(const KParams P)
         const int idx = __builtin_amdgcn_readfirstlane(*s_next);
         __syncthreads();  // everyone has read s_next, and the previous tile's LDS use is over
         if (idx < 0) break;
+        PPD_MARK(P, 1);
         const ppd_work_item it = P.items[idx];
         if (it.kind == 0)
             narrow_item<HD>(P, it, smem);
         else
             mfma_item<HD>(P, it, smem);
+        PPD_MARK(P, 7);
     }
+    PPD_MARK(P, 8);
     PPD_WG_SPAN_END(P);
     if (tid == 0) {
         // the last workgroup to run out of work re-arms the cursors for the next launch
@@ -799,7 +819,7 @@ __global__ __launch_bounds__(kThreads, 2) void ppd_mixed_kernel(const KParams P)
         if (done == gridDim.x - 1) {
 #pragma unroll
             for (int q = 0; q <= kNarrowQueue; ++q)
-                __hip_atomic_store(&P.counters[q], 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                __hip_atomic_store(&P.counters[kCursorBase + q * kCursorStride], 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
             __hip_atomic_store(&P.counters[10], 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
         }
     }
