@@ -58,7 +58,9 @@ static void split_range(int64_t len, int64_t chunk, std::vector<int32_t>* bounds
 // and ranks the candidates of one batch correctly.
 struct RowBlock { int64_t vis_end; int32_t nrows; };
 static int64_t choose_mfma_chunk(const std::vector<RowBlock>& blocks, int G, int Hkv, int D, double slots_for_mfma) {
-    constexpr double kTileStartUs = 16.0, kTileIterUs = 1.7;
+    constexpr double kTileStartUs = 16.0;
+    // 1.7 us per 64 keys at D = 128; at D = 64 the two products halve and the softmax stays (measured ~0.65x)
+    const double kTileIterUs = 1.7 * (0.3 + 0.7 * D / 128.0);
     constexpr double kMergeLaunchUs = 12.0, kPartialBytesPerUs = 2.5e6;
     static const int64_t kCandidates[] = {32768, 24576, 16384, 12288, 8192, 6144, 4096, 3072, 2048, 1024, 512};
     const int S = (int)std::max(1.0, std::floor(slots_for_mfma / Hkv + 0.5));

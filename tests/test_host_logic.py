@@ -123,6 +123,38 @@ def test_plan_covers_every_pair_once(opts):
         assert 1 <= st.grid <= max(1, st.n_items)
 
 
+def test_mfma_split_size_and_queue_order():
+    """The split size of the row-block tiles comes from a scheduling estimate: enough equal row blocks stay whole
+    (no partials); a single short append-prefill over a long context is cut until the tiles occupy the
+    workgroups; inside every MFMA queue the groups run longest tile first."""
+    # 8 sequences x 8 row blocks x 8 KV heads = 512 equal tiles on 256 workgroups: nothing to gain from splitting
+    items, st = ppd.ppd_plan_build(32, 8, 128, 16, 1 << 20, [8192] * 8, [512] * 8)
+    assert st.n_groups == 0 and st.n_items == 512 and st.mfma_chunk == 32768
+    # one row block per KV head over 32000 cached tokens: 8 whole tiles would leave 248 workgroups idle
+    items, st = ppd.ppd_plan_build(32, 8, 128, 16, 1 << 20, [32000], [64])
+    assert st.n_groups == 8 and 128 <= st.n_items <= 512
+    assert all(t.kv_end - t.kv_begin <= st.mfma_chunk + 64 for t in items)
+    # a fixed option overrides the estimate
+    items, st = ppd.ppd_plan_build(32, 8, 128, 16, 1 << 20, [32000], [64], mfma_chunk=4096)
+    assert st.mfma_chunk == 4096 and st.n_items == 8 * 8
+    # queue order: by the longest tile of a group, descending
+    rng = np.random.default_rng(11)
+    L = rng.integers(2048, 16384, size=16)
+    n = rng.integers(16, 1024, size=16)
+    items, st = ppd.ppd_plan_build(32, 8, 128, 16, 1 << 20, L, n)
+    for q in range(8):
+        longest, last = [], None
+        for t in items:
+            if t.queue != q:
+                continue
+            key = (t.seq, t.kvh, t.kv_begin)
+            if key != last:
+                longest.append(0)
+                last = key
+            longest[-1] = max(longest[-1], t.kv_end - t.kv_begin)
+        assert longest == sorted(longest, reverse=True)
+
+
 def test_plan_classification_follows_L_and_n():
     # n*G <= 16 columns is the narrow (decode-like) path; more rows go to the MFMA row blocks
     items, st = ppd.ppd_plan_build(32, 8, 128, 16, 1024, [100, 100, 100, 0], [1, 4, 5, 64])
