@@ -389,7 +389,7 @@ def main():
         print(json.dumps({"workload": "kv_landing_5115_tokens_32_layers", "landing": run_landing(torch, args.seed, args.steps)}))
         return
     if args.sweeps:
-        print(json.dumps({"workload": "interference_sweeps", "sweeps": run_sweeps(torch, args.seed, max(3, args.steps // 4),
+        print(json.dumps({"workload": "interference_sweeps", "sweeps": run_sweeps(torch, args.seed, max(10, args.steps // 2),
                                                                                   options)}))
         return
     if args.copy_probe:

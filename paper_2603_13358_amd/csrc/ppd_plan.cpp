@@ -50,49 +50,78 @@ static void split_range(int64_t len, int64_t chunk, std::vector<int32_t>* bounds
 
 // Split size of the MFMA row-block tiles.  Every split costs a partial (fp32 o, m, l per column) that the tile
 // writes and a separate merge launch reads back; not splitting leaves few, long tiles that may not fill or balance
-// the workgroups.  The choice is made by estimate: for each candidate size, the row blocks of ONE KV head are cut
-// (all heads are alike), their tiles list-scheduled longest-first onto slots / Hkv workgroups at
-// kTileStartUs + kTileIterUs per 64 keys, and the cost of the partials added; candidates run from whole key ranges
+// the workgroups.  The choice is made by estimate: for each candidate size the row blocks are cut (all KV heads
+// alike), their tiles list-scheduled longest-first, at kTileStartUs + kTileIterUs per 64 keys, onto the
+// workgroups that will take MFMA tiles first in the launch; the launch then takes the longer of that schedule and
+// of all work spread evenly over all workgroups (narrow tiles included: a compute unit streams ~45 GB/s, HBM
+// delivers ~6.5 TB/s to all of them together), plus the cost of the partials.  Candidates run from whole key ranges
 // downwards and stop once there are far more tiles than workgroups.  Constants fitted to measured launches
-// (append-prefill batches of 2..16 sequences, 256 workgroups): the estimate is within ~8 % of the kernel time
-// and ranks the candidates of one batch correctly.
+// (append-prefill batches of 2..16 sequences, 256 workgroups): the estimate is within ~8 % of the kernel time and
+// ranks the candidates of one batch correctly.
 struct RowBlock { int64_t vis_end; int32_t nrows; };
-static int64_t choose_mfma_chunk(const std::vector<RowBlock>& blocks, int G, int Hkv, int D, double slots_for_mfma) {
+
+// Compute units (of the 32 of an XCD) whose workgroups take narrow tiles first.  Two workgroups share a compute
+// unit; an MFMA tile next to a narrow tile on the same unit runs far below half the unit's MFMA rate, so the split
+// is by physical unit.  Narrow tiles are bound by the bytes a unit keeps in flight (about 45 GB/s each), MFMA tiles
+// by compute (about 2.3 us per 64 keys of a row block): the split is sized so that both kinds finish together;
+// whoever finishes first steals from the other anyway.
+static int narrow_units(double narrow_bytes, double mfma_iters) {
+    if (narrow_bytes == 0) return 0;
+    if (mfma_iters == 0) return 32;
+    const double narrow_cu_us = narrow_bytes / 45e3;  // CU-microseconds at 45 GB/s per unit
+    const double mfma_us = mfma_iters * 2.3 / kWgPerCu;
+    const int cus = (int)std::lround(32.0 * narrow_cu_us / (narrow_cu_us + mfma_us));
+    return std::min(std::max(cus, 2), 20);            // HBM saturates well before all units stream
+}
+
+static int64_t choose_mfma_chunk(const std::vector<RowBlock>& blocks, int G, int Hkv, int D, int slots,
+                                 double narrow_bytes) {
     constexpr double kTileStartUs = 16.0;
     // 1.7 us per 64 keys at D = 128; at D = 64 the two products halve and the softmax stays (measured ~0.65x)
     const double kTileIterUs = 1.7 * (0.3 + 0.7 * D / 128.0);
     constexpr double kMergeLaunchUs = 12.0, kPartialBytesPerUs = 2.5e6;
+    constexpr double kUnitBytesPerUs = 45e3, kHbmBytesPerUs = 6.5e6;
     static const int64_t kCandidates[] = {32768, 24576, 16384, 12288, 8192, 6144, 4096, 3072, 2048, 1024, 512};
-    const int S = (int)std::max(1.0, std::floor(slots_for_mfma / Hkv + 0.5));
+    const double narrow_work = narrow_bytes / kUnitBytesPerUs;  // unit-microseconds
+    const double narrow_floor = narrow_bytes / kHbmBytesPerUs;  // however many units stream
     int64_t best_chunk = kCandidates[0];
     double best = -1.0;
     std::vector<double> tiles, load;
     std::vector<int32_t> bounds;
     for (int64_t c : kCandidates) {
         tiles.clear();
-        double partial_bytes = 0;
+        double partial_bytes = 0, mfma_work = 0, iters = 0;
         for (const RowBlock& rb : blocks) {
             split_range(rb.vis_end, c, &bounds);
             const int nsplit = (int)bounds.size() - 1;
-            for (int k = 0; k < nsplit; ++k)
-                tiles.push_back(kTileStartUs + kTileIterUs * (double)((bounds[k + 1] - bounds[k] + kTileTokens - 1) / kTileTokens));
+            for (int k = 0; k < nsplit; ++k) {
+                const double it = (double)((bounds[k + 1] - bounds[k] + kTileTokens - 1) / kTileTokens);
+                tiles.push_back(kTileStartUs + kTileIterUs * it);
+                mfma_work += tiles.back() * Hkv;
+                iters += it * Hkv;
+            }
             if (nsplit > 1) partial_bytes += (double)rb.nrows * G * (D + 2) * 4.0 * nsplit * Hkv;
         }
+        // the workgroups that take MFMA tiles first, as the launch will split them
+        const int S = std::max(1, slots - narrow_units(narrow_bytes, iters) * slots / 32);
         std::sort(tiles.begin(), tiles.end(), std::greater<double>());
         load.assign((size_t)S, 0.0);  // min-heap of workgroup finish times
         auto later = [](double a, double b) { return a > b; };
-        for (double t : tiles) {
-            std::pop_heap(load.begin(), load.end(), later);
-            load.back() += t;
-            std::push_heap(load.begin(), load.end(), later);
-        }
+        for (double t : tiles)
+            for (int h = 0; h < Hkv; ++h) {
+                std::pop_heap(load.begin(), load.end(), later);
+                load.back() += t;
+                std::push_heap(load.begin(), load.end(), later);
+            }
         const double makespan = *std::max_element(load.begin(), load.end());
-        const double est = makespan + (partial_bytes > 0 ? kMergeLaunchUs + partial_bytes / kPartialBytesPerUs : 0.0);
+        const double even = std::max((mfma_work + narrow_work) / slots, narrow_floor);
+        const double est = std::max(makespan, even) +
+                           (partial_bytes > 0 ? kMergeLaunchUs + partial_bytes / kPartialBytesPerUs : 0.0);
         if (best < 0 || est < 0.99 * best) {  // a smaller chunk has to win clearly
             best = est;
             best_chunk = c;
         }
-        if ((int64_t)tiles.size() > 16LL * S) break;  // plenty of tiles already: smaller pieces only add partials
+        if ((int64_t)tiles.size() * Hkv > 16LL * S) break;  // plenty of tiles already: smaller pieces only add partials
     }
     return best_chunk;
 }
@@ -135,21 +164,16 @@ ppd_status build_plan(const ppd_shape& s, const int32_t* L, const int32_t* n, in
 
     // Total cost in "token units": a narrow tile costs its tokens, an MFMA tile twice its tokens (rough
     // ratio of time per key at the rates the two paths reach; only the order of tiles depends on it).
-    double cost_total = 0;
     double narrow_tokens = 0;  // keys of the narrow tiles, counted once per KV head
     std::vector<RowBlock> row_blocks;  // of one KV head
-    double mfma_iters = 0;             // 64-key steps of all row blocks of one KV head
     for (int i = 0; i < B; ++i) {
         if (is_narrow(i)) {
-            cost_total += (double)Hkv * (L[i] + n[i]);
             narrow_tokens += (double)Hkv * (L[i] + n[i]);
         } else {
             for (int r0 = 0; r0 < n[i]; r0 += rows_per_block) {
                 const int nrows = std::min(rows_per_block, n[i] - r0);
                 const int64_t vis_end = (int64_t)L[i] + r0 + nrows;
-                cost_total += 2.0 * Hkv * vis_end;
                 row_blocks.push_back(RowBlock{vis_end, nrows});
-                mfma_iters += std::ceil((double)vis_end / kTileTokens);
             }
         }
     }
@@ -162,14 +186,8 @@ ppd_status build_plan(const ppd_shape& s, const int32_t* L, const int32_t* n, in
                                ? o.narrow_chunk
                                : std::min<int64_t>(8192, std::max<int64_t>(512, round_up((int64_t)(narrow_tokens / 96), kTileTokens)));
     int64_t mfma_chunk = o.mfma_chunk;
-    if (mfma_chunk == 0 && !row_blocks.empty()) {
-        // workgroups left to the MFMA tiles when narrow tiles run beside them (same two constants as the split
-        // of the compute units below: 45 GB/s per unit streaming, 2.3 us per 64 keys of a row block)
-        const double narrow_cu_us = narrow_tokens * kv_tok_bytes_head / 45e3;
-        const double mfma_cu_us = mfma_iters * Hkv * 2.3;
-        const double share = std::max(12.0 / 32.0, mfma_cu_us / (mfma_cu_us + narrow_cu_us));
-        mfma_chunk = choose_mfma_chunk(row_blocks, G, Hkv, D, slots * share);
-    }
+    if (mfma_chunk == 0 && !row_blocks.empty())
+        mfma_chunk = choose_mfma_chunk(row_blocks, G, Hkv, D, slots, narrow_tokens * kv_tok_bytes_head);
     if (mfma_chunk == 0) mfma_chunk = kMaxMfmaChunk;
 
     struct Keyed { double cost; ppd_work_item it; };
@@ -287,28 +305,15 @@ ppd_status build_plan(const ppd_shape& s, const int32_t* L, const int32_t* n, in
     }
     plan->queue_begin[kNarrowQueue + 1] = (int32_t)plan->items.size();
 
-    // Split of the compute units between the two kinds when both are present.  Two workgroups share a compute
-    // unit; an MFMA tile next to a narrow tile on the same unit runs far below half the unit's MFMA rate, so
-    // the split is by physical unit: narrow_cus of the 32 units of every XCD take narrow tiles first, the others
-    // MFMA tiles.  Narrow tiles are bound by the bytes a unit keeps in flight (about 45 GB/s each), MFMA tiles
-    // by compute (about 2.3 us per 64-key tile of a row block on half a unit): size the split so that both
-    // kinds finish together; whoever finishes first steals from the other anyway.
+    // Split of the compute units between the two kinds when both are present (see narrow_units).
     {
-        double narrow_bytes = 0, mfma_us = 0;
+        double narrow_bytes = 0, mfma_iters = 0;
         for (auto& k : keyed) {
             const double toks = (double)(k.it.kv_end - k.it.kv_begin);
             if (k.it.kind == 0) narrow_bytes += toks * kv_tok_bytes_head;
-            else mfma_us += std::ceil(toks / kTileTokens) * 2.3 / kWgPerCu;
+            else mfma_iters += std::ceil(toks / kTileTokens);
         }
-        int cus = 16;
-        if (narrow_bytes == 0) cus = 0;
-        else if (mfma_us == 0) cus = 32;
-        else {
-            const double narrow_cu_us = narrow_bytes / 45e3;  // CU-microseconds at 45 GB/s per unit
-            cus = (int)std::lround(32.0 * narrow_cu_us / (narrow_cu_us + mfma_us));
-            cus = std::min(std::max(cus, 2), 20);             // HBM saturates well before all units stream
-        }
-        plan->narrow_cus = o.narrow_cus >= 0 ? std::min(o.narrow_cus, 32) : cus;
+        plan->narrow_cus = o.narrow_cus >= 0 ? std::min(o.narrow_cus, 32) : narrow_units(narrow_bytes, mfma_iters);
     }
 
     ppd_plan_stats& st = plan->stats;
