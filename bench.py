@@ -81,15 +81,21 @@ class Runner:
         torch.cuda.synchronize()
         return (time.perf_counter() - t0) * 1e3 / steps
 
-    def kernel_ms(self, steps):
-        """Average duration of the mixed kernel alone (HIP events recorded by the library around its launch)."""
+    def kernel_ms(self, steps, warmup=0):
+        """Mean duration of the mixed kernel alone over a timed region of its own: the same back-to-back steps as
+        time_steps, with a pair of HIP events recorded by the library around every launch of the kernel, on the
+        stream it is launched on; the events are read after the region has ended."""
+        for _ in range(warmup):
+            self.step()
+        self.torch.cuda.synchronize()
         self.ctx.set_option("timing", 1)
-        tot = 0.0
         for _ in range(steps):
             self.step()
-            tot += self.ctx.last_kernel_ms()
+        self.torch.cuda.synchronize()
+        total, launches = self.ctx.timed_kernels_ms()
         self.ctx.set_option("timing", 0)
-        return tot / steps
+        assert launches == steps
+        return total / launches
 
     def close(self):
         self.ctx.close()
@@ -346,8 +352,8 @@ def run_sweeps(torch, seed, steps, options):
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=20)
-    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--steps", type=int, default=50)
+    ap.add_argument("--warmup", type=int, default=20)
     ap.add_argument("--workload", default="cfg4_mixed_ap",
                     choices=["cfg4_mixed_ap", "cfg4_mixed_full", "cfg4_decode_only", "cfg2_decode", "cfg3_ap"])
     ap.add_argument("--seed", type=int, default=0)
@@ -408,7 +414,7 @@ def main():
         r.step()                                   # first call: plans and uploads
         first_plan_us = r.ctx.plan_stats().plan_host_us
         ms = r.time_steps(steps, warmup)
-        kms = r.kernel_ms(max(3, min(steps, 10)))
+        kms = r.kernel_ms(steps)
         st = r.ctx.plan_stats().as_dict()
         st["plan_host_us"] = first_plan_us
         res = {"workload": name, "ms_per_step": ms, "mixed_kernel_ms": kms, "plan": st,
@@ -440,11 +446,11 @@ def main():
 
     extras = {}
     if not args.no_extras:
-        few, fw = max(5, args.steps // 2), 3
+        few, fw = max(5, args.steps // 2), max(3, args.warmup // 2)
         for name in ["cfg4_decode_only", "cfg4_mixed_full", "cfg2_decode", "cfg3_ap", "cfg4_mixed_ap"]:
             if name == args.workload:
                 continue
-            steps = 3 if name == "cfg4_mixed_full" else few
+            steps = 5 if name == "cfg4_mixed_full" else few
             r = run(name, steps, 2 if name == "cfg4_mixed_full" else fw)
             ks = r["mixed_kernel_ms"] * 1e-3
             extras[name] = {"us_per_step": r["ms_per_step"] * 1e3, "mixed_kernel_us": r["mixed_kernel_ms"] * 1e3,

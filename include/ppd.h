@@ -180,6 +180,12 @@ ppd_status ppd_device_error_flags(ppd_ctx *ctx, void *stream, uint32_t *flags);
  * the merge kernel are outside the bracket). */
 ppd_status ppd_last_kernel_ms(ppd_ctx *ctx, float *ms);
 
+/* With option "timing" set: waits for the mixed-attention kernels of all ppd_mixed_attention calls made since the
+ * option was set or since the last call of this function (at most 4096 are kept; later ones are not timed),
+ * returns the sum of their durations in *total_ms and their number in *launches, and starts a new series.
+ * This is how a benchmark gets the kernel's mean duration over exactly its timed region. */
+ppd_status ppd_timed_kernels_ms(ppd_ctx *ctx, double *total_ms, int32_t *launches);
+
 /* Debugging aid: synchronises `stream` and copies the context's 64 device counter words (word
  * 9 error flags, 10 finished workgroups, and -- in a build with -DPPD_PHASE_TIMING -- six 64-bit
  * per-phase cycle sums of the MFMA tile loop in words 16..27) to HOST out64[64]; clear != 0 zeroes words

@@ -41,7 +41,7 @@ class PlanStats(ctypes.Structure):
 
 EXPORTS = ["ppd_create", "ppd_destroy", "ppd_last_error", "ppd_set_option", "ppd_kv_append", "ppd_kv_land",
            "ppd_transfer_delay_s", "ppd_mixed_attention",
-           "ppd_get_plan_stats", "ppd_plan_build", "ppd_device_error_flags", "ppd_last_kernel_ms", "ppd_debug_counters",
+           "ppd_get_plan_stats", "ppd_plan_build", "ppd_device_error_flags", "ppd_last_kernel_ms", "ppd_timed_kernels_ms", "ppd_debug_counters",
            "ppd_route_score", "ppd_route_table_build", "ppd_route_cell", "ppd_route_decide", "ppd_version"]
 
 
@@ -74,6 +74,7 @@ def load_library():
                                    ctypes.POINTER(WorkItem), i64, ctypes.POINTER(PlanStats)]
     lib.ppd_device_error_flags.argtypes = [vp, vp, ctypes.POINTER(ctypes.c_uint32)]
     lib.ppd_last_kernel_ms.argtypes = [vp, ctypes.POINTER(ctypes.c_float)]
+    lib.ppd_timed_kernels_ms.argtypes = [vp, ctypes.POINTER(ctypes.c_double), ctypes.POINTER(ctypes.c_int32)]
     lib.ppd_debug_counters.argtypes = [vp, vp, ctypes.POINTER(ctypes.c_uint32), i32]
     dbl = ctypes.c_double
     lib.ppd_route_score.argtypes = [dbl, dbl, dbl, dbl]
@@ -178,6 +179,14 @@ def ppd_last_kernel_ms(ctx):
     return float(ms.value)
 
 
+def ppd_timed_kernels_ms(ctx):
+    """(sum of the mixed kernel's durations in ms, number of launches) since timing was switched on / last asked."""
+    total = ctypes.c_double(0)
+    count = ctypes.c_int32(0)
+    _check(load_library().ppd_timed_kernels_ms(ctx, ctypes.byref(total), ctypes.byref(count)), ctx)
+    return float(total.value), int(count.value)
+
+
 def ppd_debug_counters(ctx, stream=None, clear=False):
     buf = (ctypes.c_uint32 * 64)()
     _check(load_library().ppd_debug_counters(ctx, stream, buf, 1 if clear else 0), ctx)
@@ -266,6 +275,9 @@ class Context:
 
     def last_kernel_ms(self):
         return ppd_last_kernel_ms(self.handle)
+
+    def timed_kernels_ms(self):
+        return ppd_timed_kernels_ms(self.handle)
 
     def device_error_flags(self, stream=None):
         return ppd_device_error_flags(self.handle, stream)

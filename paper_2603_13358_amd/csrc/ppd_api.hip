@@ -7,6 +7,7 @@
 #include <cstdio>
 #include <cstring>
 #include <string>
+#include <utility>
 #include <vector>
 
 #include "ppd_internal.h"
@@ -16,6 +17,7 @@ namespace {
 thread_local std::string g_create_error;
 
 constexpr int kStagingSlots = 4;
+constexpr size_t kMaxTimedLaunches = 4096;
 
 struct Staging {
     void* host = nullptr;  // pinned
@@ -46,10 +48,11 @@ struct ppd_ctx {
     std::vector<int32_t> plan_L, plan_n;
     ppd::PlanOptions plan_opts;
     bool plan_on_device = false;
-    // optional timing of the mixed kernel alone (option "timing")
+    // optional timing of the mixed kernel alone (option "timing"): one pair of events per launch since the option
+    // was set or the times were last collected, up to kMaxTimedLaunches
     bool timing = false;
-    bool timed = false;
-    hipEvent_t ev_begin = nullptr, ev_end = nullptr;
+    std::vector<std::pair<hipEvent_t, hipEvent_t>> ev_pairs;
+    size_t ev_used = 0;
 };
 
 namespace {
@@ -134,8 +137,6 @@ ppd_status ppd_create(const ppd_shape* shape, int32_t device, ppd_ctx** out) {
     if ((e = hipMemset(ctx->d_counters, 0, counter_bytes)) != hipSuccess) return bail(e, "hipMemset(counters)");
     for (auto& s : ctx->staging)
         if ((e = hipEventCreateWithFlags(&s.done, hipEventDisableTiming)) != hipSuccess) return bail(e, "hipEventCreate");
-    if ((e = hipEventCreate(&ctx->ev_begin)) != hipSuccess) return bail(e, "hipEventCreate");
-    if ((e = hipEventCreate(&ctx->ev_end)) != hipSuccess) return bail(e, "hipEventCreate");
     *out = ctx;
     return PPD_OK;
 }
@@ -151,8 +152,10 @@ ppd_status ppd_destroy(ppd_ctx* ctx) {
         if (s.host) (void)hipHostFree(s.host);
         if (s.done) (void)hipEventDestroy(s.done);
     }
-    if (ctx->ev_begin) (void)hipEventDestroy(ctx->ev_begin);
-    if (ctx->ev_end) (void)hipEventDestroy(ctx->ev_end);
+    for (auto& p : ctx->ev_pairs) {
+        if (p.first) (void)hipEventDestroy(p.first);
+        if (p.second) (void)hipEventDestroy(p.second);
+    }
     delete ctx;
     return PPD_OK;
 }
@@ -179,7 +182,7 @@ ppd_status ppd_set_option(ppd_ctx* ctx, const char* key, int64_t value) {
         ctx->opts.narrow_cus = (int32_t)value;
     } else if (k == "timing") {
         ctx->timing = value != 0;
-        ctx->timed = false;
+        ctx->ev_used = 0;
     } else {
         return fail(ctx, PPD_ERR_RANGE, "unknown option " + k);
     }
@@ -347,12 +350,22 @@ ppd_status ppd_mixed_attention(ppd_ctx* ctx, const void* q, const void* kv_pages
     kp.G = G;
     kp.invG = 65536 / G + 1;
     kp.scale_log2e = scale_log2e;
-    if (ctx->timing) PPD_HIP(ctx, hipEventRecord(ctx->ev_begin, hs));
+    const bool timed = ctx->timing && ctx->ev_used < kMaxTimedLaunches;
+    if (timed) {
+        if (ctx->ev_used == ctx->ev_pairs.size()) {
+            std::pair<hipEvent_t, hipEvent_t> p{nullptr, nullptr};
+            PPD_HIP(ctx, hipEventCreate(&p.first));
+            ctx->ev_pairs.push_back(p);  // owned by the context from here on, also if the second create fails
+            PPD_HIP(ctx, hipEventCreate(&ctx->ev_pairs.back().second));
+        }
+        if (!ctx->ev_pairs[ctx->ev_used].second) PPD_HIP(ctx, hipEventCreate(&ctx->ev_pairs[ctx->ev_used].second));
+        PPD_HIP(ctx, hipEventRecord(ctx->ev_pairs[ctx->ev_used].first, hs));
+    }
     int rc = ppd::launch_mixed(kp, ctx->shape.head_dim, plan.stats.grid, stream);
     if (rc != 0) return hip_fail(ctx, (hipError_t)rc, "launch mixed attention");
-    if (ctx->timing) {
-        PPD_HIP(ctx, hipEventRecord(ctx->ev_end, hs));
-        ctx->timed = true;
+    if (timed) {
+        PPD_HIP(ctx, hipEventRecord(ctx->ev_pairs[ctx->ev_used].second, hs));
+        ctx->ev_used += 1;
     }
     if (!plan.groups.empty()) {
         ppd::MergeParams mp;
@@ -382,10 +395,29 @@ ppd_status ppd_get_plan_stats(const ppd_ctx* ctx, ppd_plan_stats* stats) {
 
 ppd_status ppd_last_kernel_ms(ppd_ctx* ctx, float* ms) {
     if (!ctx || !ms) return fail(ctx, PPD_ERR_NULL, "ctx / ms is NULL");
-    if (!ctx->timed) return fail(ctx, PPD_ERR_RANGE, "no timed launch: set option \"timing\" to 1 and run a step");
+    if (ctx->ev_used == 0) return fail(ctx, PPD_ERR_RANGE, "no timed launch: set option \"timing\" to 1 and run a step");
     PPD_HIP(ctx, hipSetDevice(ctx->device));
-    PPD_HIP(ctx, hipEventSynchronize(ctx->ev_end));
-    PPD_HIP(ctx, hipEventElapsedTime(ms, ctx->ev_begin, ctx->ev_end));
+    const auto& p = ctx->ev_pairs[ctx->ev_used - 1];
+    PPD_HIP(ctx, hipEventSynchronize(p.second));
+    PPD_HIP(ctx, hipEventElapsedTime(ms, p.first, p.second));
+    return PPD_OK;
+}
+
+ppd_status ppd_timed_kernels_ms(ppd_ctx* ctx, double* total_ms, int32_t* launches) {
+    if (!ctx || !total_ms || !launches) return fail(ctx, PPD_ERR_NULL, "ctx / total_ms / launches is NULL");
+    *total_ms = 0.0;
+    *launches = 0;
+    PPD_HIP(ctx, hipSetDevice(ctx->device));
+    double sum = 0.0;
+    for (size_t i = 0; i < ctx->ev_used; ++i) {
+        float ms = 0.f;
+        PPD_HIP(ctx, hipEventSynchronize(ctx->ev_pairs[i].second));
+        PPD_HIP(ctx, hipEventElapsedTime(&ms, ctx->ev_pairs[i].first, ctx->ev_pairs[i].second));
+        sum += ms;
+    }
+    *total_ms = sum;
+    *launches = (int32_t)ctx->ev_used;
+    ctx->ev_used = 0;
     return PPD_OK;
 }
 

@@ -322,6 +322,36 @@ def test_host_argument_errors_enqueue_nothing():
         assert e.value.status == code
 
 
+def test_kernel_timing_series():
+    """Option "timing": one pair of events per launch; the series is read (and restarted) in one call."""
+    import torch
+    import paper_2603_13358_amd as ppd
+    b = si.cfg1_tiny(0)
+    pool, out, stats, ctx = _step(b, return_ctx=True)
+    with pytest.raises(ppd.PPDError):
+        ctx.last_kernel_ms()                       # nothing was timed yet
+    assert ctx.timed_kernels_ms() == (0.0, 0)
+    dev = torch.device("cuda:0")
+    from gpu_helpers import to_dev_u16
+    q = to_dev_u16(b.q, torch, dev)
+    pl = to_dev_u16(pool, torch, dev)
+    pt = torch.from_numpy(b.page_tables).to(dev)
+    o = torch.empty((b.T, b.Hq, b.D), dtype=torch.int16, device=dev)
+    ctx.set_option("timing", 1)
+    for _ in range(3):
+        ctx.mixed_attention(q, pl, pt, b.L, b.n, b.scale, o)
+    last = ctx.last_kernel_ms()
+    total, launches = ctx.timed_kernels_ms()
+    assert launches == 3 and 0.0 < last < total < 50.0
+    assert ctx.timed_kernels_ms() == (0.0, 0)
+    ctx.set_option("timing", 0)
+    ctx.mixed_attention(q, pl, pt, b.L, b.n, b.scale, o)
+    assert ctx.timed_kernels_ms() == (0.0, 0)
+    torch.cuda.synchronize()
+    assert np.array_equal(o.cpu().numpy().view(np.uint16), out)
+    ctx.close()
+
+
 def test_chunked_append_prefill_equals_one_shot():
     """An append-prefill fed in chunks over several steps (token-budgeted steps, as chunked-prefill schedulers
     do; the paper's related work, section 2.2) gives the rows of the one-shot append-prefill: each chunk is an
