@@ -162,9 +162,7 @@ ppd_status build_plan(const ppd_shape& s, const int32_t* L, const int32_t* n, in
     auto is_narrow = [&](int i) { return o.force_kind != 1 && (int64_t)n[i] * G <= kNarrowCols; };
     const int rows_per_block = kMfmaCols / G;
 
-    // Total cost in "token units": a narrow tile costs its tokens, an MFMA tile twice its tokens (rough
-    // ratio of time per key at the rates the two paths reach; only the order of tiles depends on it).
-    double narrow_tokens = 0;  // keys of the narrow tiles, counted once per KV head
+    double narrow_tokens = 0;          // keys of the narrow tiles, counted once per KV head
     std::vector<RowBlock> row_blocks;  // of one KV head
     for (int i = 0; i < B; ++i) {
         if (is_narrow(i)) {
