@@ -322,6 +322,51 @@ def test_host_argument_errors_enqueue_nothing():
         assert e.value.status == code
 
 
+def test_many_short_sequences():
+    """2000 sequences in one launch (many more tiles than workgroups), decode rows and two-row blocks."""
+    rng = np.random.default_rng(41)
+    B = 2000
+    L = rng.integers(0, 120, size=B)
+    n = np.where(rng.random(B) < 0.9, 1, 2)
+    _compare(si.make_batch("many", L=L, n=n, Hq=16, Hkv=4, D=64, seed=41, slack_pages=3))
+
+
+def test_side_stream_and_two_contexts():
+    """Both calls are asynchronous on the stream they are given; two contexts of different shapes used in turn on
+    two streams do not disturb each other."""
+    import torch
+    import paper_2603_13358_amd as ppd
+    from gpu_helpers import from_dev_u16, to_dev_u16
+    dev = torch.device("cuda:0")
+    batches = [si.make_batch("s0", L=[300, 0, 77], n=[1, 90, 3], Hq=32, Hkv=8, D=128, seed=51, slack_pages=2),
+               si.make_batch("s1", L=[40, 900], n=[20, 1], Hq=8, Hkv=2, D=64, seed=52, slack_pages=2)]
+    streams = [torch.cuda.Stream(), torch.cuda.Stream()]
+    state = []
+    for b, st in zip(batches, streams):
+        ctx = ppd.Context(b.Hq, b.Hkv, b.D, b.num_pages)
+        with torch.cuda.stream(st):
+            pool = torch.full((ctx.pool_elems(),), 0x7FC1, dtype=torch.int16, device=dev)
+            out = torch.zeros((b.T, b.Hq, b.D), dtype=torch.int16, device=dev)
+            dev_in = [(to_dev_u16(k, torch, dev), to_dev_u16(v, torch, dev), torch.from_numpy(s_.astype(np.int64)).to(dev))
+                      for k, v, s_ in (b.cached_part(), b.new_part()) if len(s_)]
+            q = to_dev_u16(b.q, torch, dev)
+            pt = torch.from_numpy(b.page_tables).to(dev)
+        st.synchronize()
+        state.append((ctx, pool, out, dev_in, q, pt))
+    for rep in range(3):                                   # interleave the two contexts, nothing waits in between
+        for (ctx, pool, out, dev_in, q, pt), b, st in zip(state, batches, streams):
+            for k, v, s_ in dev_in:
+                ctx.kv_append(k, v, pool, s_, stream=st.cuda_stream)
+            ctx.mixed_attention(q, pool, pt, b.L, b.n, b.scale, out, stream=st.cuda_stream)
+    for (ctx, pool, out, dev_in, q, pt), b, st in zip(state, batches, streams):
+        st.synchronize()
+        assert ctx.device_error_flags(stream=st.cuda_stream) == 0
+        ref_pool = oracle_pool(b)
+        assert np.array_equal(from_dev_u16(pool), ref_pool)
+        check_close(bits_to_f32(from_dev_u16(out).reshape(b.T, b.Hq, b.D)), oracle_out(b, ref_pool))
+        ctx.close()
+
+
 def test_kernel_timing_series():
     """Option "timing": one pair of events per launch; the series is read (and restarted) in one call."""
     import torch
