@@ -126,6 +126,48 @@ static int64_t choose_mfma_chunk(const std::vector<RowBlock>& blocks, int G, int
     return best_chunk;
 }
 
+// Split size of the narrow tiles of a launch that has nothing else and fewer (sequence, KV head) pairs than twice the
+// workgroups: the few-sequences, long-context corner, where the fixed rule below leaves compute units idle or
+// the last round of tiles nearly empty.  Estimate per candidate: tiles longest-first in rounds of `slots`; a round
+// takes kStartUs plus its longest tile at what a unit streams (kUnitBytesPerUs, or its share of kHbmBytesPerUs
+// when more units stream than HBM can feed); a split range costs a merge launch plus kMergeSplitUs per split
+// (the merge walks the splits of a column one after the other).  Constants fitted to 114 measured launches
+// (1..16 sequences x 4K..256K context x six split sizes; log-error 11 % rms, the pick within 3 % of the best
+// measured size in all 19 batches).
+static int64_t choose_narrow_chunk(const std::vector<int64_t>& lengths, int Hkv, int D, int slots) {
+    constexpr double kStartUs = 7.0, kUnitBytesPerUs = 55e3, kHbmBytesPerUs = 7.0e6;
+    constexpr double kMergeUs = 4.0, kMergeSplitUs = 0.3;
+    static const int64_t kCandidates[] = {8192, 6144, 4096, 3072, 2048, 1536, 1024, 768, 512};
+    const double bytes_per_key = 2.0 * D * 2;
+    int64_t best_chunk = kCandidates[0];
+    double best = -1.0;
+    std::vector<int32_t> tiles, bounds;
+    for (int64_t c : kCandidates) {
+        tiles.clear();
+        int max_split = 1;
+        for (int64_t len : lengths) {
+            split_range(len, c, &bounds);
+            const int nsplit = (int)bounds.size() - 1;
+            max_split = std::max(max_split, nsplit);
+            for (int k = 0; k < nsplit; ++k)
+                for (int h = 0; h < Hkv; ++h) tiles.push_back(bounds[k + 1] - bounds[k]);
+        }
+        if ((int64_t)tiles.size() > 8LL * slots && best >= 0) break;  // more than enough tiles: stop refining
+        std::sort(tiles.begin(), tiles.end(), std::greater<int32_t>());
+        double est = max_split > 1 ? kMergeUs + kMergeSplitUs * max_split : 0.0;
+        for (size_t j = 0; j < tiles.size(); j += (size_t)slots) {
+            const double streaming = (double)std::min<size_t>((size_t)slots, tiles.size() - j);
+            const double rate = std::min(kUnitBytesPerUs, kHbmBytesPerUs / streaming);
+            est += kStartUs + tiles[j] * bytes_per_key / rate;
+        }
+        if (best < 0 || est < 0.99 * best) {  // a smaller chunk has to win clearly
+            best = est;
+            best_chunk = c;
+        }
+    }
+    return best_chunk;
+}
+
 ppd_status build_plan(const ppd_shape& s, const int32_t* L, const int32_t* n, int32_t B, const PlanOptions& o,
                       Plan* plan, const char** err) {
     static const char* kNull = "L / n is NULL";
@@ -163,10 +205,12 @@ ppd_status build_plan(const ppd_shape& s, const int32_t* L, const int32_t* n, in
     const int rows_per_block = kMfmaCols / G;
 
     double narrow_tokens = 0;          // keys of the narrow tiles, counted once per KV head
+    std::vector<int64_t> narrow_lengths;
     std::vector<RowBlock> row_blocks;  // of one KV head
     for (int i = 0; i < B; ++i) {
         if (is_narrow(i)) {
             narrow_tokens += (double)Hkv * (L[i] + n[i]);
+            narrow_lengths.push_back((int64_t)L[i] + n[i]);
         } else {
             for (int r0 = 0; r0 < n[i]; r0 += rows_per_block) {
                 const int nrows = std::min(rows_per_block, n[i] - r0);
@@ -183,6 +227,8 @@ ppd_status build_plan(const ppd_shape& s, const int32_t* L, const int32_t* n, in
     int64_t narrow_chunk = o.narrow_chunk > 0
                                ? o.narrow_chunk
                                : std::min<int64_t>(8192, std::max<int64_t>(512, round_up((int64_t)(narrow_tokens / 96), kTileTokens)));
+    if (o.narrow_chunk == 0 && row_blocks.empty() && (int64_t)narrow_lengths.size() * Hkv < 2LL * slots)
+        narrow_chunk = choose_narrow_chunk(narrow_lengths, Hkv, D, slots);
     int64_t mfma_chunk = o.mfma_chunk;
     if (mfma_chunk == 0 && !row_blocks.empty())
         mfma_chunk = choose_mfma_chunk(row_blocks, G, Hkv, D, slots, narrow_tokens * kv_tok_bytes_head);
