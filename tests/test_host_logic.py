@@ -155,6 +155,22 @@ def test_mfma_split_size_and_queue_order():
         assert longest == sorted(longest, reverse=True)
 
 
+def test_narrow_split_size_of_small_decode_batches():
+    """Few sequences, long context: the key ranges are cut until the tiles occupy the workgroups without leaving a
+    nearly empty last round; many sequences keep their ranges whole."""
+    for B, L in [(1, 65536), (4, 16384), (2, 16384), (8, 65536)]:
+        items, st = ppd.ppd_plan_build(32, 8, 128, 16, 1 << 22, [L] * B, [1] * B)
+        assert st.n_narrow == st.n_items
+        per_round = st.n_items % 256 or 256
+        assert st.n_items >= 128 and per_round >= 128, (B, L, st.n_items)
+        assert 512 <= st.narrow_chunk <= 8192
+    items, st = ppd.ppd_plan_build(32, 8, 128, 16, 1 << 22, [4000] * 256, [1] * 256)
+    assert st.n_groups == 0 and st.n_items == 256 * 8
+    # a fixed option overrides the estimate
+    items, st = ppd.ppd_plan_build(32, 8, 128, 16, 1 << 22, [16384] * 4, [1] * 4, narrow_chunk=1024)
+    assert st.narrow_chunk == 1024 and st.n_items == 4 * 8 * 17
+
+
 def test_plan_classification_follows_L_and_n():
     # n*G <= 16 columns is the narrow (decode-like) path; more rows go to the MFMA row blocks
     items, st = ppd.ppd_plan_build(32, 8, 128, 16, 1024, [100, 100, 100, 0], [1, 4, 5, 64])
