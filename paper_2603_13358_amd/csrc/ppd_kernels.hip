@@ -726,10 +726,10 @@ __global__ __launch_bounds__(kThreads, 2) void ppd_mixed_kernel(const KParams P)
     const int tid = threadIdx.x;
     // Nine queues in one list: MFMA row-block tiles in eight queues, one per XCD (tiles that read the same K/V
     // sit in the same queue, next to each other, so the workgroups of one XCD find them in their L2), and one
-    // queue of narrow tiles; each longest-first.  A workgroup prefers one kind, chosen by the compute
+    // queue of narrow tiles; each longest tile first.  A workgroup prefers one kind, chosen by the compute
     // unit it runs on (narrow_cus of the 32 units of every XCD take narrow tiles, spread evenly over the shader
-    // engines; the planner sizes the split so that both kinds finish together): the two workgroups that share
-    // a unit then run the same kind, and HBM-bound and MFMA-bound tiles run side by side on different units.
+    // engines; the planner sizes the split so that both kinds finish together): workgroups that share a unit
+    // then run the same kind, and HBM-bound and MFMA-bound tiles run side by side on different units.
     // It takes MFMA tiles from its own XCD's queue first, and steals from the other queues when its own run dry.
     int pref;
     switch (P.pref_mode) {
