@@ -123,6 +123,25 @@ def test_plan_covers_every_pair_once(opts):
         assert 1 <= st.grid <= max(1, st.n_items)
 
 
+def test_plan_of_random_batches_covers_every_pair_once():
+    """Random head shapes, batch sizes and length mixes (decode, few-row, append-prefill, full prefill; contexts up
+    to 70K) through the automatic split choices: coverage, partial layout and the 32768-key limit of an MFMA tile."""
+    rng = np.random.default_rng(17)
+    for trial in range(60):
+        Hkv = int(rng.choice([1, 2, 4, 8, 16]))
+        G = int(rng.integers(1, 9))
+        D = int(rng.choice([64, 128]))
+        B = int(rng.choice([1, 2, 5, 30, 120]))
+        kind = rng.integers(0, 4, B)
+        L = np.where(kind == 3, 0, rng.integers(0, int(rng.choice([100, 5000, 70000])), B)).astype(np.int64)
+        n = np.where(kind == 0, 1, np.where(kind == 1, rng.integers(2, 9, B),
+                                            rng.integers(1, int(rng.choice([70, 700, 3000])), B))).astype(np.int64)
+        items, st = ppd.ppd_plan_build(G * Hkv, Hkv, D, 16, 1 << 24, L, n)
+        assert replay(items, L, n, Hkv, G, D) == st.partial_floats
+        assert all(t.kv_end - t.kv_begin <= 32768 for t in items if t.kind == 1)
+        assert all(t.kv_begin % 64 == 0 for t in items)
+
+
 def test_mfma_split_size_and_queue_order():
     """The split size of the row-block tiles comes from a scheduling estimate: enough equal row blocks stay whole
     (no partials); a single short append-prefill over a long context is cut until the tiles occupy the
