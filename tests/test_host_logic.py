@@ -233,3 +233,20 @@ def test_trace_schedule_is_consistent():
             seen_attend = True
         cached[s.conv] += s.n
     assert seen_attend and np.array_equal(cached, max_tokens)
+
+
+def test_bench_refuses_more_than_one_gpu_and_reads_its_traffic_file():
+    """bench.py measures one GPU (its --gpus N > 1 exits with a message, before anything touches a GPU), and its
+    roofline.traffic comes from the committed counter summary."""
+    import subprocess
+    import sys
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    res = subprocess.run([sys.executable, os.path.join(root, "bench.py"), "--gpus", "2"], stdout=subprocess.PIPE,
+                         stderr=subprocess.PIPE, text=True)
+    assert res.returncode != 0 and "one GPU" in (res.stderr + res.stdout)
+    import bench
+    for w in ("cfg4_mixed_ap", "cfg2_decode", "cfg3_ap", "cfg4_decode_only"):
+        t = bench.measured_traffic(w)
+        b = bench.make_shapes(w, 0)
+        assert t is not None and 0.9 * b.kv_read_bytes() < t < 3.0 * b.kv_read_bytes()
+    assert bench.measured_traffic("no_such_workload") is None
