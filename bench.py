@@ -91,6 +91,21 @@ class Runner:
         torch.cuda.synchronize()
         return (time.perf_counter() - t0) * 1e3 / steps
 
+    def step_distribution_us(self, steps):
+        """p10 / p50 / p90 of single steps (append + attention), each bracketed by events on the stream the work
+        runs on (torch's current stream), back to back, read after the region."""
+        torch = self.torch
+        ev = [torch.cuda.Event(enable_timing=True) for _ in range(steps + 1)]
+        torch.cuda.synchronize()
+        ev[0].record()
+        for i in range(steps):
+            self.step()
+            ev[i + 1].record()
+        torch.cuda.synchronize()
+        us = sorted(ev[i].elapsed_time(ev[i + 1]) * 1e3 for i in range(steps))
+        pick = lambda f: us[min(steps - 1, int(f * steps))]
+        return {"p10": pick(0.10), "p50": pick(0.50), "p90": pick(0.90), "steps": steps}
+
     def kernel_ms(self, steps, warmup=0):
         """Mean duration of the mixed kernel alone over a timed region of its own: the same back-to-back steps as
         time_steps, with a pair of HIP events recorded by the library around every launch of the kernel, on the
@@ -468,9 +483,10 @@ def main():
             r.step()
         ms = r.time_steps(steps, warmup)
         kms = r.kernel_ms(steps)
+        dist = r.step_distribution_us(steps) if want_cpu or name == args.workload else None
         st = r.ctx.plan_stats().as_dict()
         st["plan_host_us"] = first_plan_us
-        res = {"workload": name, "ms_per_step": ms, "mixed_kernel_ms": kms, "plan": st,
+        res = {"workload": name, "ms_per_step": ms, "mixed_kernel_ms": kms, "plan": st, "step_us": dist,
                "kv_bytes": b.kv_read_bytes(), "flops": b.attention_flops(), "rows": b.T, "sequences": b.B}
         if want_cpu:
             res["cpu"] = cpu_baseline(r)
@@ -531,6 +547,7 @@ def main():
                    "kv_bytes_per_step": b_bytes, "attention_flops_per_step": b_flops,
                    "tiles": main_res["plan"]["n_items"], "grid": main_res["plan"]["grid"],
                    "plan_host_us": main_res["plan"]["plan_host_us"],
+                   "step_us_distribution": main_res["step_us"],
                    "note": "steady state: the device plan is reused while L, n are unchanged, as across the "
                            "layers of one engine step; plan_host_us is the once-per-step planning cost"},
         "roofline": roofline,
