@@ -40,6 +40,18 @@ def measured_traffic(workload):
         return None
 
 
+def per_sequence_roofline_us(b):
+    """Sum over the sequences of max(KV bytes / HBM peak, attention flops / MFMA peak): the time at peak if every
+    sequence ran alone against the bound that governs it (decode rows: bytes; append-prefill rows above ~80 new
+    tokens at G = 4: flops)."""
+    import numpy as np
+    L = b.L.astype(np.float64)
+    n = b.n.astype(np.float64)
+    t_hbm = (L + n) * b.kv_bytes_per_token() / (HBM_PEAK_GBS * 1e9)
+    t_mfma = 4.0 * b.Hq * b.D * (n * L + n * (n + 1) / 2) / (MFMA_BF16_PEAK_TFLOPS * 1e12)
+    return float(np.sum(np.maximum(t_hbm, t_mfma)) * 1e6)
+
+
 def make_shapes(name, seed):
     import synthetic_inputs as si
     if name == "cfg4_mixed_ap":
@@ -487,7 +499,8 @@ def main():
         st = r.ctx.plan_stats().as_dict()
         st["plan_host_us"] = first_plan_us
         res = {"workload": name, "ms_per_step": ms, "mixed_kernel_ms": kms, "plan": st, "step_us": dist,
-               "kv_bytes": b.kv_read_bytes(), "flops": b.attention_flops(), "rows": b.T, "sequences": b.B}
+               "kv_bytes": b.kv_read_bytes(), "flops": b.attention_flops(), "rows": b.T, "sequences": b.B,
+               "seq_roofline_us": per_sequence_roofline_us(b)}
         if want_cpu:
             res["cpu"] = cpu_baseline(r)
         r.close()
@@ -509,6 +522,9 @@ def main():
     # no overlap between them; `frac` above is against the larger one alone, i.e. perfect overlap).
     roofline["time_at_peak_us"] = {"hbm": t_hbm * 1e6, "mfma": t_mfma * 1e6}
     roofline["frac_of_both_in_series"] = (t_hbm + t_mfma) / kernel_s
+    # ... and against the sum over the sequences of the bound that governs each (see per_sequence_roofline_us)
+    roofline["per_sequence_bound_us"] = main_res["seq_roofline_us"]
+    roofline["frac_of_per_sequence_bounds"] = main_res["seq_roofline_us"] * 1e-6 / kernel_s
     roofline["traffic"] = measured_traffic(args.workload)
     roofline["kernel"] = "ppd_mixed_kernel<128>"
     roofline["kernel_ms"] = main_res["mixed_kernel_ms"]
@@ -526,6 +542,7 @@ def main():
                             "hbm_GBs": r["kv_bytes"] / ks / 1e9, "hbm_frac": r["kv_bytes"] / ks / 1e9 / HBM_PEAK_GBS,
                             "mfma_TFLOPs": r["flops"] / ks / 1e12,
                             "mfma_frac": r["flops"] / ks / 1e12 / MFMA_BF16_PEAK_TFLOPS,
+                            "frac_of_per_sequence_bounds": r["seq_roofline_us"] * 1e-6 / ks,
                             "tiles": r["plan"]["n_items"]}
         extras[args.workload] = {"us_per_step": main_res["ms_per_step"] * 1e3,
                                  "mixed_kernel_us": main_res["mixed_kernel_ms"] * 1e3}
