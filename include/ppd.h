@@ -155,7 +155,8 @@ double ppd_transfer_delay_s(int64_t n_tokens, int64_t kv_bytes_per_token, double
  *   L, n          HOST int32 [B]
  *   scale         softmax scale (>= 0, finite), applied to q.k before the softmax
  * Result per row is the softmax-weighted average of the visible V rows; run-to-run bitwise deterministic
- * for fixed arguments and options.  B = 0 is a no-op. */
+ * for fixed arguments and options.  B = 0 is a no-op.  A batch whose work list would exceed 2^22 tiles (far beyond
+ * any step that fits the chip: a 128K-token full prefill needs ~10^5) is refused with PPD_ERR_RANGE. */
 ppd_status ppd_mixed_attention(ppd_ctx *ctx, const void *q, const void *kv_pages, const int32_t *page_tables,
                                int32_t max_pages, const int32_t *L, const int32_t *n, int32_t B, float scale,
                                void *out, void *stream);

@@ -9,6 +9,7 @@
 namespace ppd {
 
 constexpr int kPage = 16;            // tokens per page
+constexpr int kMaxTiles = 1 << 22;   // work-list entries of one launch (a 128K-token full prefill needs ~10^5)
 constexpr int kNarrowCols = 16;      // a narrow tile holds rows*G <= 16 query columns
 #ifndef PPD_WAVES
 #define PPD_WAVES 8

@@ -173,6 +173,7 @@ ppd_status build_plan(const ppd_shape& s, const int32_t* L, const int32_t* n, in
     static const char* kNull = "L / n is NULL";
     static const char* kNeg = "n_i must be >= 1 and L_i >= 0";
     static const char* kBig = "L_i + n_i and the total row count must stay below 2^30";
+    static const char* kTiles = "the batch needs more than 2^22 tiles: too large for one launch";
     static const char* kChunk = "chunk options must be 0 or a positive multiple of 64 (mfma_chunk <= 32768); grid >= 0";
     const char* dummy;
     if (!err) err = &dummy;
@@ -212,6 +213,8 @@ ppd_status build_plan(const ppd_shape& s, const int32_t* L, const int32_t* n, in
             narrow_tokens += (double)Hkv * (L[i] + n[i]);
             narrow_lengths.push_back((int64_t)L[i] + n[i]);
         } else {
+            const int64_t blocks = ((int64_t)n[i] + rows_per_block - 1) / rows_per_block;
+            if (((int64_t)row_blocks.size() + blocks) * Hkv > kMaxTiles) { *err = kTiles; return PPD_ERR_RANGE; }
             for (int r0 = 0; r0 < n[i]; r0 += rows_per_block) {
                 const int nrows = std::min(rows_per_block, n[i] - r0);
                 const int64_t vis_end = (int64_t)L[i] + r0 + nrows;
@@ -219,6 +222,7 @@ ppd_status build_plan(const ppd_shape& s, const int32_t* L, const int32_t* n, in
             }
         }
     }
+    if ((int64_t)(row_blocks.size() + narrow_lengths.size()) * Hkv > kMaxTiles) { *err = kTiles; return PPD_ERR_RANGE; }
     const int slots = o.grid > 0 ? o.grid : kWgPerCu * o.num_cus;  // resident workgroups
     // Narrow tiles: every split costs a partial and, above all, a gap in the workgroup's stream of loads (claim,
     // page ids, first loads: ~8 us), so key ranges stay whole unless the batch is too small to occupy the chip:
@@ -248,6 +252,7 @@ ppd_status build_plan(const ppd_shape& s, const int32_t* L, const int32_t* n, in
             const int64_t vis_end = (int64_t)L[i] + r0 + nrows;  // keys 0 .. L + last row of the block
             split_range(vis_end, narrow ? narrow_chunk : mfma_chunk, &bounds);
             const int nsplit = (int)bounds.size() - 1;
+            if ((int64_t)keyed.size() + (int64_t)nsplit * Hkv > kMaxTiles) { *err = kTiles; return PPD_ERR_RANGE; }
             const int64_t stride = (int64_t)nrows * G * (D + 2);
             for (int h = 0; h < Hkv; ++h) {
                 int group = -1;
@@ -280,6 +285,7 @@ ppd_status build_plan(const ppd_shape& s, const int32_t* L, const int32_t* n, in
                     bytes_tiles += toks * kv_tok_bytes_head;
                 }
             }
+
         }
         grow += n[i];
     }

@@ -190,6 +190,17 @@ def test_narrow_split_size_of_small_decode_batches():
     assert st.narrow_chunk == 1024 and st.n_items == 4 * 8 * 17
 
 
+def test_plan_refuses_a_batch_that_needs_millions_of_tiles():
+    # 2^29 new tokens in one sequence: 8.4M row blocks x 8 KV heads, far beyond one launch's work list
+    with pytest.raises(ppd.PPDError) as e:
+        ppd.ppd_plan_build(32, 8, 128, 16, 1 << 24, [0], [1 << 29])
+    assert e.value.status == -3
+    # many long decode sequences: tiles counted as they are made
+    with pytest.raises(ppd.PPDError) as e:
+        ppd.ppd_plan_build(32, 8, 128, 16, 1 << 24, [(1 << 30) - 2] * 64, [1] * 64, narrow_chunk=64)
+    assert e.value.status == -3
+
+
 def test_plan_classification_follows_L_and_n():
     # n*G <= 16 columns is the narrow (decode-like) path; more rows go to the MFMA row blocks
     items, st = ppd.ppd_plan_build(32, 8, 128, 16, 1024, [100, 100, 100, 0], [1, 4, 5, 64])
