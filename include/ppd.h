@@ -25,6 +25,11 @@
  *  - Values that live in device memory (page ids, slots) cannot be checked on the host; the kernels
  *    never dereference an out-of-range id (the token or key is skipped) and raise a sticky flag that
  *    ppd_device_error_flags reads back.
+ *  - ppd_kv_append enqueues one kernel launch.  ppd_mixed_attention plans on the host and uploads the plan when L, n
+ *    or the options differ from the previous call on the context (pinned staging buffer, one asynchronous copy);
+ *    otherwise -- the other layers of the same engine step -- it enqueues kernel launches only.  Such a step can be
+ *    captured into a HIP graph and replayed (the kernels reset their own queue cursors; no memset nodes); with the
+ *    option "timing" set, events are recorded as well, so leave it off under capture.
  *  - One context serves one stream at a time.  Calls on a context are not thread-safe.
  *
  * Page pool layout (bf16 elements; P = 16 tokens per page; D = head_dim; Hkv = KV heads):

@@ -367,6 +367,47 @@ def test_side_stream_and_two_contexts():
         ctx.close()
 
 
+def test_step_replays_from_a_hip_graph():
+    """A step whose plan is already on the device is two or three kernel launches and nothing else: captured into a
+    HIP graph it replays bit-identically, also with eager work and synchronisations between the replays."""
+    import torch
+    from gpu_helpers import from_dev_u16, to_dev_u16
+    b = si.make_batch("graph", L=[900, 0, 2500, 333, 64, 4000], n=[1, 150, 70, 2, 3, 1], Hq=32, Hkv=8, D=128, seed=61,
+                      slack_pages=3)
+    pool_ref, out_ref, stats, ctx = _step(b, return_ctx=True, options={"narrow_chunk": 512, "mfma_chunk": 512})
+    assert stats["n_groups"] > 0                      # the merge kernel is part of the step
+    dev = torch.device("cuda:0")
+    pool = to_dev_u16(oracle_pool(b, parts=("cached",)), torch, dev)
+    k, v, slots = b.new_part()
+    kd, vd = to_dev_u16(k, torch, dev), to_dev_u16(v, torch, dev)
+    sd = torch.from_numpy(slots.astype(np.int64)).to(dev)
+    q = to_dev_u16(b.q, torch, dev)
+    pt = torch.from_numpy(b.page_tables).to(dev)
+    out = torch.zeros((b.T, b.Hq, b.D), dtype=torch.int16, device=dev)
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):                      # same L, n, options as the step above: the plan is reused
+        ctx.kv_append(kd, vd, pool, sd, stream=side.cuda_stream)
+        ctx.mixed_attention(q, pool, pt, b.L, b.n, b.scale, out, stream=side.cuda_stream)
+    side.synchronize()
+    assert np.array_equal(from_dev_u16(out).reshape(out_ref.shape), out_ref)
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        s = torch.cuda.current_stream().cuda_stream
+        ctx.kv_append(kd, vd, pool, sd, stream=s)
+        ctx.mixed_attention(q, pool, pt, b.L, b.n, b.scale, out, stream=s)
+    for rep in range(4):
+        out.fill_(7)
+        scratch = torch.randn(1 << 20, device=dev).sum().item()      # eager work and a synchronisation in between
+        graph.replay()
+        torch.cuda.synchronize()
+        assert np.array_equal(from_dev_u16(out).reshape(out_ref.shape), out_ref), "replay %d differs" % rep
+    assert np.array_equal(from_dev_u16(pool), pool_ref)
+    assert ctx.device_error_flags() == 0
+    del graph
+    ctx.close()
+
+
 def test_kernel_timing_series():
     """Option "timing": one pair of events per launch; the series is read (and restarted) in one call."""
     import torch
