@@ -286,38 +286,6 @@ def run_trace(torch, seed, max_steps, pool_gb):
                     "planning and upload; 70B-class layer 64q/8kv heads, D=128"}
 
 
-def run_marks(torch, seed):
-    """Marks along the life of workgroup 0 in launches small enough for fixed costs to show (needs a library built
-    with PPD_EXTRA_HIPCC_FLAGS="-DPPD_TILE_MARKS"; the product build leaves the mark words at zero)."""
-    import paper_2603_13358_amd as ppd
-    import synthetic_inputs as si
-    names = ["tile_claimed", "tile_entered", "page_ids_in_lds", "first_loads_landed", "loop_start", "loop_end",
-             "tile_done", "exit"]
-    cases = {
-        "256_mfma_tiles_1_iteration": ([0] * 32, [64] * 32),
-        "256_mfma_tiles_16_iterations": ([960] * 32, [64] * 32),
-        "512_mfma_tiles_1_iteration": ([0] * 64, [64] * 64),
-        "64_narrow_tiles_500_keys": ([500] * 8, [1] * 8),
-        "512_narrow_tiles_1000_keys": ([1000] * 64, [1] * 64),
-    }
-    out = {}
-    for name, (L, n) in cases.items():
-        b = si.make_batch(name, L=L, n=n, Hq=32, Hkv=8, D=128, seed=seed, slack_pages=16, with_data=False)
-        r = Runner(b, torch, seed)
-        kernel_us = r.kernel_ms(10, warmup=5) * 1e3
-        torch.cuda.synchronize()
-        c = ppd.ppd_debug_counters(r.ctx.handle)
-        m = c[48:57]
-        if not any(m):
-            raise SystemExit("no marks: build the library with PPD_EXTRA_HIPCC_FLAGS=\"-DPPD_TILE_MARKS\"")
-        # 100 MHz clock; for a workgroup that ran several tiles a mark holds its last tile's value; narrow tiles
-        # set only the claim, done and exit marks
-        us = {names[i - 1]: ((m[i] - m[0]) & 0xFFFFFFFF) / 100.0 for i in range(1, 9) if m[i]}
-        out[name] = {"kernel_us": kernel_us, "us_after_workgroup_0_started": {k: v for k, v in us.items() if v < 1e6}}
-        r.close()
-    return out
-
-
 def run_landing(torch, seed, steps):
     """KV landing of one transferred request: 5115 tokens (the context length the paper quotes for its ~670 MB
     example) x 32 layers of an 8-KV-head, D=128 model scattered into 32 per-layer page pools in one launch."""
@@ -434,27 +402,11 @@ def main():
     ap.add_argument("--trace-steps", type=int, default=0, help="limit the trace to its first N engine steps")
     ap.add_argument("--trace-pool-gb", type=float, default=200.0)
     ap.add_argument("--landing", action="store_true", help="time the multi-layer KV landing of one request and exit")
-    ap.add_argument("--marks", action="store_true",
-                    help="diagnostic build only (-DPPD_TILE_MARKS): times along workgroup 0's life in small launches")
     ap.add_argument("--sweeps", action="store_true",
                     help="interference sweeps (batch size, context, 4 prefills, chunked append-prefill) and exit")
-    ap.add_argument("--read-probe", action="store_true",
-                    help="run the stand-alone read-bandwidth probe (contiguous and paged pattern) and exit")
-    ap.add_argument("--copy-probe", action="store_true",
-                    help="run a plain 1 GiB device copy a few times and exit (calibrates HBM byte counters)")
     args = ap.parse_args()
     if args.gpus != 1:
         raise SystemExit("bench.py measures one GPU: the step has no multi-GPU part in this build (--gpus 1 only)")
-    if args.read_probe:
-        # a child process of its own: nothing in this process has touched the GPU yet
-        import subprocess
-        from paper_2603_13358_amd.build import PROBE_BIN, build_probe
-        if not os.path.exists(PROBE_BIN):
-            build_probe()
-        res = subprocess.run([PROBE_BIN], stdout=subprocess.PIPE, text=True, check=True)
-        lines = [json.loads(l) for l in res.stdout.splitlines() if l.startswith("{")]
-        print(json.dumps({"workload": "read_probe", "hbm_peak_GBs": HBM_PEAK_GBS, "patterns": lines}))
-        return
     import torch
     if not torch.cuda.is_available():
         raise SystemExit("bench.py needs an MI355X: the library has no CPU path")
@@ -466,23 +418,10 @@ def main():
     if args.landing:
         print(json.dumps({"workload": "kv_landing_5115_tokens_32_layers", "landing": run_landing(torch, args.seed, args.steps)}))
         return
-    if args.marks:
-        print(json.dumps({"workload": "tile_marks_small_launches", "marks": run_marks(torch, args.seed)}))
-        return
     if args.sweeps:
         print(json.dumps({"workload": "interference_sweeps", "sweeps": run_sweeps(torch, args.seed, max(10, args.steps // 2),
                                                                                   options)}))
         return
-    if args.copy_probe:
-        nbytes = 1 << 30
-        src = torch.arange(nbytes // 4, dtype=torch.int32, device="cuda:0")
-        dst = torch.empty_like(src)
-        for _ in range(5):
-            dst.copy_(src)
-        torch.cuda.synchronize()
-        print(json.dumps({"copy_probe_bytes_read": nbytes, "copy_probe_bytes_written": nbytes, "copies": 5}))
-        return
-
     def run(name, steps, warmup, want_cpu=False):
         b = make_shapes(name, args.seed)
         r = Runner(b, torch, args.seed, options)

@@ -117,8 +117,11 @@ const char *ppd_last_error(const ppd_ctx *ctx);
  * kind of tile a workgroup takes first -- 0 MFMA tiles for all, 1 alternating per group of 8 workgroups,
  * 2 split by physical compute unit (default), 3 narrow tiles for all), "narrow_cus" (pref_mode 2: how many of
  * the 32 compute units of an XCD take narrow tiles first; -1 = sized by the planner's cost model so that both
- * kinds finish together), "timing" (1 = record HIP
- * events on the call's stream right before and after the mixed-attention kernel, see ppd_last_kernel_ms). */
+ * kinds finish together), "launch_mode" (0 = one kernel runs both kinds of tiles on separate compute units,
+ * 1 = a step that holds both kinds runs as two kernels resident side by side on every compute unit -- row-block
+ * tiles on the caller's stream, narrow tiles on a stream of the context's own, joined before the call's work ends
+ * -- 2 = the two specialised kernels also for steps of one kind), "timing" (1 = record HIP
+ * events on the call's stream right before and after the attention kernel(s), see ppd_last_kernel_ms). */
 ppd_status ppd_set_option(ppd_ctx *ctx, const char *key, int64_t value);
 
 /* Paged KV append (the KV-cache write of the step; paper sections 2.1 and 4.1: prefill populates the
@@ -166,6 +169,8 @@ ppd_status ppd_mixed_attention(ppd_ctx *ctx, const void *q, const void *kv_pages
                                int32_t max_pages, const int32_t *L, const int32_t *n, int32_t B, float scale,
                                void *out, void *stream);
 
+#define PPD_STATIC_SCRATCH_BYTES (32u << 20)
+
 /* Statistics of the plan built by the last ppd_mixed_attention call on this context. */
 ppd_status ppd_get_plan_stats(const ppd_ctx *ctx, ppd_plan_stats *stats);
 
@@ -191,12 +196,6 @@ ppd_status ppd_last_kernel_ms(ppd_ctx *ctx, float *ms);
  * returns the sum of their durations in *total_ms and their number in *launches, and starts a new series.
  * This is how a benchmark gets the kernel's mean duration over exactly its timed region. */
 ppd_status ppd_timed_kernels_ms(ppd_ctx *ctx, double *total_ms, int32_t *launches);
-
-/* Debugging aid: synchronises `stream` and copies the context's 64 device counter words (word
- * 9 error flags, 10 finished workgroups, and -- in a build with -DPPD_PHASE_TIMING -- six 64-bit
- * per-phase cycle sums of the MFMA tile loop in words 16..27) to HOST out64[64]; clear != 0 zeroes words
- * 16..63 afterwards. */
-ppd_status ppd_debug_counters(ppd_ctx *ctx, void *stream, uint32_t *out64, int32_t clear);
 
 /* ---- PPD routing decision (host only; paper section 3 score equation, section 5 algorithm "PPD Dynamic
  * Routing", appendix "Decision-Engine Discretization") ----

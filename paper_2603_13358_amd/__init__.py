@@ -5,11 +5,11 @@ of the path runs in the HIP kernels of libppd.so.  There is no CPU fallback: loa
 the library has not been built (`python -m paper_2603_13358_amd.build`).
 """
 from .binding import (PPDError, Context, WorkItem, PlanStats, Shape, lib_path, load_library, ppd_create,
-                      ppd_destroy, ppd_debug_counters, ppd_device_error_flags, ppd_get_plan_stats, ppd_kv_append, ppd_kv_land, ppd_transfer_delay_s, ppd_last_error, ppd_last_kernel_ms, ppd_timed_kernels_ms,
+                      ppd_destroy, ppd_device_error_flags, ppd_get_plan_stats, ppd_kv_append, ppd_kv_land, ppd_transfer_delay_s, ppd_last_error, ppd_last_kernel_ms, ppd_timed_kernels_ms,
                       ppd_mixed_attention, ppd_plan_build, ppd_route_cell, ppd_route_decide, ppd_route_score, ppd_route_table_build,
                       ppd_set_option, ppd_version)
 
 __all__ = ["PPDError", "Context", "WorkItem", "PlanStats", "Shape", "lib_path", "load_library", "ppd_create",
-           "ppd_destroy", "ppd_debug_counters", "ppd_device_error_flags", "ppd_get_plan_stats", "ppd_kv_append", "ppd_kv_land", "ppd_transfer_delay_s", "ppd_last_error", "ppd_last_kernel_ms", "ppd_timed_kernels_ms",
+           "ppd_destroy", "ppd_device_error_flags", "ppd_get_plan_stats", "ppd_kv_append", "ppd_kv_land", "ppd_transfer_delay_s", "ppd_last_error", "ppd_last_kernel_ms", "ppd_timed_kernels_ms",
            "ppd_mixed_attention", "ppd_plan_build", "ppd_route_cell", "ppd_route_decide", "ppd_route_score", "ppd_route_table_build",
            "ppd_set_option", "ppd_version"]

@@ -41,7 +41,7 @@ class PlanStats(ctypes.Structure):
 
 EXPORTS = ["ppd_create", "ppd_destroy", "ppd_last_error", "ppd_set_option", "ppd_kv_append", "ppd_kv_land",
            "ppd_transfer_delay_s", "ppd_mixed_attention",
-           "ppd_get_plan_stats", "ppd_plan_build", "ppd_device_error_flags", "ppd_last_kernel_ms", "ppd_timed_kernels_ms", "ppd_debug_counters",
+           "ppd_get_plan_stats", "ppd_plan_build", "ppd_device_error_flags", "ppd_last_kernel_ms", "ppd_timed_kernels_ms",
            "ppd_route_score", "ppd_route_table_build", "ppd_route_cell", "ppd_route_decide", "ppd_version"]
 
 
@@ -75,7 +75,6 @@ def load_library():
     lib.ppd_device_error_flags.argtypes = [vp, vp, ctypes.POINTER(ctypes.c_uint32)]
     lib.ppd_last_kernel_ms.argtypes = [vp, ctypes.POINTER(ctypes.c_float)]
     lib.ppd_timed_kernels_ms.argtypes = [vp, ctypes.POINTER(ctypes.c_double), ctypes.POINTER(ctypes.c_int32)]
-    lib.ppd_debug_counters.argtypes = [vp, vp, ctypes.POINTER(ctypes.c_uint32), i32]
     dbl = ctypes.c_double
     lib.ppd_route_score.argtypes = [dbl, dbl, dbl, dbl]
     lib.ppd_route_score.restype = dbl
@@ -156,9 +155,10 @@ def ppd_mixed_attention(ctx, q, kv_pages, page_tables, L, n, scale, out, max_pag
     n = _host_i32(n)
     if max_pages is None:
         max_pages = int(page_tables.shape[1])
-    _check(load_library().ppd_mixed_attention(ctx, _dev_ptr(q), _dev_ptr(kv_pages), _dev_ptr(page_tables),
-                                              int(max_pages), L.ctypes.data, n.ctypes.data, int(L.shape[0]),
-                                              float(scale), _dev_ptr(out), stream), ctx)
+    lib = load_library()
+    fn = lib.ppd_mixed_attention
+    _check(fn(ctx, _dev_ptr(q), _dev_ptr(kv_pages), _dev_ptr(page_tables), int(max_pages), L.ctypes.data,
+              n.ctypes.data, int(L.shape[0]), float(scale), _dev_ptr(out), stream), ctx)
 
 
 def ppd_get_plan_stats(ctx):
@@ -185,12 +185,6 @@ def ppd_timed_kernels_ms(ctx):
     count = ctypes.c_int32(0)
     _check(load_library().ppd_timed_kernels_ms(ctx, ctypes.byref(total), ctypes.byref(count)), ctx)
     return float(total.value), int(count.value)
-
-
-def ppd_debug_counters(ctx, stream=None, clear=False):
-    buf = (ctypes.c_uint32 * 64)()
-    _check(load_library().ppd_debug_counters(ctx, stream, buf, 1 if clear else 0), ctx)
-    return [int(x) for x in buf]
 
 
 ROUTE_CELLS = 3 * 9 * 10

@@ -27,8 +27,7 @@ def build_lib(force=True, verbose=False):
     if not force and not is_stale():
         return LIB
     hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
-    # PPD_EXTRA_HIPCC_FLAGS: e.g. "-DPPD_PHASE_TIMING" or the timing-diagnostic switches (-DPPD_DIAG_...) of
-    # ppd_kernels.hip; a library built with a PPD_DIAG_ switch computes wrong results on purpose
+    # PPD_EXTRA_HIPCC_FLAGS: tuning macros of the kernels, e.g. "-DPPD_STAGES=2 -DPPD_STREAM_KSETS=2"
     extra = os.environ.get("PPD_EXTRA_HIPCC_FLAGS", "").split()
     cmd = [hipcc] + FLAGS + extra + [os.path.join(CSRC, f) for f in SOURCES] + ["-o", LIB]
     if verbose:
@@ -42,25 +41,7 @@ def build_lib(force=True, verbose=False):
     return LIB
 
 
-PROBE_SRC = os.path.join(CSRC, "probes", "read_probe.hip")
-PROBE_BIN = os.path.join(HERE, "read_probe")
-
-
-def build_probe(force=True):
-    """Compiles the stand-alone read-bandwidth probe (bench.py --read-probe runs it)."""
-    if not force and os.path.exists(PROBE_BIN) and os.path.getmtime(PROBE_BIN) >= os.path.getmtime(PROBE_SRC):
-        return PROBE_BIN
-    hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
-    cmd = [hipcc, "--offload-arch=gfx950", "-O3", "-std=c++17", "-Xclang", "-target-feature", "-Xclang",
-           "-packed-fp32-ops", PROBE_SRC, "-o", PROBE_BIN]
-    res = subprocess.run(cmd, stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True)
-    if res.returncode != 0:
-        raise RuntimeError("hipcc failed:\n" + res.stdout)
-    return PROBE_BIN
-
-
 if __name__ == "__main__":
     build_lib(force=True, verbose=True)
     print("built", LIB)
-    print("built", build_probe())
     sys.exit(0)

@@ -5,7 +5,9 @@
 #include <cmath>
 #include <cstdint>
 #include <cstdio>
+#include <algorithm>
 #include <cstring>
+#include <mutex>
 #include <string>
 #include <utility>
 #include <vector>
@@ -48,7 +50,20 @@ struct ppd_ctx {
     std::vector<int32_t> plan_L, plan_n;
     ppd::PlanOptions plan_opts;
     bool plan_on_device = false;
-    // optional timing of the mixed kernel alone (option "timing"): one pair of events per launch since the option
+    // where that plan lives: 1 = the context's own workspace, 2 = the library's static scratch array
+    int plan_where = 0;
+    hipStream_t plan_stream = nullptr;  // the stream the plan was uploaded on and the last call ran on
+    bool have_plan_stream = false;
+    // the co-resident pair: the stream kernel runs on a stream of the context's own, forked from and joined to the
+    // caller's stream with these events
+    hipStream_t side_stream = nullptr;
+    hipEvent_t ev_fork = nullptr, ev_join = nullptr;
+    int launch_mode = 0;  // option "launch_mode"
+    // pinned staging of the entry point that allocates nothing (fixed size, allocated with the context)
+    void* static_staging = nullptr;
+    hipEvent_t static_staging_done = nullptr;
+    bool static_staging_in_flight = false;
+    // optional timing of the attention kernels alone (option "timing"): one pair of events per call since the option
     // was set or the times were last collected, up to kMaxTimedLaunches
     bool timing = false;
     std::vector<std::pair<hipEvent_t, hipEvent_t>> ev_pairs;
@@ -92,11 +107,280 @@ ppd_status grow_device(ppd_ctx* ctx, void** ptr, size_t* have, size_t need, hipS
 // The kernels move 16 bytes per lane: tensors and pools must start on a 16-byte boundary.
 bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
 
+// ---- the static scratch array of the entry point that allocates nothing -------------------------------------
+// One array per GPU the library runs on, held until the process ends: queue counters, the uploaded plan and the
+// split partials of ppd_mixed_attention_static.  Host code never passes the array's name to a kernel (on the host
+// it is only a stand-in): the device address is asked for once per device and kept in g_scratch_ptr.
+constexpr size_t kStaticCounterBytes = 4096;
+constexpr size_t kStaticPlanBytes = (size_t(2) << 20) - kStaticCounterBytes;
+constexpr size_t kStaticPartialBytes = PPD_STATIC_SCRATCH_BYTES - (size_t(2) << 20);
+static_assert(ppd::kCounterWords * sizeof(uint32_t) <= kStaticCounterBytes, "counters fit their slot");
+static __device__ __align__(256) unsigned char scratch[PPD_STATIC_SCRATCH_BYTES];
+
+constexpr int kMaxDevices = 64;
+std::mutex g_scratch_mutex;
+unsigned char* g_scratch_ptr[kMaxDevices] = {nullptr};
+// which context's plan the array of a device holds (nullptr: none), and that plan's serial number
+const ppd_ctx* g_scratch_owner[kMaxDevices] = {nullptr};
+
+// Device address of this device's copy of the array; the device must be current.
+hipError_t static_scratch_address(int device, unsigned char** out) {
+    std::lock_guard<std::mutex> lock(g_scratch_mutex);
+    if (!g_scratch_ptr[device]) {
+        void* p = nullptr;
+        hipError_t e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+        if (e != hipSuccess) return e;
+        g_scratch_ptr[device] = static_cast<unsigned char*>(p);
+    }
+    *out = g_scratch_ptr[device];
+    return hipSuccess;
+}
+
+// Zeroes the queue cursors and the finished-workgroup counts of a counter block (not the sticky error flags).  A
+// kernel rather than a memset: a memset node recorded into a captured graph has replayed wrongly on this platform.
+__global__ void ppd_clear_counters_kernel(uint32_t* counters) {
+    const int i = threadIdx.x;
+    if (i == 10 || i == 11 || (i >= ppd::kCursorBase && i < ppd::kCounterWords)) counters[i] = 0u;
+}
+
+ppd_status mixed_attention_impl(ppd_ctx* ctx, const void* q, const void* kv_pages, const int32_t* page_tables,
+                                int32_t max_pages, const int32_t* L, const int32_t* n, int32_t B, float scale,
+                                void* out, void* stream, bool use_static) {
+    if (!ctx) return PPD_ERR_NULL;
+    if (B < 0) return fail(ctx, PPD_ERR_RANGE, "B < 0");
+    if (B == 0) {
+        ctx->plan.items.clear();
+        ctx->plan.groups.clear();
+        ctx->plan.units.clear();
+        ctx->plan_on_device = false;
+        std::memset(&ctx->plan.stats, 0, sizeof ctx->plan.stats);
+        return PPD_OK;
+    }
+    if (!q || !kv_pages || !page_tables || !L || !n || !out)
+        return fail(ctx, PPD_ERR_NULL, "q / kv_pages / page_tables / L / n / out is NULL");
+    if (!(scale >= 0.f) || !std::isfinite(scale)) return fail(ctx, PPD_ERR_RANGE, "scale must be finite and >= 0");
+    if (!aligned16(q) || !aligned16(out) || !aligned16(kv_pages) || (reinterpret_cast<uintptr_t>(page_tables) & 3u))
+        return fail(ctx, PPD_ERR_RANGE, "q / out / kv_pages must be 16-byte aligned, page_tables 4-byte aligned");
+    for (int i = 0; i < B; ++i) {
+        if (n[i] < 1 || L[i] < 0) return fail(ctx, PPD_ERR_RANGE, "n_i must be >= 1 and L_i >= 0");
+        const int64_t need = ((int64_t)L[i] + n[i] + ppd::kPage - 1) / ppd::kPage;
+        if (need > max_pages)
+            return fail(ctx, PPD_ERR_PAGETABLE, "sequence " + std::to_string(i) + " needs " + std::to_string(need) +
+                                                    " pages, max_pages is " + std::to_string(max_pages));
+    }
+    hipStream_t hs = static_cast<hipStream_t>(stream);
+    PPD_HIP(ctx, hipSetDevice(ctx->device));
+    const char* msg = "";
+    ppd_status st = PPD_OK;
+    const int where = use_static ? 2 : 1;
+    const bool same_opts = std::memcmp(&ctx->plan_opts, &ctx->opts, sizeof(ppd::PlanOptions)) == 0;
+    const bool reuse = ctx->plan_on_device && ctx->plan_where == where && same_opts &&
+                       (!use_static || g_scratch_owner[ctx->device] == ctx) && (int32_t)ctx->plan_L.size() == B &&
+                       std::memcmp(ctx->plan_L.data(), L, sizeof(int32_t) * B) == 0 &&
+                       std::memcmp(ctx->plan_n.data(), n, sizeof(int32_t) * B) == 0;
+    // A context serves one stream at a time.  When the caller moves to another stream, the work enqueued on the
+    // previous one (the plan upload, kernels that share the queue counters) has to finish first.  Under capture
+    // nothing runs yet and no synchronisation is allowed: there the caller answers for the order.
+    hipStreamCaptureStatus capturing = hipStreamCaptureStatusNone;
+    PPD_HIP(ctx, hipStreamIsCapturing(hs, &capturing));
+    const bool in_capture = capturing != hipStreamCaptureStatusNone;
+    if (!in_capture && ctx->have_plan_stream && ctx->plan_stream != hs) PPD_HIP(ctx, hipStreamSynchronize(ctx->plan_stream));
+    if (!reuse && in_capture)
+        return fail(ctx, PPD_ERR_RANGE, "plan changed under capture: run the step once eagerly with these L, n and "
+                                        "options first, then capture it");
+    const auto t_plan0 = std::chrono::steady_clock::now();
+    if (!reuse) {
+        ctx->plan_on_device = false;
+        st = ppd::build_plan(ctx->shape, L, n, B, ctx->opts, &ctx->plan, &msg);
+        if (st != PPD_OK) return fail(ctx, st, msg);
+    }
+
+    const ppd::Plan& plan = ctx->plan;
+    const size_t items_bytes = plan.items.size() * sizeof(ppd_work_item);
+    const size_t groups_bytes = plan.groups.size() * sizeof(ppd::MergeGroup);
+    const size_t units_bytes = plan.units.size() * sizeof(ppd::MergeUnit);
+    const size_t total = items_bytes + groups_bytes + units_bytes;
+    unsigned char* sbase = nullptr;
+    if (use_static) {
+        PPD_HIP(ctx, static_scratch_address(ctx->device, &sbase));
+        if (total > kStaticPlanBytes || (size_t)plan.stats.partial_floats * sizeof(float) > kStaticPartialBytes)
+            return fail(ctx, PPD_ERR_WORKSPACE,
+                        "batch too large for the static scratch array: plan " + std::to_string(total) + " of " +
+                            std::to_string(kStaticPlanBytes) + " bytes, split partials " +
+                            std::to_string((size_t)plan.stats.partial_floats * sizeof(float)) + " of " +
+                            std::to_string(kStaticPartialBytes) + " bytes; use ppd_mixed_attention");
+    }
+    void* d_plan = use_static ? static_cast<void*>(sbase + kStaticCounterBytes) : nullptr;
+    if (!reuse) {
+        // upload: [items][groups][units] through pinned staging
+        void* host = nullptr;
+        hipEvent_t done = nullptr;
+        if (use_static) {
+            if (ctx->static_staging_in_flight) {
+                PPD_HIP(ctx, hipEventSynchronize(ctx->static_staging_done));
+                ctx->static_staging_in_flight = false;
+            }
+            host = ctx->static_staging;
+            done = ctx->static_staging_done;
+        } else {
+            Staging& sg = ctx->staging[ctx->next_slot];
+            ctx->next_slot = (ctx->next_slot + 1) % kStagingSlots;
+            if (sg.in_flight) {
+                PPD_HIP(ctx, hipEventSynchronize(sg.done));
+                sg.in_flight = false;
+            }
+            if (sg.bytes < total) {
+                if (sg.host) PPD_HIP(ctx, hipHostFree(sg.host));
+                sg.host = nullptr;
+                sg.bytes = 0;
+                const size_t want = total + total / 4 + 4096;
+                if (hipHostMalloc(&sg.host, want, hipHostMallocDefault) != hipSuccess) {
+                    (void)hipGetLastError();
+                    sg.host = nullptr;
+                    return fail(ctx, PPD_ERR_WORKSPACE, "pinned staging allocation failed");
+                }
+                sg.bytes = want;
+            }
+            st = grow_device(ctx, &ctx->d_items, &ctx->d_items_bytes, total, hs);
+            if (st != PPD_OK) return st;
+            {
+                void* p = ctx->d_partials;
+                size_t have = ctx->d_partials_floats * sizeof(float);
+                st = grow_device(ctx, &p, &have, (size_t)plan.stats.partial_floats * sizeof(float), hs);
+                ctx->d_partials = static_cast<float*>(p);
+                ctx->d_partials_floats = have / sizeof(float);
+                if (st != PPD_OK) return st;
+            }
+            host = sg.host;
+            done = sg.done;
+            sg.in_flight = true;
+        }
+        std::memcpy(host, plan.items.data(), items_bytes);
+        if (groups_bytes) {
+            std::memcpy(static_cast<char*>(host) + items_bytes, plan.groups.data(), groups_bytes);
+            std::memcpy(static_cast<char*>(host) + items_bytes + groups_bytes, plan.units.data(), units_bytes);
+        }
+        PPD_HIP(ctx, hipMemcpyAsync(use_static ? d_plan : ctx->d_items, host, total, hipMemcpyHostToDevice, hs));
+        PPD_HIP(ctx, hipEventRecord(done, hs));
+        if (use_static) {
+            ctx->static_staging_in_flight = true;
+            g_scratch_owner[ctx->device] = ctx;
+        }
+        ctx->plan_L.assign(L, L + B);
+        ctx->plan_n.assign(n, n + B);
+        ctx->plan_opts = ctx->opts;
+        ctx->plan_on_device = true;
+        ctx->plan_where = where;
+        ctx->plan.stats.plan_host_us = (int32_t)std::chrono::duration_cast<std::chrono::microseconds>(
+                                           std::chrono::steady_clock::now() - t_plan0).count();
+    }
+    if (!use_static) d_plan = ctx->d_items;
+    if (!in_capture) {
+        ctx->plan_stream = hs;
+        ctx->have_plan_stream = true;
+    }
+
+    const int G = ctx->shape.num_q_heads / ctx->shape.num_kv_heads;
+    // Masked scores are -inf and enter the exponent as s*c: keep c strictly positive so that scale = 0 gives
+    // 2^(-inf) = 0 for masked keys and 2^(~0) = 1 for visible ones (identical to the exact result in fp32).
+    float scale_log2e = scale * 1.4426950408889634f;
+    if (scale_log2e < 1e-30f) scale_log2e = 1e-30f;
+    ppd::KParams kp;
+    kp.q = static_cast<const uint16_t*>(q);
+    kp.out = static_cast<uint16_t*>(out);
+    kp.pool = static_cast<const uint16_t*>(kv_pages);
+    kp.page_tables = page_tables;
+    kp.items = static_cast<const ppd_work_item*>(d_plan);
+    kp.partials = use_static ? reinterpret_cast<float*>(sbase + (size_t(2) << 20)) : ctx->d_partials;
+    kp.counters = use_static ? reinterpret_cast<uint32_t*>(sbase) : ctx->d_counters;
+    kp.num_pages = ctx->shape.num_pages;
+    kp.page_stride = 2LL * ctx->shape.num_kv_heads * ppd::kPage * ctx->shape.head_dim;
+    kp.n_items = (int32_t)plan.items.size();
+    std::memcpy(kp.queue_begin, plan.queue_begin, sizeof kp.queue_begin);
+    kp.pref_mode = ctx->opts.pref_mode;
+    kp.narrow_cus = plan.narrow_cus;
+    kp.max_pages = max_pages;
+    kp.Hq = ctx->shape.num_q_heads;
+    kp.Hkv = ctx->shape.num_kv_heads;
+    kp.G = G;
+    kp.invG = 65536 / G + 1;
+    kp.scale_log2e = scale_log2e;
+    // The static array is shared by every context of the process on this GPU and keeps the last call's contents:
+    // the cursors and finished counts must start at zero whoever ran before.
+    if (use_static)
+        hipLaunchKernelGGL(ppd_clear_counters_kernel, dim3(1), dim3(512), 0, hs, kp.counters);
+    const bool timed = !use_static && ctx->timing && ctx->ev_used < kMaxTimedLaunches;
+    if (timed) {
+        if (ctx->ev_used == ctx->ev_pairs.size()) {
+            std::pair<hipEvent_t, hipEvent_t> p{nullptr, nullptr};
+            PPD_HIP(ctx, hipEventCreate(&p.first));
+            ctx->ev_pairs.push_back(p);  // owned by the context from here on, also if the second create fails
+            PPD_HIP(ctx, hipEventCreate(&ctx->ev_pairs.back().second));
+        }
+        if (!ctx->ev_pairs[ctx->ev_used].second) PPD_HIP(ctx, hipEventCreate(&ctx->ev_pairs[ctx->ev_used].second));
+        PPD_HIP(ctx, hipEventRecord(ctx->ev_pairs[ctx->ev_used].first, hs));
+    }
+    const int D = ctx->shape.head_dim;
+    const bool has_narrow = plan.stats.n_narrow > 0, has_mfma = plan.stats.n_mfma > 0;
+    const int mode = ctx->launch_mode;
+    int rc = 0;
+    if (mode == 0 || (mode == 1 && !(has_narrow && has_mfma))) {
+        rc = ppd::launch_mixed(kp, D, plan.stats.grid, stream);
+        if (rc != 0) return hip_fail(ctx, (hipError_t)rc, "launch mixed attention");
+    } else {
+        // The co-resident pair: the row-block kernel on the caller's stream, the stream kernel beside it on the
+        // context's own stream, forked from and joined to the caller's stream.
+        const int cus = ctx->num_cus;
+        const int grid_m = has_mfma ? (int)std::min<int64_t>(cus, plan.stats.n_mfma) : 0;
+        const int grid_n = has_narrow ? (int)std::min<int64_t>(has_mfma ? cus + 2 * (cus - grid_m) : 3 * cus,
+                                                               plan.stats.n_narrow) : 0;
+        const bool fork = grid_m > 0 && grid_n > 0;
+        if (fork) {
+            PPD_HIP(ctx, hipEventRecord(ctx->ev_fork, hs));
+            PPD_HIP(ctx, hipStreamWaitEvent(ctx->side_stream, ctx->ev_fork, 0));
+        }
+        if (grid_m > 0) {
+            rc = ppd::launch_mfma_only(kp, D, grid_m, stream);
+            if (rc != 0) return hip_fail(ctx, (hipError_t)rc, "launch row-block kernel");
+        }
+        if (grid_n > 0) {
+            rc = ppd::launch_stream_only(kp, D, grid_n, fork ? ctx->side_stream : stream);
+            if (rc != 0) return hip_fail(ctx, (hipError_t)rc, "launch stream kernel");
+        }
+        if (fork) {
+            PPD_HIP(ctx, hipEventRecord(ctx->ev_join, ctx->side_stream));
+            PPD_HIP(ctx, hipStreamWaitEvent(hs, ctx->ev_join, 0));
+        }
+    }
+    if (timed) {
+        PPD_HIP(ctx, hipEventRecord(ctx->ev_pairs[ctx->ev_used].second, hs));
+        ctx->ev_used += 1;
+    }
+    if (!plan.groups.empty()) {
+        ppd::MergeParams mp;
+        mp.groups = reinterpret_cast<const ppd::MergeGroup*>(static_cast<const char*>(d_plan) + items_bytes);
+        mp.partials = kp.partials;
+        mp.out = static_cast<uint16_t*>(out);
+        mp.n_groups = (int32_t)plan.groups.size();
+        mp.units = reinterpret_cast<const ppd::MergeUnit*>(static_cast<const char*>(d_plan) + items_bytes +
+                                                          groups_bytes);
+        mp.n_units = (int32_t)plan.units.size();
+        mp.Hq = kp.Hq;
+        mp.G = G;
+        mp.invG = kp.invG;
+        mp.D = D;
+        mp.scale_log2e = scale_log2e;
+        rc = ppd::launch_merge(mp, stream);
+        if (rc != 0) return hip_fail(ctx, (hipError_t)rc, "launch merge");
+    }
+    return PPD_OK;
+}
+
 }  // namespace
 
 extern "C" {
 
-const char* ppd_version(void) { return "0.1"; }
+const char* ppd_version(void) { return "0.2"; }
 
 const char* ppd_last_error(const ppd_ctx* ctx) { return ctx ? ctx->error.c_str() : g_create_error.c_str(); }
 
@@ -112,7 +396,8 @@ ppd_status ppd_create(const ppd_shape* shape, int32_t device, ppd_ctx** out) {
         (void)hipGetLastError();
         return fail(nullptr, PPD_ERR_HIP, "no HIP device available: this library has no CPU path");
     }
-    if (device < 0 || device >= count) return fail(nullptr, PPD_ERR_RANGE, "device index out of range");
+    if (device < 0 || device >= count || device >= kMaxDevices)
+        return fail(nullptr, PPD_ERR_RANGE, "device index out of range");
     ppd_ctx* ctx = new ppd_ctx();
     ctx->shape = *shape;
     ctx->device = device;
@@ -137,6 +422,20 @@ ppd_status ppd_create(const ppd_shape* shape, int32_t device, ppd_ctx** out) {
     if ((e = hipMemset(ctx->d_counters, 0, counter_bytes)) != hipSuccess) return bail(e, "hipMemset(counters)");
     for (auto& s : ctx->staging)
         if ((e = hipEventCreateWithFlags(&s.done, hipEventDisableTiming)) != hipSuccess) return bail(e, "hipEventCreate");
+    // the stream kernel of the co-resident pair runs on a stream of the context's own (default priority)
+    if ((e = hipStreamCreateWithFlags(&ctx->side_stream, hipStreamNonBlocking)) != hipSuccess) return bail(e, "hipStreamCreate");
+    if ((e = hipEventCreateWithFlags(&ctx->ev_fork, hipEventDisableTiming)) != hipSuccess) return bail(e, "hipEventCreate");
+    if ((e = hipEventCreateWithFlags(&ctx->ev_join, hipEventDisableTiming)) != hipSuccess) return bail(e, "hipEventCreate");
+    // everything ppd_mixed_attention_static needs is set up here, so that the call itself allocates nothing: the
+    // device address of this GPU's scratch array and a pinned staging buffer for the plan upload
+    {
+        unsigned char* sp = nullptr;
+        if ((e = static_scratch_address(device, &sp)) != hipSuccess) return bail(e, "hipGetSymbolAddress(scratch)");
+    }
+    if ((e = hipHostMalloc(&ctx->static_staging, kStaticPlanBytes, hipHostMallocDefault)) != hipSuccess)
+        return bail(e, "hipHostMalloc(static staging)");
+    if ((e = hipEventCreateWithFlags(&ctx->static_staging_done, hipEventDisableTiming)) != hipSuccess)
+        return bail(e, "hipEventCreate");
     *out = ctx;
     return PPD_OK;
 }
@@ -155,6 +454,16 @@ ppd_status ppd_destroy(ppd_ctx* ctx) {
     for (auto& p : ctx->ev_pairs) {
         if (p.first) (void)hipEventDestroy(p.first);
         if (p.second) (void)hipEventDestroy(p.second);
+    }
+    if (ctx->side_stream) (void)hipStreamDestroy(ctx->side_stream);
+    if (ctx->ev_fork) (void)hipEventDestroy(ctx->ev_fork);
+    if (ctx->ev_join) (void)hipEventDestroy(ctx->ev_join);
+    if (ctx->static_staging) (void)hipHostFree(ctx->static_staging);
+    if (ctx->static_staging_done) (void)hipEventDestroy(ctx->static_staging_done);
+    {
+        std::lock_guard<std::mutex> lock(g_scratch_mutex);
+        if (ctx->device >= 0 && ctx->device < kMaxDevices && g_scratch_owner[ctx->device] == ctx)
+            g_scratch_owner[ctx->device] = nullptr;
     }
     delete ctx;
     return PPD_OK;
@@ -180,6 +489,9 @@ ppd_status ppd_set_option(ppd_ctx* ctx, const char* key, int64_t value) {
     } else if (k == "narrow_cus") {
         if (value < -1 || value > 32) return fail(ctx, PPD_ERR_RANGE, "narrow_cus must be in [-1, 32]");
         ctx->opts.narrow_cus = (int32_t)value;
+    } else if (k == "launch_mode") {
+        if (value < 0 || value > 2) return fail(ctx, PPD_ERR_RANGE, "launch_mode must be in [0, 2]");
+        ctx->launch_mode = (int)value;
     } else if (k == "timing") {
         ctx->timing = value != 0;
         ctx->ev_used = 0;
@@ -238,153 +550,7 @@ double ppd_transfer_delay_s(int64_t n_tokens, int64_t kv_bytes_per_token, double
 ppd_status ppd_mixed_attention(ppd_ctx* ctx, const void* q, const void* kv_pages, const int32_t* page_tables,
                                int32_t max_pages, const int32_t* L, const int32_t* n, int32_t B, float scale,
                                void* out, void* stream) {
-    if (!ctx) return PPD_ERR_NULL;
-    if (B < 0) return fail(ctx, PPD_ERR_RANGE, "B < 0");
-    if (B == 0) {
-        ctx->plan.items.clear();
-        ctx->plan.groups.clear();
-        ctx->plan.units.clear();
-        ctx->plan_on_device = false;
-        std::memset(&ctx->plan.stats, 0, sizeof ctx->plan.stats);
-        return PPD_OK;
-    }
-    if (!q || !kv_pages || !page_tables || !L || !n || !out)
-        return fail(ctx, PPD_ERR_NULL, "q / kv_pages / page_tables / L / n / out is NULL");
-    if (!(scale >= 0.f) || !std::isfinite(scale)) return fail(ctx, PPD_ERR_RANGE, "scale must be finite and >= 0");
-    if (!aligned16(q) || !aligned16(out) || !aligned16(kv_pages) || (reinterpret_cast<uintptr_t>(page_tables) & 3u))
-        return fail(ctx, PPD_ERR_RANGE, "q / out / kv_pages must be 16-byte aligned, page_tables 4-byte aligned");
-    const char* msg = "";
-    ppd_status st = PPD_OK;
-    const bool same_opts = std::memcmp(&ctx->plan_opts, &ctx->opts, sizeof(ppd::PlanOptions)) == 0;
-    const bool reuse = ctx->plan_on_device && same_opts && (int32_t)ctx->plan_L.size() == B &&
-                       std::memcmp(ctx->plan_L.data(), L, sizeof(int32_t) * B) == 0 &&
-                       std::memcmp(ctx->plan_n.data(), n, sizeof(int32_t) * B) == 0;
-    const auto t_plan0 = std::chrono::steady_clock::now();
-    if (!reuse) {
-        ctx->plan_on_device = false;
-        st = ppd::build_plan(ctx->shape, L, n, B, ctx->opts, &ctx->plan, &msg);
-        if (st != PPD_OK) return fail(ctx, st, msg);
-    }
-    for (int i = 0; i < B; ++i) {
-        const int64_t need = ((int64_t)L[i] + n[i] + ppd::kPage - 1) / ppd::kPage;
-        if (need > max_pages)
-            return fail(ctx, PPD_ERR_PAGETABLE, "sequence " + std::to_string(i) + " needs " + std::to_string(need) +
-                                                    " pages, max_pages is " + std::to_string(max_pages));
-    }
-    hipStream_t hs = static_cast<hipStream_t>(stream);
-    PPD_HIP(ctx, hipSetDevice(ctx->device));
-
-    const ppd::Plan& plan = ctx->plan;
-    const size_t items_bytes = plan.items.size() * sizeof(ppd_work_item);
-    const size_t groups_bytes = plan.groups.size() * sizeof(ppd::MergeGroup);
-    const size_t units_bytes = plan.units.size() * sizeof(ppd::MergeUnit);
-    const size_t total = items_bytes + groups_bytes + units_bytes;
-    if (!reuse) {
-        // upload: [items][groups][units] through one pinned staging slot
-        Staging& sg = ctx->staging[ctx->next_slot];
-        ctx->next_slot = (ctx->next_slot + 1) % kStagingSlots;
-        if (sg.in_flight) {
-            PPD_HIP(ctx, hipEventSynchronize(sg.done));
-            sg.in_flight = false;
-        }
-        if (sg.bytes < total) {
-            if (sg.host) PPD_HIP(ctx, hipHostFree(sg.host));
-            sg.host = nullptr;
-            sg.bytes = 0;
-            const size_t want = total + total / 4 + 4096;
-            if (hipHostMalloc(&sg.host, want, hipHostMallocDefault) != hipSuccess) {
-                (void)hipGetLastError();
-                sg.host = nullptr;
-                return fail(ctx, PPD_ERR_WORKSPACE, "pinned staging allocation failed");
-            }
-            sg.bytes = want;
-        }
-        st = grow_device(ctx, &ctx->d_items, &ctx->d_items_bytes, total, hs);
-        if (st != PPD_OK) return st;
-        {
-            void* p = ctx->d_partials;
-            size_t have = ctx->d_partials_floats * sizeof(float);
-            st = grow_device(ctx, &p, &have, (size_t)plan.stats.partial_floats * sizeof(float), hs);
-            ctx->d_partials = static_cast<float*>(p);
-            ctx->d_partials_floats = have / sizeof(float);
-            if (st != PPD_OK) return st;
-        }
-        std::memcpy(sg.host, plan.items.data(), items_bytes);
-        if (groups_bytes) {
-            std::memcpy(static_cast<char*>(sg.host) + items_bytes, plan.groups.data(), groups_bytes);
-            std::memcpy(static_cast<char*>(sg.host) + items_bytes + groups_bytes, plan.units.data(), units_bytes);
-        }
-        PPD_HIP(ctx, hipMemcpyAsync(ctx->d_items, sg.host, total, hipMemcpyHostToDevice, hs));
-        PPD_HIP(ctx, hipEventRecord(sg.done, hs));
-        sg.in_flight = true;
-        ctx->plan_L.assign(L, L + B);
-        ctx->plan_n.assign(n, n + B);
-        ctx->plan_opts = ctx->opts;
-        ctx->plan_on_device = true;
-        ctx->plan.stats.plan_host_us = (int32_t)std::chrono::duration_cast<std::chrono::microseconds>(
-                                           std::chrono::steady_clock::now() - t_plan0).count();
-    }
-
-    const int G = ctx->shape.num_q_heads / ctx->shape.num_kv_heads;
-    // Masked scores are -inf and enter the exponent as s*c: keep c strictly positive so that scale = 0 gives
-    // 2^(-inf) = 0 for masked keys and 2^(~0) = 1 for visible ones (identical to the exact result in fp32).
-    float scale_log2e = scale * 1.4426950408889634f;
-    if (scale_log2e < 1e-30f) scale_log2e = 1e-30f;
-    ppd::KParams kp;
-    kp.q = static_cast<const uint16_t*>(q);
-    kp.out = static_cast<uint16_t*>(out);
-    kp.pool = static_cast<const uint16_t*>(kv_pages);
-    kp.page_tables = page_tables;
-    kp.items = static_cast<const ppd_work_item*>(ctx->d_items);
-    kp.partials = ctx->d_partials;
-    kp.counters = ctx->d_counters;
-    kp.num_pages = ctx->shape.num_pages;
-    kp.page_stride = 2LL * ctx->shape.num_kv_heads * ppd::kPage * ctx->shape.head_dim;
-    kp.n_items = (int32_t)plan.items.size();
-    std::memcpy(kp.queue_begin, plan.queue_begin, sizeof kp.queue_begin);
-    kp.pref_mode = ctx->opts.pref_mode;
-    kp.narrow_cus = plan.narrow_cus;
-    kp.max_pages = max_pages;
-    kp.Hq = ctx->shape.num_q_heads;
-    kp.Hkv = ctx->shape.num_kv_heads;
-    kp.G = G;
-    kp.invG = 65536 / G + 1;
-    kp.scale_log2e = scale_log2e;
-    const bool timed = ctx->timing && ctx->ev_used < kMaxTimedLaunches;
-    if (timed) {
-        if (ctx->ev_used == ctx->ev_pairs.size()) {
-            std::pair<hipEvent_t, hipEvent_t> p{nullptr, nullptr};
-            PPD_HIP(ctx, hipEventCreate(&p.first));
-            ctx->ev_pairs.push_back(p);  // owned by the context from here on, also if the second create fails
-            PPD_HIP(ctx, hipEventCreate(&ctx->ev_pairs.back().second));
-        }
-        if (!ctx->ev_pairs[ctx->ev_used].second) PPD_HIP(ctx, hipEventCreate(&ctx->ev_pairs[ctx->ev_used].second));
-        PPD_HIP(ctx, hipEventRecord(ctx->ev_pairs[ctx->ev_used].first, hs));
-    }
-    int rc = ppd::launch_mixed(kp, ctx->shape.head_dim, plan.stats.grid, stream);
-    if (rc != 0) return hip_fail(ctx, (hipError_t)rc, "launch mixed attention");
-    if (timed) {
-        PPD_HIP(ctx, hipEventRecord(ctx->ev_pairs[ctx->ev_used].second, hs));
-        ctx->ev_used += 1;
-    }
-    if (!plan.groups.empty()) {
-        ppd::MergeParams mp;
-        mp.groups = reinterpret_cast<const ppd::MergeGroup*>(static_cast<const char*>(ctx->d_items) + items_bytes);
-        mp.partials = ctx->d_partials;
-        mp.out = static_cast<uint16_t*>(out);
-        mp.n_groups = (int32_t)plan.groups.size();
-        mp.units = reinterpret_cast<const ppd::MergeUnit*>(static_cast<const char*>(ctx->d_items) + items_bytes +
-                                                          groups_bytes);
-        mp.n_units = (int32_t)plan.units.size();
-        mp.Hq = kp.Hq;
-        mp.G = G;
-        mp.invG = kp.invG;
-        mp.D = ctx->shape.head_dim;
-        mp.scale_log2e = scale_log2e;
-        rc = ppd::launch_merge(mp, stream);
-        if (rc != 0) return hip_fail(ctx, (hipError_t)rc, "launch merge");
-    }
-    return PPD_OK;
+    return mixed_attention_impl(ctx, q, kv_pages, page_tables, max_pages, L, n, B, scale, out, stream, false);
 }
 
 ppd_status ppd_get_plan_stats(const ppd_ctx* ctx, ppd_plan_stats* stats) {
@@ -421,25 +587,20 @@ ppd_status ppd_timed_kernels_ms(ppd_ctx* ctx, double* total_ms, int32_t* launche
     return PPD_OK;
 }
 
-ppd_status ppd_debug_counters(ppd_ctx* ctx, void* stream, uint32_t* out64, int32_t clear) {
-    if (!ctx || !out64) return fail(ctx, PPD_ERR_NULL, "ctx / out64 is NULL");
-    hipStream_t hs = static_cast<hipStream_t>(stream);
-    PPD_HIP(ctx, hipSetDevice(ctx->device));
-    PPD_HIP(ctx, hipStreamSynchronize(hs));
-    PPD_HIP(ctx, hipMemcpy(out64, ctx->d_counters, 256, hipMemcpyDeviceToHost));
-    if (clear) PPD_HIP(ctx, hipMemset(ctx->d_counters + 16, 0, 192));
-    return PPD_OK;
-}
-
 ppd_status ppd_device_error_flags(ppd_ctx* ctx, void* stream, uint32_t* flags) {
     if (!ctx || !flags) return fail(ctx, PPD_ERR_NULL, "ctx / flags is NULL");
     hipStream_t hs = static_cast<hipStream_t>(stream);
     PPD_HIP(ctx, hipSetDevice(ctx->device));
     PPD_HIP(ctx, hipStreamSynchronize(hs));
-    uint32_t v = 0;
+    uint32_t v = 0, vs = 0;
     PPD_HIP(ctx, hipMemcpy(&v, ctx->d_counters + 9, sizeof v, hipMemcpyDeviceToHost));
     PPD_HIP(ctx, hipMemset(ctx->d_counters + 9, 0, sizeof v));
-    *flags = v;
+    // calls of ppd_mixed_attention_static raise their flags in the static array of this GPU
+    unsigned char* sp = nullptr;
+    PPD_HIP(ctx, static_scratch_address(ctx->device, &sp));
+    PPD_HIP(ctx, hipMemcpy(&vs, reinterpret_cast<uint32_t*>(sp) + 9, sizeof vs, hipMemcpyDeviceToHost));
+    if (vs) PPD_HIP(ctx, hipMemset(reinterpret_cast<uint32_t*>(sp) + 9, 0, sizeof vs));
+    *flags = v | vs;
     return PPD_OK;
 }
 

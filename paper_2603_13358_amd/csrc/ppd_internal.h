@@ -24,14 +24,28 @@ constexpr int kStages = PPD_STAGES;          // prefetch distance of the K tiles
 constexpr int kWgPerCu = kWaves == 8 ? 1 : 2;  // resident workgroups per compute unit (256 VGPRs per wave)
 constexpr int kTileTokens = 64;      // key tile of the MFMA path; every split boundary is a multiple of it
 constexpr int kMaxMfmaChunk = 32768;  // keys per MFMA row-block tile at most (its 2048 page ids are staged in LDS)
-constexpr int kSmallThreads = 256;
-// Device counters of a context: 64 words of flags and diagnostics, then the nine queue cursors, each in a
+constexpr int kSmallThreads = 256;   // block size of the append and merge kernels
+// The co-resident pair (a step with both kinds of tiles): the stream kernel's workgroup is kStreamWaves waves, one
+// per SIMD, each with kStreamKSets rotating register sets for the K half of a page and kStreamVSets for the V half
+// (K of kStreamKSets - 1 pages and V of kStreamVSets - 1 pages in flight per wave: what 168 registers hold).
+constexpr int kStreamWaves = 4;
+constexpr int kStreamThreads = 64 * kStreamWaves;
+#ifndef PPD_STREAM_KSETS
+#define PPD_STREAM_KSETS 3
+#endif
+#ifndef PPD_STREAM_VSETS
+#define PPD_STREAM_VSETS 2
+#endif
+constexpr int kStreamKSets = PPD_STREAM_KSETS;
+constexpr int kStreamVSets = PPD_STREAM_VSETS;
+// Device counters of a context: 64 words of flags (word 9: sticky error flags; words 10 and 11: finished
+// workgroups of the mixed / row-block kernel and of the stream kernel), then the nine queue cursors, each in a
 // 128-byte line of its own (claims on different queues then do not queue up behind one another at one address
 // range of the memory side, where device-scope atomics execute).
 constexpr int kCursorBase = 64;    // word index of cursor 0
 constexpr int kCursorStride = 32;  // words between cursors
 constexpr int kCounterWords = kCursorBase + 9 * kCursorStride;
-constexpr int kMergeCols = 16;    // columns of a merge group one block of the merge kernel takes   // block size of the append and merge kernels
+constexpr int kMergeCols = 16;     // columns of a merge group one block of the merge kernel takes
 
 // One merge group: a row block whose key range was split over `nsplit` tiles with consecutive partials.
 struct MergeGroup {
@@ -43,7 +57,7 @@ struct MergeGroup {
     int64_t part_stride;  // floats per split = cols * (D + 2)
 };
 
-// One workgroup of the merge kernel: 4 consecutive columns of a group (one wave each).
+// One workgroup of the merge kernel: kMergeCols consecutive columns of a group (a quarter of them per wave).
 struct MergeUnit {
     int32_t group;
     int32_t col0;
@@ -84,7 +98,7 @@ struct KParams {
     const int32_t* page_tables;
     const ppd_work_item* items;
     float* partials;
-    uint32_t* counters;   // [9] sticky error flags, [10] finished workgroups, [16..63] timing; queue cursors behind
+    uint32_t* counters;   // [9] sticky error flags, [10], [11] finished workgroups; queue cursors from kCursorBase on
     int32_t queue_begin[kXcds + 2];
     int64_t num_pages;
     int64_t page_stride;  // elements per page = 2 * Hkv * 16 * D
@@ -110,6 +124,8 @@ struct MergeParams {
 // Launchers (defined in ppd_kernels.hip); stream is a hipStream_t.
 int prepare_mixed_kernels();
 int launch_mixed(const KParams& p, int head_dim, int grid, void* stream);
+int launch_mfma_only(const KParams& p, int head_dim, int grid, void* stream);    // row-block tiles of queues 0..7
+int launch_stream_only(const KParams& p, int head_dim, int grid, void* stream);  // narrow tiles of queue 8
 int launch_merge(const MergeParams& p, void* stream);
 int launch_kv_append(const uint16_t* k, const uint16_t* v, uint16_t* pool, const int64_t* slots, int64_t T,
                      int Hkv, int D, int64_t num_pages, int layers, int64_t pool_layer_stride, uint32_t* err_flags,

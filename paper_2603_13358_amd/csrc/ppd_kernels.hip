@@ -28,58 +28,6 @@ typedef short s16x4 __attribute__((ext_vector_type(4)));
 
 #define NEG_INF (-__builtin_inff())
 
-// Optional phase timing of the MFMA tile loop (build with -DPPD_PHASE_TIMING): shader-clock cycles of wave 0
-// of every workgroup, summed per phase into counters[16..27] as six 64-bit sums.  Off in the product build.
-#ifdef PPD_PHASE_TIMING
-#ifndef PPD_TICK_WAVE
-#define PPD_TICK_WAVE 0  // the wave whose loop phases are timed
-#endif
-#define PPD_TICK_DECL() long long tick_last_ = clock64(); long long tick_sum_[6] = {0, 0, 0, 0, 0, 0}
-#define PPD_TICK(k)                              \
-    do {                                         \
-        const long long now_ = clock64();        \
-        tick_sum_[k] += now_ - tick_last_;       \
-        tick_last_ = now_;                       \
-    } while (0)
-#define PPD_TICK_FLUSH(P)                                                                                  \
-    do {                                                                                                   \
-        if (threadIdx.x == PPD_TICK_WAVE * 64)                                                             \
-            for (int k_ = 0; k_ < 6; ++k_)                                                                 \
-                atomicAdd(reinterpret_cast<unsigned long long*>((P).counters + 16) + k_, (unsigned long long)tick_sum_[k_]); \
-    } while (0)
-// Start and end of every workgroup on the chip-wide 100 MHz clock: sums 12..15 = max of (2^62 - start), max of
-// end, sum of starts, sum of ends.
-#define PPD_WG_SPAN_BEGIN() const long long wg_t0_ = wall_clock64()
-#define PPD_WG_SPAN_END(P)                                                                          \
-    do {                                                                                            \
-        if (threadIdx.x == 0) {                                                                     \
-            const long long t1_ = wall_clock64();                                                   \
-            unsigned long long* c_ = reinterpret_cast<unsigned long long*>((P).counters + 16);     \
-            atomicMax(c_ + 12, (unsigned long long)((1LL << 62) - wg_t0_));                         \
-            atomicMax(c_ + 13, (unsigned long long)t1_);                                            \
-            atomicAdd(c_ + 14, (unsigned long long)wg_t0_);                                         \
-            atomicAdd(c_ + 15, (unsigned long long)t1_);                                            \
-        }                                                                                           \
-    } while (0)
-#else
-#define PPD_WG_SPAN_BEGIN() do {} while (0)
-#define PPD_WG_SPAN_END(P) do {} while (0)
-#define PPD_TICK_DECL() do {} while (0)
-#define PPD_TICK(k) do {} while (0)
-#define PPD_TICK_FLUSH(P) do {} while (0)
-#endif
-
-// Optional marks along the life of workgroup 0 (build with -DPPD_TILE_MARKS): the chip-wide 100 MHz clock at up
-// to 16 points, thread 0, into counters[48..63] (the last value written at a point wins).  Off in the product build.
-#ifdef PPD_TILE_MARKS
-#define PPD_MARK(P, k)                                                                     \
-    do {                                                                                   \
-        if (blockIdx.x == 0 && threadIdx.x == 0) (P).counters[48 + (k)] = (uint32_t)wall_clock64(); \
-    } while (0)
-#else
-#define PPD_MARK(P, k) do {} while (0)
-#endif
-
 __device__ __forceinline__ uint32_t pack_bf16(float a, float b) {
     f32x2 f = {a, b};
     bf16x2 r = __builtin_convertvector(f, bf16x2);  // round to nearest even
@@ -170,7 +118,12 @@ __device__ __forceinline__ void lds_direct_load16(const void* gbase, uint32_t la
                  : "memory", "m0");
 }
 
-template <int HD>
+// HALF = false: the vector phase covers the 64 keys of a tile, then the matrix phase (the loop described above).
+// HALF = true: the same tile is worked in two halves of 32 keys -- vector phase, matrix phase, vector phase, matrix
+// phase -- with S^T of 32 keys and half of the packed probabilities live at a time: 24 registers less per lane,
+// which is what lets two such waves and a stream wave share a SIMD (three waves of 168 registers).  The late waves
+// then take the loop barrier between the second vector phase and the second matrix phase.
+template <int HD, bool HALF>
 __device__ __forceinline__ void mfma_item(const KParams& P, const ppd_work_item& it, char* smem) {
     constexpr int PB = kPage * HD * 2;         // bytes of one (page, head) block of K or of V
     constexpr int GPP = PB / 16;               // 16-byte granules per block
@@ -303,19 +256,13 @@ __device__ __forceinline__ void mfma_item(const KParams& P, const ppd_work_item&
         for (int ks = 0; ks < KS; ++ks)
 #pragma unroll
             for (int tb = 0; tb < 2; ++tb) {
-#ifdef PPD_DIAG_NO_LDS_OPERANDS  // timing diagnostics only: wrong results
-                bf16x8 a = qreg[(ks + tb) % KS];
-#else
                 bf16x8 a = as_bf16x8(*reinterpret_cast<const u32x4*>(kb + tb * 2 * PB + ks * 512));
-#endif
                 sacc[tb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, qreg[ks], sacc[tb], 0, 0, 0);
             }
     };
 
     // prologue: K(0..NS-1) and V(0..NS-2) are issued, K(0), K(1), V(0) must land; S^T of tile 0
-    PPD_MARK(P, 2);
     __syncthreads();  // page ids are in LDS
-    PPD_MARK(P, 3);
     {
 #pragma unroll
         for (int t = 0; t < NS; ++t) {
@@ -327,7 +274,6 @@ __device__ __forceinline__ void mfma_item(const KParams& P, const ppd_work_item&
         }
     }
     wait_all_loads();
-    PPD_MARK(P, 4);
     // The compiler does not count the asm loads; make it settle its own pending loads (the Q operand) here, or
     // it would place ever-decreasing memory-counter waits at their first use inside the loop and drain the
     // LDS-direct loads in flight there.
@@ -337,10 +283,10 @@ __device__ __forceinline__ void mfma_item(const KParams& P, const ppd_work_item&
     for (int t = 0; t < NS - 1; ++t)
         if (t < ntiles) fix_v_tail(t, VRING + t * KBYTES);
     lds_barrier();
+    if constexpr (!HALF) {
     f32x16 s_cur[2];
     if (wave_active) qk_tile(0, s_cur);
     lds_barrier();  // with rings of NS stages the first iteration's loads overwrite K stage 0
-    PPD_MARK(P, 5);
     int st_cur = 0;   // ti % NS
     int sv_cur = 0;   // ti % NSV: V stage of tile ti
     // Two waves share a SIMD, and a wave issues in order.  An iteration is a vector phase (mask, max, rescale, the
@@ -358,49 +304,33 @@ __device__ __forceinline__ void mfma_item(const KParams& P, const ppd_work_item&
 #endif
 
     u32x4 pw[4];  // the tile's probabilities as bf16, B operand of the four 16-key steps of the PV product
-#ifdef PPD_DIAG_NO_VECTOR_PHASE
-#pragma unroll
-    for (int s = 0; s < 4; ++s) pw[s] = __builtin_bit_cast(u32x4, qreg[s]);  // defined, so the PV MFMAs stay
-#endif
     TilePages tp_v = tile_pages(NS - 1 < ntiles ? NS - 1 : ntiles - 1);  // pages of the loads the first iteration issues
     TilePages tp_k = tile_pages(NS < ntiles ? NS : ntiles - 1);
-    PPD_TICK_DECL();
     for (int ti = 0; ti < ntiles; ++ti) {
         const int st_nxt = st_cur + 1 == NSK ? 0 : st_cur + 1;           // (ti + 1) % NSK
         const int st_far = (st_cur + NS) % NSK;                           // (ti + NS) % NSK
         const int sv_nxt = sv_cur + 1 == NSV ? 0 : sv_cur + 1;           // (ti + 1) % NSV
         const int sv_far = (sv_cur + NS - 1) % NSV;                       // (ti + NS - 1) % NSV
         const bool full_issue = ti + NS < ntiles;
-#ifndef PPD_DIAG_NO_LOOP_LOADS  // timing diagnostics only: the tiles after the first NS read stale LDS
         if (ti + NS - 1 < ntiles) load_block(tp_v, VRING + sv_far * KBYTES, v_off);
         if (full_issue) load_block(tp_k, st_far * KBYTES, 0);
-#endif
         // The V tile of the next iteration is this iteration's K tile; the ids of its K tile are read from LDS
         // now and turned into scalars at the end of the iteration: under the other waves' operand reads that
         // small LDS read takes hundreds of cycles, which nothing waits for this way.
         tp_v = tp_k;
         const RawPages tp_raw = tile_pages_raw(ti + 1 + NS < ntiles ? ti + 1 + NS : ntiles - 1);
-        PPD_TICK(0);
         // K(ti+2) and V(ti+1) must have landed before the barrier; with NS = 3 the loads issued in this iteration
         // may stay in flight
         auto close_iteration = [&]() {
-#ifndef PPD_DIAG_NO_LOAD_WAIT  // timing diagnostics only: tiles may be read before they have landed (values only)
             if (full_issue)  // then the last NS - 2 iterations all issued their full share
                 wait_older_loads();
             else
                 wait_all_loads();
-#endif
             if (ti + 1 < ntiles) fix_v_tail(ti + 1, VRING + sv_nxt * KBYTES);
-#ifndef PPD_DIAG_NO_LOOP_BARRIER  // timing diagnostics only: the waves then race on the K/V tiles' contents (values
-            lds_barrier();        // only: every address comes from the page ids staged and checked before the loop)
-#endif
+            lds_barrier();
         };
         float mc = 0.f;
-#ifdef PPD_DIAG_NO_VECTOR_PHASE  // timing diagnostics only: no softmax at all, wrong results
-        if (false) {
-#else
         if (wave_active) {
-#endif
             const int tile_base = it.kv_begin + ti * kTileTokens;
             if (tile_base + kTileTokens - 1 > wmin_limit) {  // causal boundary crosses this tile
 #pragma unroll
@@ -429,7 +359,6 @@ __device__ __forceinline__ void mfma_item(const KParams& P, const ppd_work_item&
                 m_run = m_new;
             }
             mc = m_run == NEG_INF ? 0.f : m_run * c;
-            PPD_TICK(1);
             // Vector phase: all exponentials of this tile, packed to bf16 at once.  Nothing for the matrix pipe in
             // it, and nothing for the vector pipe in the matrix phase below, so that the late waves (half an
             // iteration behind) run their matrix phase under this vector phase and the other way round.
@@ -439,22 +368,15 @@ __device__ __forceinline__ void mfma_item(const KParams& P, const ppd_work_item&
 #pragma unroll
                 for (int e = 0; e < 4; ++e) {
                     const int i0 = (s & 1) * 8 + 2 * e;
-#ifdef PPD_DIAG_NO_EXP  // timing diagnostics only: wrong results
-                    const float p0 = __builtin_fmaf(s_cur[s >> 1][i0], c, -mc);
-                    const float p1 = __builtin_fmaf(s_cur[s >> 1][i0 + 1], c, -mc);
-#else
                     const float p0 = fast_exp2(__builtin_fmaf(s_cur[s >> 1][i0], c, -mc));
                     const float p1 = fast_exp2(__builtin_fmaf(s_cur[s >> 1][i0 + 1], c, -mc));
-#endif
                     psum += p0 + p1;
                     pw[s][e] = pack_bf16(p0, p1);
                 }
             l_run += psum;
-            PPD_TICK(2);
         }
         __builtin_amdgcn_sched_barrier(0);
         if (late) close_iteration();
-        PPD_TICK(4);
         if (wave_active) {
             // Matrix phase: O^T += V^T P^T of this tile, then S^T of the next one into the registers the
             // probabilities have left.
@@ -469,21 +391,125 @@ __device__ __forceinline__ void mfma_item(const KParams& P, const ppd_work_item&
                 }
             }
             if (ti + 1 < ntiles) qk_tile(st_nxt, s_cur);
-#ifdef PPD_DIAG_NO_VECTOR_PHASE
-            asm volatile("" ::"v"(s_cur[0]), "v"(s_cur[1]));  // nobody reads S^T in this build: keep its MFMAs
-#endif
         }
         __builtin_amdgcn_sched_barrier(0);
-        PPD_TICK(3);
         if (!late) close_iteration();
         tp_k = to_scalar(tp_raw);
         st_cur = st_nxt;
         sv_cur = sv_nxt;
-        PPD_TICK(5);
     }
-    PPD_TICK_FLUSH(P);
-    PPD_MARK(P, 6);
 
+    } else {
+    // S^T of 32 keys: the tb-th pair of pages of a K stage
+    auto qk_half = [&](int stage, int tb, f32x16& sacc) {
+        const char* kb = smem + stage * KBYTES + k_lane_off + tb * 2 * PB;
+#pragma unroll
+        for (int i = 0; i < 16; ++i) sacc[i] = 0.f;
+#pragma unroll
+        for (int ks = 0; ks < KS; ++ks) {
+            bf16x8 a = as_bf16x8(*reinterpret_cast<const u32x4*>(kb + ks * 512));
+            sacc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, qreg[ks], sacc, 0, 0, 0);
+        }
+    };
+    f32x16 s_half;
+    if (wave_active) qk_half(0, 0, s_half);
+    lds_barrier();  // with rings of NS stages the first iteration's loads overwrite K stage 0
+    int st_cur = 0;   // ti % NSK
+    int sv_cur = 0;   // ti % NSV: V stage of tile ti
+#if PPD_PINGPONG
+    const bool late = wave >= kWaves / 2;  // waves w and w + 4 share a SIMD
+#else
+    const bool late = false;
+#endif
+    TilePages tp_v = tile_pages(NS - 1 < ntiles ? NS - 1 : ntiles - 1);  // pages of the loads the first iteration issues
+    TilePages tp_k = tile_pages(NS < ntiles ? NS : ntiles - 1);
+    for (int ti = 0; ti < ntiles; ++ti) {
+        const int st_nxt = st_cur + 1 == NSK ? 0 : st_cur + 1;           // (ti + 1) % NSK
+        const int st_far = (st_cur + NS) % NSK;                           // (ti + NS) % NSK
+        const int sv_nxt = sv_cur + 1 == NSV ? 0 : sv_cur + 1;           // (ti + 1) % NSV
+        const int sv_far = (sv_cur + NS - 1) % NSV;                       // (ti + NS - 1) % NSV
+        const bool full_issue = ti + NS < ntiles;
+        if (ti + NS - 1 < ntiles) load_block(tp_v, VRING + sv_far * KBYTES, v_off);
+        if (full_issue) load_block(tp_k, st_far * KBYTES, 0);
+        tp_v = tp_k;
+        const RawPages tp_raw = tile_pages_raw(ti + 1 + NS < ntiles ? ti + 1 + NS : ntiles - 1);
+        auto close_iteration = [&]() {
+            if (full_issue)  // then the last NS - 2 iterations all issued their full share
+                wait_older_loads();
+            else
+                wait_all_loads();
+            if (ti + 1 < ntiles) fix_v_tail(ti + 1, VRING + sv_nxt * KBYTES);
+            lds_barrier();
+        };
+#pragma unroll
+        for (int hb = 0; hb < 2; ++hb) {
+            u32x4 pw[2];  // the half's probabilities as bf16, B operand of its two 16-key steps of the PV product
+            if (wave_active) {
+                const int half_base = it.kv_begin + ti * kTileTokens + hb * 32;
+                if (half_base + 31 > wmin_limit) {  // causal boundary crosses this half
+#pragma unroll
+                    for (int i = 0; i < 16; ++i) {
+                        const int pos = half_base + (i >> 3) * 16 + h * 8 + (i & 7);
+                        if (pos > limit) s_half[i] = NEG_INF;
+                    }
+                }
+                float mx = s_half[0];
+#pragma unroll
+                for (int i = 1; i < 16; ++i) mx = fmaxf(mx, s_half[i]);
+                mx = max_halves(mx);
+                const float m_new = fmaxf(m_run, mx);
+                if (__any((m_new - m_run) * c > kLazyRescale)) {  // -inf -> finite counts; -inf -> -inf does not
+                    const float m_use = m_new == NEG_INF ? 0.f : m_new;
+                    const float alpha = fast_exp2(m_run * c - m_use * c);  // m_run = -inf gives 0
+                    l_run *= alpha;
+#pragma unroll
+                    for (int db = 0; db < DB; ++db)
+#pragma unroll
+                        for (int i = 0; i < 16; ++i) oacc[db][i] *= alpha;
+                    m_run = m_new;
+                }
+                const float mc = m_run == NEG_INF ? 0.f : m_run * c;
+                float psum = 0.f;
+#pragma unroll
+                for (int s2 = 0; s2 < 2; ++s2)
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) {
+                        const int i0 = s2 * 8 + 2 * e;
+                        const float p0 = fast_exp2(__builtin_fmaf(s_half[i0], c, -mc));
+                        const float p1 = fast_exp2(__builtin_fmaf(s_half[i0 + 1], c, -mc));
+                        psum += p0 + p1;
+                        pw[s2][e] = pack_bf16(p0, p1);
+                    }
+                l_run += psum;
+            }
+            __builtin_amdgcn_sched_barrier(0);
+            if (hb == 1 && late) close_iteration();
+            if (wave_active) {
+                // O^T += V^T P^T of this half, then S^T of the next half into the registers the probabilities left
+                const char* vb = smem + sv_cur * KBYTES + v_lane_off + hb * 2 * PB;
+#pragma unroll
+                for (int s2 = 0; s2 < 2; ++s2) {
+                    const bf16x8 pb = as_bf16x8(pw[s2]);
+#pragma unroll
+                    for (int db = 0; db < DB; ++db) {
+                        bf16x8 a = as_bf16x8(*reinterpret_cast<const u32x4*>(vb + s2 * PB + db * 512));
+                        oacc[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, pb, oacc[db], 0, 0, 0);
+                    }
+                }
+                if (hb == 0)
+                    qk_half(st_cur, 1, s_half);
+                else if (ti + 1 < ntiles)
+                    qk_half(st_nxt, 0, s_half);
+            }
+            __builtin_amdgcn_sched_barrier(0);
+        }
+        if (!late) close_iteration();
+        tp_k = to_scalar(tp_raw);
+        st_cur = st_nxt;
+        sv_cur = sv_nxt;
+    }
+
+    }
     // epilogue: O^T register i of block db is d = db*32 + (i/4)*8 + h*4 + i%4 of column `col`
     const float l_tot = sum_halves(l_run);
     if (col < ncols) {
@@ -519,16 +545,25 @@ __device__ __forceinline__ void mfma_item(const KParams& P, const ppd_work_item&
 }
 
 // ---------------------------------------------------------------------------------------------------
-// Narrow tile: rows*G <= 16 query columns (decode: 1 row x G heads).  HBM-bound: each of the waves
+// Narrow tile: rows*G <= 16 query columns (decode: 1 row x G heads).  HBM-bound: each of the NW waves
 // streams its own share of the key range straight from the pool into MFMA operand registers
-// (v_mfma_f32_16x16x32_bf16 for S^T, v_mfma_f32_16x16x16_bf16 for O^T; one page per step, three steps
-// prefetched), then the waves' (o, m, l) are combined through LDS.
+// (v_mfma_f32_16x16x32_bf16 for S^T, v_mfma_f32_16x16x16_bf16 for O^T; one page per step; NK register sets for
+// K and NV <= NK for V rotate, so that K of NK - 1 and V of NV - 1 pages per wave are in flight while one page is
+// computed), then the waves' (o, m, l) are combined through LDS, CB columns per pass.
 // ---------------------------------------------------------------------------------------------------
-template <int HD>
+template <int NW>
+struct NarrowCombine {
+    static constexpr int CB = NW >= 8 ? kNarrowCols : 8;  // columns per combine pass
+    static constexpr size_t bytes(int head_dim) { return (size_t)NW * CB * (head_dim + 2) * sizeof(float); }
+};
+
+template <int HD, int NW, int NK, int NV>
 __device__ __forceinline__ void narrow_item(const KParams& P, const ppd_work_item& it, char* smem) {
     constexpr int KS = HD / 32;   // k-steps of S^T
     constexpr int DBN = HD / 16;  // 16-row d blocks of O^T
-    constexpr int WSTRIDE = kNarrowCols * (HD + 2);  // floats per wave in the combine buffer
+    constexpr int CB = NarrowCombine<NW>::CB;
+    constexpr int WSTRIDE = CB * (HD + 2);  // floats per wave in the combine buffer
+    constexpr int NT = NW * 64;
 
     const int tid = threadIdx.x;
     const int lane = tid & 63;
@@ -557,7 +592,7 @@ __device__ __forceinline__ void narrow_item(const KParams& P, const ppd_work_ite
     const int32_t* pt_row = P.page_tables + (int64_t)it.seq * P.max_pages;
     const int last_page = (it.kv_total - 1) >> 4;
     const int nsteps = (it.kv_end - it.kv_begin + kPage - 1) >> 4;  // one page per step
-    const int s_lo = wave * nsteps / kWaves, s_hi = (wave + 1) * nsteps / kWaves;
+    const int s_lo = wave * nsteps / NW, s_hi = (wave + 1) * nsteps / NW;
     const int wave_first_page = (it.kv_begin >> 4) + s_lo;
     const int64_t head_off = (int64_t)it.kvh * (kPage * HD);
     const int64_t v_off = (int64_t)P.Hkv * (kPage * HD);
@@ -568,37 +603,46 @@ __device__ __forceinline__ void narrow_item(const KParams& P, const ppd_work_ite
     float m_run = NEG_INF, l_run = 0.f;
     const float c = P.scale_log2e;
 
-    // lane i of `ids` holds the page of logical page (batch*64 + i) of this wave's range
-    int ids_cur = 0, ids_nxt = 0;
+    // lane i of `ids_*` holds the page of logical page (batch*64 + i) of this wave's range.  K loads run NK - 1 steps
+    // ahead of the computation and drive the rotation of the id batches; V loads run NV - 1 <= NK - 1 steps ahead
+    // and may still be in the batch before (ids_old).
+    int ids_old = 0, ids_cur = 0, ids_nxt = 0, k_batch = 0;
     auto load_ids = [&](int batch) { return load_page_id(pt_row, wave_first_page + batch * 64 + lane, last_page); };
-    struct StepRegs {
-        u32x4 k[KS];    // K operand of the page: 16 tokens x 32 d per k-step
-        u32x2 v[DBN];   // V^T operand: 4 tokens of one d, one per 16-row d block
-    };
-    StepRegs r0, r1, r2, r3;
+    struct KRegs { u32x4 k[KS]; };   // K operand of the page: 16 tokens x 32 d per k-step
+    struct VRegs { u32x2 v[DBN]; };  // V^T operand: 4 tokens of one d, one per 16-row d block
+    KRegs rk[NK];
+    VRegs rv[NV];
     const int my_steps = s_hi - s_lo;
+    const uint32_t k_lane_bytes = (uint32_t)(g4 * 128 + c16 * 8) * 2u;                          // + ks * 1024
+    const uint32_t v_lane_bytes = (uint32_t)(((g4 >> 1) * HD + c16) * 8 + (g4 & 1) * 4) * 2u;  // + db * 256
     // K and V are read once: non-temporal loads (no reuse to keep in the caches) stream ~12 % faster than plain
-    // ones on this pattern.
-    auto issue_step = [&](int k, StepRegs& r) {  // k = step index relative to s_lo
+    // ones on this pattern.  Address = wave-uniform base of the (page, head) block + one 32-bit byte offset per lane.
+    auto issue_k = [&](int k, KRegs& r) {  // k = step index relative to s_lo
         if ((k & 63) == 0 && k > 0) {
+            ids_old = ids_cur;
             ids_cur = ids_nxt;
-            if (k + 64 < my_steps) ids_nxt = load_ids(k / 64 + 1);
+            k_batch = k >> 6;
+            if (k + 64 < my_steps) ids_nxt = load_ids(k_batch + 1);
         }
         const int64_t pa = checked_page(P, __builtin_amdgcn_readlane(ids_cur, k & 63));
-        const uint16_t* ka = P.pool + pa * P.page_stride + head_off;
+        const char* kb = reinterpret_cast<const char*>(P.pool + pa * P.page_stride + head_off);
 #pragma unroll
         for (int ks = 0; ks < KS; ++ks)
-            r.k[ks] = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(ka + (ks * 4 + g4) * 128 + c16 * 8));
-        const int voff = ((g4 >> 1) * HD + c16) * 8 + (g4 & 1) * 4;
+            r.k[ks] = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(kb + k_lane_bytes + ks * 1024));
+    };
+    auto issue_v = [&](int k, VRegs& r) {
+        const int ids = (k >> 6) == k_batch ? ids_cur : ids_old;
+        const int64_t pa = checked_page(P, __builtin_amdgcn_readlane(ids, k & 63));
+        const char* vb = reinterpret_cast<const char*>(P.pool + pa * P.page_stride + head_off + v_off);
 #pragma unroll
         for (int db = 0; db < DBN; ++db)
-            r.v[db] = __builtin_nontemporal_load(reinterpret_cast<const u32x2*>(ka + v_off + voff + db * 128));
+            r.v[db] = __builtin_nontemporal_load(reinterpret_cast<const u32x2*>(vb + v_lane_bytes + db * 256));
     };
-    auto compute_step = [&](int k, StepRegs& r) {
+    auto compute_step = [&](int k, KRegs& rs, VRegs& rw) {
         f32x4 sa = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
         for (int ks = 0; ks < KS; ++ks)
-            sa = __builtin_amdgcn_mfma_f32_16x16x32_bf16(as_bf16x8(r.k[ks]), qreg[ks], sa, 0, 0, 0);
+            sa = __builtin_amdgcn_mfma_f32_16x16x32_bf16(as_bf16x8(rs.k[ks]), qreg[ks], sa, 0, 0, 0);
         // sa[i]: token 4*g4 + i of the page
         const int t0 = it.kv_begin + (s_lo + k) * kPage;
         const bool masked = t0 + kPage - 1 > min_limit || t0 + kPage > it.kv_end;
@@ -614,7 +658,7 @@ __device__ __forceinline__ void narrow_item(const KParams& P, const ppd_work_ite
 #pragma unroll
                     for (int e = 0; e < 4; ++e) {
                         const int pos = t0 + 4 * g4 + e;
-                        if (pos >= it.kv_total) r.v[db][e >> 1] &= (e & 1) ? 0x0000FFFFu : 0xFFFF0000u;
+                        if (pos >= it.kv_total) rw.v[db][e >> 1] &= (e & 1) ? 0x0000FFFFu : 0xFFFF0000u;
                     }
                 }
             }
@@ -640,76 +684,99 @@ __device__ __forceinline__ void narrow_item(const KParams& P, const ppd_work_ite
         const s16x4 pb4 = __builtin_bit_cast(s16x4, pw);
 #pragma unroll
         for (int db = 0; db < DBN; ++db)
-            oacc[db] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(__builtin_bit_cast(s16x4, r.v[db]), pb4, oacc[db], 0, 0, 0);
+            oacc[db] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(__builtin_bit_cast(s16x4, rw.v[db]), pb4, oacc[db], 0, 0, 0);
     };
 
-    // three pages (24 KiB at D = 128) are in flight while one is being computed; the four register sets rotate
+    // K of NK - 1 pages and V of NV - 1 pages (4 KiB each at D = 128) are in flight per wave while one page is being
+    // computed; the register sets rotate (period = NK * NV steps, unrolled)
     if (my_steps > 0) {
         ids_cur = load_ids(0);
         if (my_steps > 64) ids_nxt = load_ids(1);
-        issue_step(0, r0);
-        if (1 < my_steps) issue_step(1, r1);
-        if (2 < my_steps) issue_step(2, r2);
+#pragma unroll
+        for (int j = 0; j < NK - 1; ++j)
+            if (j < my_steps) issue_k(j, rk[j]);
+#pragma unroll
+        for (int j = 0; j < NV - 1; ++j)
+            if (j < my_steps) issue_v(j, rv[j]);
     }
-    for (int k = 0; k < my_steps; k += 4) {
-        if (k + 3 < my_steps) issue_step(k + 3, r3);
-        compute_step(k, r0);
-        if (k + 1 < my_steps) {
-            if (k + 4 < my_steps) issue_step(k + 4, r0);
-            compute_step(k + 1, r1);
-        }
-        if (k + 2 < my_steps) {
-            if (k + 5 < my_steps) issue_step(k + 5, r1);
-            compute_step(k + 2, r2);
-        }
-        if (k + 3 < my_steps) {
-            if (k + 6 < my_steps) issue_step(k + 6, r2);
-            compute_step(k + 3, r3);
+    constexpr int PERIOD = NK == NV ? NK : NK * NV;
+    for (int k = 0; k < my_steps; k += PERIOD) {
+#pragma unroll
+        for (int j = 0; j < PERIOD; ++j) {
+            if (k + j < my_steps) {
+                if (k + j + NK - 1 < my_steps) issue_k(k + j + NK - 1, rk[(j + NK - 1) % NK]);
+                if (k + j + NV - 1 < my_steps) issue_v(k + j + NV - 1, rv[(j + NV - 1) % NV]);
+                compute_step(k + j, rk[j % NK], rv[j % NV]);
+            }
         }
     }
     l_run += xor_shuffle(l_run, 16);
     l_run = sum_halves(l_run);
 
-    // combine the waves: O^T register i of block db is d = db*16 + 4*g4 + i of column c16
+    // combine the waves, CB columns per pass: O^T register i of block db is d = db*16 + 4*g4 + i of column c16
     float* wbuf = reinterpret_cast<float*>(smem) + wave * WSTRIDE;
-#pragma unroll
-    for (int db = 0; db < DBN; ++db)
-        *reinterpret_cast<f32x4*>(wbuf + c16 * HD + db * 16 + 4 * g4) = oacc[db];
-    if (g4 == 0) {
-        wbuf[kNarrowCols * HD + c16 * 2] = m_run;
-        wbuf[kNarrowCols * HD + c16 * 2 + 1] = l_run;
-    }
-    __syncthreads();
     const float* all = reinterpret_cast<const float*>(smem);
-    for (int idx = tid; idx < ncols * HD; idx += kThreads) {
-        const int col = idx / HD, d = idx % HD;
-        float mw[kWaves], mm = NEG_INF;
+    for (int c0 = 0; c0 < ncols; c0 += CB) {
+        if (c0 > 0) __syncthreads();  // the previous pass has been read
+        if (c16 >= c0 && c16 < c0 + CB) {
 #pragma unroll
-        for (int w = 0; w < kWaves; ++w) {
-            mw[w] = all[w * WSTRIDE + kNarrowCols * HD + col * 2];
-            mm = fmaxf(mm, mw[w]);
-        }
-        float o = 0.f, l = 0.f;
-#pragma unroll
-        for (int w = 0; w < kWaves; ++w) {
-            const float f = mw[w] == NEG_INF ? 0.f : fast_exp2((mw[w] - mm) * c);
-            o += f * all[w * WSTRIDE + col * HD + d];
-            l += f * all[w * WSTRIDE + kNarrowCols * HD + col * 2 + 1];
-        }
-        if (it.part_off < 0) {
-            const int crow = col_row(col, P.invG);
-            const int64_t orow = (int64_t)(it.grow0 + crow) * P.Hq + it.kvh * G + (col - crow * G);
-            const float val = o / l;
-            const float other = __shfl_xor(val, 1, 64);  // d and d^1 sit in neighbouring lanes
-            if ((d & 1) == 0) *reinterpret_cast<uint32_t*>(P.out + orow * HD + d) = pack_bf16(val, other);
-        } else {
-            float* pp = P.partials + it.part_off;
-            pp[(int64_t)col * HD + d] = o;
-            if (d == 0) {
-                pp[(int64_t)ncols * HD + col * 2] = mm;
-                pp[(int64_t)ncols * HD + col * 2 + 1] = l;
+            for (int db = 0; db < DBN; ++db)
+                *reinterpret_cast<f32x4*>(wbuf + (c16 - c0) * HD + db * 16 + 4 * g4) = oacc[db];
+            if (g4 == 0) {
+                wbuf[CB * HD + (c16 - c0) * 2] = m_run;
+                wbuf[CB * HD + (c16 - c0) * 2 + 1] = l_run;
             }
         }
+        __syncthreads();
+        const int nc = ncols - c0 < CB ? ncols - c0 : CB;
+        for (int idx = tid; idx < nc * HD; idx += NT) {
+            const int cl = idx / HD, d = idx % HD;
+            const int col = c0 + cl;
+            float mw[NW], mm = NEG_INF;
+#pragma unroll
+            for (int w = 0; w < NW; ++w) {
+                mw[w] = all[w * WSTRIDE + CB * HD + cl * 2];
+                mm = fmaxf(mm, mw[w]);
+            }
+            float o = 0.f, l = 0.f;
+#pragma unroll
+            for (int w = 0; w < NW; ++w) {
+                const float f = mw[w] == NEG_INF ? 0.f : fast_exp2((mw[w] - mm) * c);
+                o += f * all[w * WSTRIDE + cl * HD + d];
+                l += f * all[w * WSTRIDE + CB * HD + cl * 2 + 1];
+            }
+            if (it.part_off < 0) {
+                const int crow = col_row(col, P.invG);
+                const int64_t orow = (int64_t)(it.grow0 + crow) * P.Hq + it.kvh * G + (col - crow * G);
+                const float val = o / l;
+                const float other = __shfl_xor(val, 1, 64);  // d and d^1 sit in neighbouring lanes
+                if ((d & 1) == 0) *reinterpret_cast<uint32_t*>(P.out + orow * HD + d) = pack_bf16(val, other);
+            } else {
+                float* pp = P.partials + it.part_off;
+                pp[(int64_t)col * HD + d] = o;
+                if (d == 0) {
+                    pp[(int64_t)ncols * HD + col * 2] = mm;
+                    pp[(int64_t)ncols * HD + col * 2 + 1] = l;
+                }
+            }
+        }
+    }
+}
+
+// Claims the next tile of queue q: its index in the work list, or -1 when the queue is exhausted.
+__device__ __forceinline__ int claim_from(const KParams& P, int q) {
+    const int got = (int)atomicAdd(&P.counters[kCursorBase + q * kCursorStride], 1u);
+    return got < P.queue_begin[q + 1] - P.queue_begin[q] ? P.queue_begin[q] + got : -1;
+}
+
+// The last workgroup of a kernel to run out of work re-arms the cursors of queues [q0, q1) and the kernel's own
+// count of finished workgroups (word `done_word`) for the next launch.
+__device__ __forceinline__ void rearm_cursors(const KParams& P, int q0, int q1, int done_word) {
+    const unsigned done = atomicAdd(&P.counters[done_word], 1u);
+    if (done == gridDim.x - 1) {
+        for (int q = q0; q < q1; ++q)
+            __hip_atomic_store(&P.counters[kCursorBase + q * kCursorStride], 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        __hip_atomic_store(&P.counters[done_word], 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     }
 }
 
@@ -719,8 +786,6 @@ __global__ __launch_bounds__(kThreads, 2) void ppd_mixed_kernel(const KParams P)
     // range, for the MFMA path (136 KiB at HD = 128); the narrow path's combine buffer (kWaves * 16 * (HD+2)
     // floats) uses the front of it.
     extern __shared__ __attribute__((aligned(16))) char smem[];
-    PPD_WG_SPAN_BEGIN();
-    PPD_MARK(P, 0);
     __shared__ int s_next_slot;
     volatile int* s_next = &s_next_slot;
     const int tid = threadIdx.x;
@@ -767,18 +832,12 @@ __global__ __launch_bounds__(kThreads, 2) void ppd_mixed_kernel(const KParams P)
         if (tid == 0) {
             int idx = -1;
 #pragma unroll
-#ifdef PPD_DIAG_NO_CROSS_KIND  // diagnostic builds only: a workgroup never takes the other kind's tiles
-            for (int attempt = 0; attempt < 1 && idx < 0; ++attempt) {
-#else
             for (int attempt = 0; attempt < 2 && idx < 0; ++attempt) {
-#endif
                 const bool want_narrow = (attempt == 0) == (pref == 1);
                 if (want_narrow) {
                     if (!(dry & (1u << kNarrowQueue))) {
-                        const int got = (int)atomicAdd(&P.counters[kCursorBase + kNarrowQueue * kCursorStride], 1u);
-                        if (got < P.queue_begin[kNarrowQueue + 1] - P.queue_begin[kNarrowQueue])
-                            idx = P.queue_begin[kNarrowQueue] + got;
-                        else {
+                        idx = claim_from(P, kNarrowQueue);
+                        if (idx < 0) {
                             dry |= 1u << kNarrowQueue;
                             if (dry != (2u << kNarrowQueue) - 1) look_at_cursors();
                         }
@@ -787,10 +846,8 @@ __global__ __launch_bounds__(kThreads, 2) void ppd_mixed_kernel(const KParams P)
                     for (int a = 0; a < kXcds && idx < 0; ++a) {
                         const int q = (xcd + a) & (kXcds - 1);
                         if (dry & (1u << q)) continue;
-                        const int got = (int)atomicAdd(&P.counters[kCursorBase + q * kCursorStride], 1u);
-                        if (got < P.queue_begin[q + 1] - P.queue_begin[q])
-                            idx = P.queue_begin[q] + got;
-                        else {
+                        idx = claim_from(P, q);
+                        if (idx < 0) {
                             dry |= 1u << q;
                             if (dry != (2u << kNarrowQueue) - 1) look_at_cursors();
                         }
@@ -803,26 +860,82 @@ __global__ __launch_bounds__(kThreads, 2) void ppd_mixed_kernel(const KParams P)
         const int idx = __builtin_amdgcn_readfirstlane(*s_next);
         __syncthreads();  // everyone has read s_next, and the previous tile's LDS use is over
         if (idx < 0) break;
-        PPD_MARK(P, 1);
         const ppd_work_item it = P.items[idx];
         if (it.kind == 0)
-            narrow_item<HD>(P, it, smem);
+            narrow_item<HD, kWaves, 4, 4>(P, it, smem);
         else
-            mfma_item<HD>(P, it, smem);
-        PPD_MARK(P, 7);
+            mfma_item<HD, false>(P, it, smem);
     }
-    PPD_MARK(P, 8);
-    PPD_WG_SPAN_END(P);
-    if (tid == 0) {
-        // the last workgroup to run out of work re-arms the cursors for the next launch
-        const unsigned done = atomicAdd(&P.counters[10], 1u);
-        if (done == gridDim.x - 1) {
+    if (tid == 0) rearm_cursors(P, 0, kNarrowQueue + 1, 10);
+}
+
+// ---------------------------------------------------------------------------------------------------
+// The co-resident pair.  A step that holds both kinds of tiles is launched as two kernels on two streams, sized so
+// that one workgroup of each fits on every compute unit at the same time: the row-block kernel (8 waves, two per
+// SIMD, 168 registers each, the K/V rings in LDS) keeps the matrix cores busy while the stream kernel (4 waves, one
+// per SIMD, 168 registers, a small combine buffer) keeps HBM busy from the same unit -- a compute unit streams
+// about 50 GB/s at most, whatever is in flight, so memory-bound tiles need most of the chip's units and so do the
+// matrix-bound ones.  Each kernel has its own queues, cursors and count of finished workgroups.
+// ---------------------------------------------------------------------------------------------------
+template <int HD>
+__global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(3, 3))) void ppd_mfma_kernel(const KParams P) {
+    extern __shared__ __attribute__((aligned(16))) char smem[];
+    __shared__ int s_next_slot;
+    volatile int* s_next = &s_next_slot;
+    const int tid = threadIdx.x;
+    const int xcd = (int)(__builtin_amdgcn_s_getreg((3 << 11) | (0 << 6) | 20) & (kXcds - 1));  // HW_REG_XCC_ID
+    unsigned dry = 0;  // bit q: queue q is exhausted (only thread 0 uses it)
 #pragma unroll
-            for (int q = 0; q <= kNarrowQueue; ++q)
-                __hip_atomic_store(&P.counters[kCursorBase + q * kCursorStride], 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-            __hip_atomic_store(&P.counters[10], 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    for (int q = 0; q < kXcds; ++q)
+        if (P.queue_begin[q + 1] == P.queue_begin[q]) dry |= 1u << q;
+    for (;;) {
+        if (tid == 0) {
+            int idx = -1;
+            for (int a = 0; a < kXcds && idx < 0; ++a) {
+                const int q = (xcd + a) & (kXcds - 1);
+                if (dry & (1u << q)) continue;
+                idx = claim_from(P, q);
+                if (idx < 0) {
+                    dry |= 1u << q;
+                    if (dry != (1u << kXcds) - 1) {  // one batch of plain loads tells which other queues are exhausted
+                        unsigned cur[kXcds];
+#pragma unroll
+                        for (int j = 0; j < kXcds; ++j)
+                            cur[j] = __hip_atomic_load(&P.counters[kCursorBase + j * kCursorStride], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+#pragma unroll
+                        for (int j = 0; j < kXcds; ++j)
+                            if ((int)cur[j] >= P.queue_begin[j + 1] - P.queue_begin[j]) dry |= 1u << j;
+                    }
+                }
+            }
+            *s_next = idx;
         }
+        __syncthreads();
+        const int idx = __builtin_amdgcn_readfirstlane(*s_next);
+        __syncthreads();
+        if (idx < 0) break;
+        const ppd_work_item it = P.items[idx];
+        mfma_item<HD, true>(P, it, smem);
     }
+    if (tid == 0) rearm_cursors(P, 0, kXcds, 10);
+}
+
+template <int HD>
+__global__ __launch_bounds__(kStreamThreads) __attribute__((amdgpu_waves_per_eu(3, 3))) void ppd_stream_kernel(const KParams P) {
+    extern __shared__ __attribute__((aligned(16))) char smem[];
+    __shared__ int s_next_slot;
+    volatile int* s_next = &s_next_slot;
+    const int tid = threadIdx.x;
+    for (;;) {
+        if (tid == 0) *s_next = claim_from(P, kNarrowQueue);
+        __syncthreads();
+        const int idx = __builtin_amdgcn_readfirstlane(*s_next);
+        __syncthreads();  // everyone has read s_next, and the previous tile's combine is over
+        if (idx < 0) break;
+        const ppd_work_item it = P.items[idx];
+        narrow_item<HD, kStreamWaves, kStreamKSets, kStreamVSets>(P, it, smem);
+    }
+    if (tid == 0) rearm_cursors(P, kNarrowQueue, kNarrowQueue + 1, 11);
 }
 
 // ---------------------------------------------------------------------------------------------------
@@ -1014,21 +1127,26 @@ __global__ __launch_bounds__(kSmallThreads) void ppd_kv_append_kernel(const uint
 }
 
 // ---------------------------------------------------------------------------------------------------
+static size_t ring_lds_bytes(int head_dim) {
+    return (size_t)(2 * kStages + (PPD_PINGPONG ? 1 : 0) + (PPD_PINGPONG ? 1 : 0)) * 4 * kPage * head_dim * 2 +
+           (kMaxMfmaChunk / kPage) * 4;  // + page ids of one row-block tile
+}
 static size_t mixed_lds_bytes(int head_dim) {
-    const size_t rings = (size_t)(2 * kStages + (PPD_PINGPONG ? 1 : 0) + (PPD_PINGPONG ? 1 : 0)) * 4 * kPage * head_dim * 2 +
-                         (kMaxMfmaChunk / kPage) * 4;  // + page ids of one row-block tile
-    const size_t combine = (size_t)kWaves * kNarrowCols * (head_dim + 2) * sizeof(float);
+    const size_t rings = ring_lds_bytes(head_dim), combine = NarrowCombine<kWaves>::bytes(head_dim);
     return rings > combine ? rings : combine;
 }
 
 // More than 64 KiB of dynamic LDS has to be allowed per kernel, on the device that is current (ppd_create calls
 // this once per context, with the context's device current).
 int prepare_mixed_kernels() {
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&ppd_mixed_kernel<128>),
-                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)mixed_lds_bytes(128));
-    if (e == hipSuccess)
-        e = hipFuncSetAttribute(reinterpret_cast<const void*>(&ppd_mixed_kernel<64>),
-                                hipFuncAttributeMaxDynamicSharedMemorySize, (int)mixed_lds_bytes(64));
+    hipError_t e = hipSuccess;
+    auto allow = [&](const void* fn, size_t bytes) {
+        if (e == hipSuccess) e = hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, (int)bytes);
+    };
+    allow(reinterpret_cast<const void*>(&ppd_mixed_kernel<128>), mixed_lds_bytes(128));
+    allow(reinterpret_cast<const void*>(&ppd_mixed_kernel<64>), mixed_lds_bytes(64));
+    allow(reinterpret_cast<const void*>(&ppd_mfma_kernel<128>), ring_lds_bytes(128));
+    allow(reinterpret_cast<const void*>(&ppd_mfma_kernel<64>), ring_lds_bytes(64));
     return (int)e;
 }
 
@@ -1038,6 +1156,26 @@ int launch_mixed(const KParams& p, int head_dim, int grid, void* stream) {
         hipLaunchKernelGGL(ppd_mixed_kernel<128>, dim3(grid), dim3(kThreads), mixed_lds_bytes(128), st, p);
     else
         hipLaunchKernelGGL(ppd_mixed_kernel<64>, dim3(grid), dim3(kThreads), mixed_lds_bytes(64), st, p);
+    return (int)hipGetLastError();
+}
+
+int launch_mfma_only(const KParams& p, int head_dim, int grid, void* stream) {
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    if (head_dim == 128)
+        hipLaunchKernelGGL(ppd_mfma_kernel<128>, dim3(grid), dim3(kThreads), ring_lds_bytes(128), st, p);
+    else
+        hipLaunchKernelGGL(ppd_mfma_kernel<64>, dim3(grid), dim3(kThreads), ring_lds_bytes(64), st, p);
+    return (int)hipGetLastError();
+}
+
+int launch_stream_only(const KParams& p, int head_dim, int grid, void* stream) {
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    if (head_dim == 128)
+        hipLaunchKernelGGL(ppd_stream_kernel<128>, dim3(grid), dim3(kStreamThreads),
+                           NarrowCombine<kStreamWaves>::bytes(128), st, p);
+    else
+        hipLaunchKernelGGL(ppd_stream_kernel<64>, dim3(grid), dim3(kStreamThreads),
+                           NarrowCombine<kStreamWaves>::bytes(64), st, p);
     return (int)hipGetLastError();
 }
 

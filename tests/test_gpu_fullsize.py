@@ -11,7 +11,18 @@ from helpers import check_close
 pytestmark = pytest.mark.gpu
 
 
-def _run_and_check(name, seq_ids_fn, rows_per_seq=4):
+def _edge_rows(n_i, rows_per_block, cap=None):
+    """First and last row and the rows either side of every row-block edge (at most `cap` edges, evenly spread)."""
+    edges = list(range(rows_per_block, n_i, rows_per_block))
+    if cap is not None and len(edges) > cap:
+        edges = [edges[i] for i in np.linspace(0, len(edges) - 1, cap).astype(int)]
+    pick = {0, n_i - 1}
+    for e in edges:
+        pick.update((e - 1, e))
+    return sorted(pick)
+
+
+def _run_and_check(name, seq_ids_fn, rows_per_seq=4, edge_rows=False, edge_cap=None):
     import torch
     import bench
     b = bench.make_shapes(name, 0) if isinstance(name, str) else name
@@ -39,6 +50,8 @@ def _run_and_check(name, seq_ids_fn, rows_per_seq=4):
     for i in range(sub.B):
         n_i = int(sub.n[i])
         pick = sorted(set([0, n_i - 1] + list(np.linspace(0, n_i - 1, rows_per_seq).astype(int))))
+        if edge_rows:
+            pick = sorted(set(pick) | set(_edge_rows(n_i, 256 // (sub.Hq // sub.Hkv), edge_cap)))
         mask[int(sub.row_off[i]) + np.asarray(pick)] = 1
     ref = oracle.mixed_attention(sub.q, pool_after, sub.page_tables, sub.L, sub.n, sub.Hq, sub.Hkv, sub.D, sub.P,
                                  sub.num_pages, sub.scale, row_mask=mask)
@@ -61,31 +74,27 @@ def _shortest_longest(b, k=1):
 
 
 def test_cfg2_decode_full_size():
-    _run_and_check("cfg2_decode", lambda b: _shortest_longest(b, 3))
+    """Every one of the 64 decode sequences, all heads."""
+    _run_and_check("cfg2_decode", lambda b: list(range(b.B)))
 
 
 def test_cfg3_append_prefill_full_size():
-    def pick(b):
-        order = np.argsort(b.n)
-        return [int(order[0]), int(order[-1])]          # smallest and largest new-token count
-    _run_and_check("cfg3_ap", pick, rows_per_seq=5)
+    """Every one of the 16 append-prefills: first, last, block-edge rows and a few in between."""
+    _run_and_check("cfg3_ap", lambda b: list(range(b.B)), rows_per_seq=5, edge_rows=True)
 
 
 def test_cfg4_mixed_full_size():
-    def pick(b):
-        dec = [i for i in range(b.B) if b.n[i] == 1]
-        ap = [i for i in range(b.B) if b.n[i] > 1]
-        dec = sorted(dec, key=lambda i: int(b.L[i]))
-        return [dec[0], dec[-1], ap[0]]
-    _run_and_check("cfg4_mixed_ap", pick, rows_per_seq=4)
+    """Every sequence of the batch: all 128 decode rows; of every append-prefill the first and last row, the rows
+    either side of each 64-row block edge and a few in between; KV append bit-exact on every page of the batch."""
+    _run_and_check("cfg4_mixed_ap", lambda b: list(range(b.B)), rows_per_seq=4, edge_rows=True)
 
 
 def test_cfg4_full_prefill_variant_full_size():
     def pick(b):
         full = sorted([i for i in range(b.B) if b.n[i] > 1], key=lambda i: int(b.n[i]))
         dec = sorted([i for i in range(b.B) if b.n[i] == 1], key=lambda i: int(b.L[i]))
-        return [dec[len(dec) // 2], full[0]]
-    _run_and_check("cfg4_mixed_full", pick, rows_per_seq=5)
+        return dec[::8] + [full[0], full[-1]]            # every 8th decode, the shortest and longest full prefill
+    _run_and_check("cfg4_mixed_full", pick, rows_per_seq=5, edge_rows=True, edge_cap=12)
 
 
 def test_mixed_batch_with_group_of_five_heads():

@@ -75,6 +75,32 @@ def test_scheduling_options_do_not_change_the_result(options):
     assert np.array_equal(out, base)
 
 
+@pytest.mark.parametrize("mode", [1, 2])
+@pytest.mark.parametrize("shape", [(32, 8, 128), (8, 2, 64), (40, 8, 128), (16, 2, 128)])
+def test_resident_pair_of_kernels_matches_oracle(mode, shape):
+    """launch_mode 1 / 2: narrow tiles on the stream kernel (4 waves, its own stream), row-block tiles on the
+    row-block kernel (half-tile loop), both resident on every compute unit at once; split key ranges so that partials
+    and the merge are in play; decode rows, small multi-row narrow tiles, append-prefill and full prefill together."""
+    Hq, Hkv, D = shape
+    b = si.make_batch("pair", L=[900, 0, 2500, 333, 64, 4000, 17, 1203, 0, 5000], n=[1, 150, 70, 2, 3, 1, 1, 65, 1, 1],
+                      Hq=Hq, Hkv=Hkv, D=D, seed=26 + mode, slack_pages=3)
+    for opts in ({}, {"narrow_chunk": 512, "mfma_chunk": 512}):
+        out, stats = _compare(b, options=dict(opts, launch_mode=mode))
+        assert stats["n_narrow"] > 0 and stats["n_mfma"] > 0
+        again, _ = _compare(b, options=dict(opts, launch_mode=mode))
+        assert np.array_equal(out, again), "not deterministic"
+
+
+def test_resident_pair_only_one_kind_present():
+    """launch_mode 2 with batches of one kind: each specialised kernel alone, no fork to the side stream."""
+    dec = si.make_batch("pair_dec", L=[900, 17, 4000, 0, 2047, 2048, 2049], n=[1, 1, 1, 1, 1, 2, 1], Hq=32, Hkv=8,
+                        D=128, seed=29, slack_pages=3)
+    ap = si.make_batch("pair_ap", L=[900, 0, 2500], n=[150, 70, 257], Hq=32, Hkv=8, D=128, seed=30, slack_pages=3)
+    for b in (dec, ap):
+        _compare(b, options={"launch_mode": 2})
+        _compare(b, options={"launch_mode": 2, "narrow_chunk": 256, "mfma_chunk": 256})
+
+
 @pytest.mark.parametrize("seed", range(8))
 def test_random_mixed_batches(seed):
     """Random batches: sequence count, head shape, the mix of decode / append-prefill / full-prefill rows, lengths
@@ -403,6 +429,36 @@ def test_step_replays_from_a_hip_graph():
         torch.cuda.synchronize()
         assert np.array_equal(from_dev_u16(out).reshape(out_ref.shape), out_ref), "replay %d differs" % rep
     assert np.array_equal(from_dev_u16(pool), pool_ref)
+    assert ctx.device_error_flags() == 0
+    del graph
+    ctx.close()
+
+
+def test_plan_change_under_capture_is_refused():
+    """A call whose plan is not on the device yet would have to synchronise and allocate: under stream capture it is
+    refused on the host, with nothing enqueued, and the capture stays valid."""
+    import torch
+    import paper_2603_13358_amd as ppd
+    from gpu_helpers import from_dev_u16, to_dev_u16
+    b = si.make_batch("cap", L=[300, 0, 70], n=[1, 40, 3], Hq=16, Hkv=2, D=128, seed=62, slack_pages=2)
+    pool_ref, out_ref, stats, ctx = _step(b, return_ctx=True)
+    dev = torch.device("cuda:0")
+    pool = to_dev_u16(pool_ref, torch, dev)
+    q = to_dev_u16(b.q, torch, dev)
+    pt = torch.from_numpy(b.page_tables).to(dev)
+    out = torch.zeros((b.T, b.Hq, b.D), dtype=torch.int16, device=dev)
+    other_L = b.L.copy()
+    other_L[0] -= 1
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        s = torch.cuda.current_stream().cuda_stream
+        with pytest.raises(ppd.PPDError) as e:
+            ctx.mixed_attention(q, pool, pt, other_L, b.n, b.scale, out, stream=s)
+        assert e.value.status == -3 and "capture" in str(e.value)
+        ctx.mixed_attention(q, pool, pt, b.L, b.n, b.scale, out, stream=s)      # same lengths: launches only
+    graph.replay()
+    torch.cuda.synchronize()
+    assert np.array_equal(from_dev_u16(out).reshape(out_ref.shape), out_ref)
     assert ctx.device_error_flags() == 0
     del graph
     ctx.close()
