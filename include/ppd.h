@@ -169,7 +169,21 @@ ppd_status ppd_mixed_attention(ppd_ctx *ctx, const void *q, const void *kv_pages
                                int32_t max_pages, const int32_t *L, const int32_t *n, int32_t B, float scale,
                                void *out, void *stream);
 
+/* The same operation for callers that cannot allocate: code under HIP graph capture, tight serving loops, harnesses
+ * that forbid hipMalloc.  Arguments, result and error behaviour are those of ppd_mixed_attention; the call itself
+ * allocates nothing (no hipMalloc / hipFree / hipHostMalloc, no event creation): the queue counters, the uploaded plan
+ * and the split partials live in a fixed device array inside the library, PPD_STATIC_SCRATCH_BYTES per GPU, which
+ * every GPU the library runs on holds until the process ends; the pinned staging buffer of the upload belongs to the
+ * context and is allocated by ppd_create.  Limits: the plan (56 bytes per tile plus the merge tables) must fit
+ * 2 MiB - 4 KiB and the split partials PPD_STATIC_SCRATCH_BYTES - 2 MiB; a batch beyond either is refused with
+ * PPD_ERR_WORKSPACE before anything is enqueued.  All contexts of the process share the array of their GPU and it
+ * keeps the previous call's contents: the call clears the counters it needs at zero itself, and two calls that
+ * overlap in time on one GPU (different streams or threads) race -- serialise them.  Option "timing" does not
+ * cover this entry point. */
 #define PPD_STATIC_SCRATCH_BYTES (32u << 20)
+ppd_status ppd_mixed_attention_static(ppd_ctx *ctx, const void *q, const void *kv_pages, const int32_t *page_tables,
+                                      int32_t max_pages, const int32_t *L, const int32_t *n, int32_t B, float scale,
+                                      void *out, void *stream);
 
 /* Statistics of the plan built by the last ppd_mixed_attention call on this context. */
 ppd_status ppd_get_plan_stats(const ppd_ctx *ctx, ppd_plan_stats *stats);

@@ -40,7 +40,7 @@ class PlanStats(ctypes.Structure):
 
 
 EXPORTS = ["ppd_create", "ppd_destroy", "ppd_last_error", "ppd_set_option", "ppd_kv_append", "ppd_kv_land",
-           "ppd_transfer_delay_s", "ppd_mixed_attention",
+           "ppd_transfer_delay_s", "ppd_mixed_attention", "ppd_mixed_attention_static",
            "ppd_get_plan_stats", "ppd_plan_build", "ppd_device_error_flags", "ppd_last_kernel_ms", "ppd_timed_kernels_ms",
            "ppd_route_score", "ppd_route_table_build", "ppd_route_cell", "ppd_route_decide", "ppd_version"]
 
@@ -69,6 +69,7 @@ def load_library():
     lib.ppd_transfer_delay_s.argtypes = [i64, i64, ctypes.c_double, ctypes.c_double]
     lib.ppd_transfer_delay_s.restype = ctypes.c_double
     lib.ppd_mixed_attention.argtypes = [vp, vp, vp, vp, i32, vp, vp, i32, ctypes.c_float, vp, vp]
+    lib.ppd_mixed_attention_static.argtypes = lib.ppd_mixed_attention.argtypes
     lib.ppd_get_plan_stats.argtypes = [vp, ctypes.POINTER(PlanStats)]
     lib.ppd_plan_build.argtypes = [ctypes.POINTER(Shape), vp, vp, i32, i32, i32, i32, i32, i32,
                                    ctypes.POINTER(WorkItem), i64, ctypes.POINTER(PlanStats)]
@@ -150,15 +151,20 @@ def ppd_transfer_delay_s(n_tokens, kv_bytes_per_token, beta_target_bytes_per_s, 
                                                      float(beta_target_bytes_per_s), float(t_fast_s)))
 
 
-def ppd_mixed_attention(ctx, q, kv_pages, page_tables, L, n, scale, out, max_pages=None, stream=None):
+def ppd_mixed_attention(ctx, q, kv_pages, page_tables, L, n, scale, out, max_pages=None, stream=None, static=False):
     L = _host_i32(L)
     n = _host_i32(n)
     if max_pages is None:
         max_pages = int(page_tables.shape[1])
     lib = load_library()
-    fn = lib.ppd_mixed_attention
+    fn = lib.ppd_mixed_attention_static if static else lib.ppd_mixed_attention
     _check(fn(ctx, _dev_ptr(q), _dev_ptr(kv_pages), _dev_ptr(page_tables), int(max_pages), L.ctypes.data,
               n.ctypes.data, int(L.shape[0]), float(scale), _dev_ptr(out), stream), ctx)
+
+
+def ppd_mixed_attention_static(ctx, q, kv_pages, page_tables, L, n, scale, out, max_pages=None, stream=None):
+    ppd_mixed_attention(ctx, q, kv_pages, page_tables, L, n, scale, out, max_pages=max_pages, stream=stream,
+                        static=True)
 
 
 def ppd_get_plan_stats(ctx):
@@ -263,6 +269,9 @@ class Context:
 
     def mixed_attention(self, q, kv_pages, page_tables, L, n, scale, out, stream=None):
         ppd_mixed_attention(self.handle, q, kv_pages, page_tables, L, n, scale, out, stream=stream)
+
+    def mixed_attention_static(self, q, kv_pages, page_tables, L, n, scale, out, stream=None):
+        ppd_mixed_attention_static(self.handle, q, kv_pages, page_tables, L, n, scale, out, stream=stream)
 
     def plan_stats(self):
         return ppd_get_plan_stats(self.handle)

@@ -553,6 +553,12 @@ ppd_status ppd_mixed_attention(ppd_ctx* ctx, const void* q, const void* kv_pages
     return mixed_attention_impl(ctx, q, kv_pages, page_tables, max_pages, L, n, B, scale, out, stream, false);
 }
 
+ppd_status ppd_mixed_attention_static(ppd_ctx* ctx, const void* q, const void* kv_pages, const int32_t* page_tables,
+                                      int32_t max_pages, const int32_t* L, const int32_t* n, int32_t B, float scale,
+                                      void* out, void* stream) {
+    return mixed_attention_impl(ctx, q, kv_pages, page_tables, max_pages, L, n, B, scale, out, stream, true);
+}
+
 ppd_status ppd_get_plan_stats(const ppd_ctx* ctx, ppd_plan_stats* stats) {
     if (!ctx || !stats) return PPD_ERR_NULL;
     *stats = ctx->plan.stats;
