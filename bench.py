@@ -333,6 +333,112 @@ def run_landing(torch, seed, steps):
                              "decode node's share"}
 
 
+# Representative request of every cell of the routing grid (paper appendix "Decision-Engine Discretization"): one
+# accumulated context per context class and (new input, expected output) token counts of the nine workload types,
+# decode-heavy to prefill-heavy (the two settings the paper names, 32/512 and 1024/32, are the extremes).
+ROUTE_CTX = (256, 2048, 8192)
+ROUTE_TYPES = ((32, 512), (64, 512), (64, 256), (128, 256), (256, 256), (512, 256), (512, 64), (1024, 64), (1024, 32))
+ROUTE_QPS = (0.5, 1, 2, 4, 6, 8, 10, 12, 16, 20)
+ROUTE_RATIO_CENTERS = tuple(a / b for a, b in ROUTE_TYPES)
+
+
+def run_route_table(torch, seed, steps, beta_gbs, layers=32, w_ttft=1.0, w_tpot=1.0, tpot_s=0.010, only=None):
+    """Offline phase of the paper's routing algorithm with this repository's own measurements in place of the
+    paper's whole-system ones: per cell, the turn's time to first token and the decode slowdown when the
+    append-prefill runs on the decode node (x = 1) against the prefill-node path (x = 0), at attention level.
+
+      x = 1: TTFT = layers * (mixed step: the decode batch + the append-prefill over the cached context)
+             extra decode-node time per request = layers * (mixed step - decode-only step)
+      x = 0: TTFT = layers * (append-prefill step alone, on a prefill node that holds the context)
+                    + transfer of the whole context's KV at `beta_gbs` (injected-delay equation of the appendix
+                      "Bandwidth Simulation" on top of the fast-interconnect time) + landing it in the page pools
+             extra decode-node time per request = the landing
+      delta_ttft = (TTFT0 - TTFT1) / TTFT0;  delta_tpot = qps * (extra1 - extra0): the share of the decode
+      node's time the choice costs, i.e. the relative lengthening of its decode steps.
+    The decode batch next to a request is the concurrency its QPS level implies at a whole-model time per output
+    token of `tpot_s` (qps * n_out * tpot_s, snapped to a power of two in 1..256).  Weight-bound GEMMs are outside
+    this repository, so both deltas are attention-only.  `only`: measure just these (context class, workload type,
+    QPS level) cells and leave the others at delta = 0 (x = 0)."""
+    import paper_2603_13358_amd as ppd
+    import synthetic_inputs as si
+    kv_bytes_token = 2 * 8 * 128 * 2 * layers                    # 128 KiB per token over 32 layers of 8 KV heads
+    fast_bw = 670433280 / 4.5e-3                                 # the fast interconnect of the appendix' example
+
+    def concurrency(qps, n_out):
+        b = max(1.0, min(256.0, qps * n_out * tpot_s))
+        return int(2 ** round(np.log2(b)))
+
+    memo = {}
+
+    def step_us(L, n):
+        key = (tuple(L), tuple(n))
+        if key not in memo:
+            b = si.make_batch("route", L=list(L), n=list(n), Hq=32, Hkv=8, D=128, seed=seed, slack_pages=16, with_data=False)
+            r = Runner(b, torch, seed)
+            memo[key] = r.time_steps(steps, 3) * 1e3
+            r.close()
+        return memo[key]
+
+    land_memo = {}
+
+    def land_us(T):
+        if T not in land_memo:
+            Hkv, D, P = 8, 128, 16
+            num_pages = (T + P - 1) // P + 8
+            pe = num_pages * 2 * Hkv * P * D
+            dev = torch.device("cuda:0")
+            ctx = ppd.Context(32, Hkv, D, num_pages)
+            k = torch.empty((layers, T, Hkv, D), dtype=torch.bfloat16, device=dev).normal_()
+            v = torch.empty((layers, T, Hkv, D), dtype=torch.bfloat16, device=dev).normal_()
+            pools = torch.zeros((layers * pe,), dtype=torch.bfloat16, device=dev)
+            t = np.arange(T)
+            slots = torch.from_numpy((np.random.default_rng(seed).permutation(num_pages)[t // P].astype(np.int64) * P + t % P)).to(dev)
+            stream = torch.cuda.current_stream().cuda_stream
+            for _ in range(3):
+                ctx.kv_land(k, v, pools, pe, layers, slots, stream=stream)
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record()
+            for _ in range(steps):
+                ctx.kv_land(k, v, pools, pe, layers, slots, stream=stream)
+            e1.record()
+            e1.synchronize()
+            land_memo[T] = e0.elapsed_time(e1) * 1e3 / steps
+            ctx.close()
+        return land_memo[T]
+
+    d_ttft, d_tpot, cells = np.zeros(270), np.zeros(270), []
+    for c, n_ctx in enumerate(ROUTE_CTX):
+        for r_, (n_in, n_out) in enumerate(ROUTE_TYPES):
+            for q, qps in enumerate(ROUTE_QPS):
+                if only is not None and (c, r_, q) not in only:
+                    continue
+                bsz = concurrency(qps, n_out)
+                t_dec = step_us([n_ctx] * bsz, [1] * bsz)
+                t_mix = step_us([n_ctx] * bsz + [n_ctx], [1] * bsz + [n_in])
+                t_ap = step_us([n_ctx], [n_in])
+                T = n_ctx + n_in
+                t_land = land_us(T)
+                t_fast = T * kv_bytes_token / fast_bw
+                t_xfer = t_fast + ppd.ppd_transfer_delay_s(T, kv_bytes_token, beta_gbs * 1e9, t_fast)
+                ttft1 = layers * t_mix * 1e-6
+                ttft0 = layers * t_ap * 1e-6 + t_xfer + t_land * 1e-6
+                extra1 = layers * (t_mix - t_dec) * 1e-6
+                extra0 = t_land * 1e-6
+                cell = (c * 9 + r_) * 10 + q
+                d_ttft[cell] = (ttft0 - ttft1) / ttft0
+                d_tpot[cell] = qps * (extra1 - extra0)
+                cells.append({"cell": cell, "n_ctx": n_ctx, "n_in": n_in, "n_out": n_out, "qps": qps, "decode_batch": bsz,
+                              "decode_step_us": t_dec, "mixed_step_us": t_mix, "ap_alone_step_us": t_ap,
+                              "landing_us": t_land, "transfer_ms": t_xfer * 1e3, "ttft_local_ms": ttft1 * 1e3,
+                              "ttft_pd_ms": ttft0 * 1e3, "delta_ttft": d_ttft[cell], "delta_tpot": d_tpot[cell]})
+    table = ppd.ppd_route_table_build(d_ttft, d_tpot, w_ttft, w_tpot)
+    by_ctx = {str(ROUTE_CTX[c]): int(table[c * 90:(c + 1) * 90].sum()) for c in range(3)}
+    return {"beta_GBs": beta_gbs, "layers": layers, "weights": [w_ttft, w_tpot], "assumed_tpot_s": tpot_s,
+            "ratio_centers": list(ROUTE_RATIO_CENTERS), "x_table": table.tolist(), "cells_local_of_90_by_context": by_ctx,
+            "delta_ttft": d_ttft.tolist(), "delta_tpot": d_tpot.tolist(), "cells": cells,
+            "measurements": len(memo) + len(land_memo)}
+
+
 def run_sweeps(torch, seed, steps, options):
     """Attention-level analogues of the paper's interference experiments (section 4.1 and its appendix): a decode
     batch co-located with append-prefill or with a full prefill of equal context, over batch size, over context
@@ -402,6 +508,10 @@ def main():
     ap.add_argument("--trace-steps", type=int, default=0, help="limit the trace to its first N engine steps")
     ap.add_argument("--trace-pool-gb", type=float, default=200.0)
     ap.add_argument("--landing", action="store_true", help="time the multi-layer KV landing of one request and exit")
+    ap.add_argument("--route-table", action="store_true",
+                    help="measure the routing grid (local append-prefill vs transfer + landing) and build the decision table")
+    ap.add_argument("--route-beta-gbs", type=float, default=25.0, help="interconnect bandwidth of the x = 0 path, GB/s")
+    ap.add_argument("--route-weights", default="1,1", help="w_ttft,w_tpot")
     ap.add_argument("--sweeps", action="store_true",
                     help="interference sweeps (batch size, context, 4 prefills, chunked append-prefill) and exit")
     args = ap.parse_args()
@@ -417,6 +527,11 @@ def main():
         return
     if args.landing:
         print(json.dumps({"workload": "kv_landing_5115_tokens_32_layers", "landing": run_landing(torch, args.seed, args.steps)}))
+        return
+    if args.route_table:
+        w = [float(x) for x in args.route_weights.split(",")]
+        print(json.dumps({"workload": "route_table", "route_table": run_route_table(
+            torch, args.seed, max(5, args.steps // 5), args.route_beta_gbs, w_ttft=w[0], w_tpot=w[1])}))
         return
     if args.sweeps:
         print(json.dumps({"workload": "interference_sweeps", "sweeps": run_sweeps(torch, args.seed, max(10, args.steps // 2),

@@ -240,6 +240,12 @@ int32_t ppd_route_cell(const double *ratio_centers, int64_t n_in, int64_t n_out,
 int32_t ppd_route_decide(const uint8_t *x_table, const double *ratio_centers, int32_t turn, int64_t n_in,
                          int64_t n_out, int64_t n_ctx, double qps);
 
+/* The online phase for `count` requests in one call (a router's inner loop): x_out[i] = ppd_route_decide(... [i]).
+ * All arrays HOST, `count` entries; x_out int8 (-1 marks an invalid request). */
+ppd_status ppd_route_decide_batch(const uint8_t *x_table, const double *ratio_centers, int64_t count,
+                                  const int32_t *turn, const int64_t *n_in, const int64_t *n_out, const int64_t *n_ctx,
+                                  const double *qps, int8_t *x_out);
+
 /* Library version, "major.minor". */
 const char *ppd_version(void);
 

@@ -42,7 +42,7 @@ class PlanStats(ctypes.Structure):
 EXPORTS = ["ppd_create", "ppd_destroy", "ppd_last_error", "ppd_set_option", "ppd_kv_append", "ppd_kv_land",
            "ppd_transfer_delay_s", "ppd_mixed_attention", "ppd_mixed_attention_static",
            "ppd_get_plan_stats", "ppd_plan_build", "ppd_device_error_flags", "ppd_last_kernel_ms", "ppd_timed_kernels_ms",
-           "ppd_route_score", "ppd_route_table_build", "ppd_route_cell", "ppd_route_decide", "ppd_version"]
+           "ppd_route_score", "ppd_route_table_build", "ppd_route_cell", "ppd_route_decide", "ppd_route_decide_batch", "ppd_version"]
 
 
 def lib_path():
@@ -82,6 +82,7 @@ def load_library():
     lib.ppd_route_table_build.argtypes = [vp, vp, dbl, dbl, vp]
     lib.ppd_route_cell.argtypes = [vp, i64, i64, i64, dbl]
     lib.ppd_route_decide.argtypes = [vp, vp, i32, i64, i64, i64, dbl]
+    lib.ppd_route_decide_batch.argtypes = [vp, vp, i64, vp, vp, vp, vp, vp, vp]
     lib.ppd_version.argtypes = []
     lib.ppd_version.restype = ctypes.c_char_p
     for name in EXPORTS:
@@ -225,6 +226,24 @@ def ppd_route_decide(x_table, ratio_centers, turn, n_in, n_out, n_ctx, qps):
     assert t.size == ROUTE_CELLS and c.size == 9
     return int(load_library().ppd_route_decide(t.ctypes.data, c.ctypes.data, int(turn), int(n_in), int(n_out),
                                                int(n_ctx), float(qps)))
+
+
+def ppd_route_decide_batch(x_table, ratio_centers, turn, n_in, n_out, n_ctx, qps):
+    """Online decisions for arrays of requests in one call; returns int8 [count]."""
+    t = np.ascontiguousarray(x_table, dtype=np.uint8)
+    c = np.ascontiguousarray(ratio_centers, dtype=np.float64)
+    assert t.size == ROUTE_CELLS and c.size == 9
+    turn = np.ascontiguousarray(turn, dtype=np.int32)
+    a, b, d = (np.ascontiguousarray(x, dtype=np.int64) for x in (n_in, n_out, n_ctx))
+    qps = np.ascontiguousarray(qps, dtype=np.float64)
+    count = turn.size
+    assert a.size == count and b.size == count and d.size == count and qps.size == count
+    out = np.empty(count, np.int8)
+    status = load_library().ppd_route_decide_batch(t.ctypes.data, c.ctypes.data, count, turn.ctypes.data, a.ctypes.data,
+                                                   b.ctypes.data, d.ctypes.data, qps.ctypes.data, out.ctypes.data)
+    if status != 0:
+        raise PPDError(status, "ppd_route_decide_batch")
+    return out
 
 
 def ppd_plan_build(num_q_heads, num_kv_heads, head_dim, page_size, num_pages, L, n, narrow_chunk=0, mfma_chunk=0,

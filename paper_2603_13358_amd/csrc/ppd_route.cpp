@@ -70,4 +70,15 @@ int32_t ppd_route_decide(const uint8_t* x_table, const double* ratio_centers, in
     return x_table[cell] ? 1 : 0;
 }
 
+ppd_status ppd_route_decide_batch(const uint8_t* x_table, const double* ratio_centers, int64_t count,
+                                  const int32_t* turn, const int64_t* n_in, const int64_t* n_out, const int64_t* n_ctx,
+                                  const double* qps, int8_t* x_out) {
+    if (count < 0) return PPD_ERR_RANGE;
+    if (count == 0) return PPD_OK;
+    if (!x_table || !ratio_centers || !turn || !n_in || !n_out || !n_ctx || !qps || !x_out) return PPD_ERR_NULL;
+    for (int64_t i = 0; i < count; ++i)
+        x_out[i] = (int8_t)ppd_route_decide(x_table, ratio_centers, turn[i], n_in[i], n_out[i], n_ctx[i], qps[i]);
+    return PPD_OK;
+}
+
 }  // extern "C"

@@ -565,3 +565,28 @@ def test_kv_land_all_layers_bit_exact():
     assert abs(ppd.ppd_transfer_delay_s(5115, 131072, 25e9, 0.0045) -
                oracle.transfer_delay(5115, 131072, 25e9, 0.0045)) < 1e-15
     ctx.close()
+
+
+def test_measured_route_table_reproduces_the_papers_regime():
+    """Offline phase of the routing algorithm (section 5) fed with this repository's own measurements, on four cells of
+    the grid: where the paper finds local append-prefill to win -- large accumulated context, prefill-heavy turn,
+    KV transfer over a 25 GB/s link (94-96 % lower TTFT for a few percent of decode slowdown, sections 4 and 6) -- the
+    measured table says x = 1 with a TTFT gain above one half; an operator who weights only decode smoothness gets
+    x = 0 in every cell that costs decode time at all; cells never measured stay on the prefill-node path."""
+    import torch
+    import bench
+    import paper_2603_13358_amd as ppd
+    cells = [(2, 8, 5), (2, 6, 9), (1, 8, 3), (0, 0, 0)]          # (context class, workload type, QPS level)
+    res = bench.run_route_table(torch, 0, 5, 25.0, only=cells)
+    table = np.asarray(res["x_table"])
+    idx = lambda c, r, q: (c * 9 + r) * 10 + q
+    for c, r, q in cells[:3]:
+        assert table[idx(c, r, q)] == 1 and res["delta_ttft"][idx(c, r, q)] > 0.5
+    assert table.sum() <= len(cells)
+    dt, dp = np.asarray(res["delta_ttft"]), np.asarray(res["delta_tpot"])
+    only_tpot = ppd.ppd_route_table_build(dt, dp, 0.0, 1.0)
+    assert all(only_tpot[idx(*cell)] == 0 for cell in cells if dp[idx(*cell)] > 0)
+    # the online phase on top of it: a turn-3 request of the first cell's shape runs locally, its turn 1 does not
+    centers = res["ratio_centers"]
+    assert ppd.ppd_route_decide(table, centers, 3, 1024, 32, 9000, 8.0) == 1
+    assert ppd.ppd_route_decide(table, centers, 1, 1024, 32, 9000, 8.0) == 0
