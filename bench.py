@@ -197,13 +197,13 @@ def cpu_baseline(runner, budget_s=15.0):
             "max_abs_err_vs_gpu": err}
 
 
-def run_trace(torch, seed, max_steps, pool_gb):
+def run_trace(torch, seed, max_steps, pool_gb, turns=5):
     """Multi-turn trace on a 70B-class GQA layer (64 q / 8 kv heads): every engine step = one KV append plus one
     mixed attention over all active conversations, pages drawn at random from a large shared pool."""
     import paper_2603_13358_amd as ppd
     import synthetic_inputs as si
     Hq, Hkv, D, P = 64, 8, 128, 16
-    steps, max_tokens = si.cfg5_trace(seed)
+    steps, max_tokens = si.cfg5_trace(seed, turns=turns)
     page_bytes = 2 * Hkv * P * D * 2
     free_b, _ = torch.cuda.mem_get_info()
     num_pages = int(min(pool_gb * 1e9, free_b * 0.9) // page_bytes)
@@ -226,6 +226,8 @@ def run_trace(torch, seed, max_steps, pool_gb):
     gen = torch.Generator(device=dev)
     gen.manual_seed(seed)
     rec, plan_us, first_us = [], [], []
+    turn_of = np.ones(len(need), np.int64)          # turn each conversation is in (turn 1 = its landing)
+    by_turn = {}                                    # turn -> [accumulated context, new tokens, step us] per append-prefill
     if max_steps:
         steps = steps[:max_steps]
     t_all0 = time.perf_counter()
@@ -260,6 +262,11 @@ def run_trace(torch, seed, max_steps, pool_gb):
         kv_bytes = int((st.L + st.n).sum()) * 2 * Hkv * D * 2 if st.attend else 0
         flops = float(4.0 * Hq * D * np.sum(st.n * st.L + st.n * (st.n + 1) / 2.0)) if st.attend else 0.0
         rec.append((us, st.attend, int((st.n > 1).sum()), int(len(st.n)), kv_bytes, flops))
+        if st.attend:
+            for c, Lc, nc in zip(st.conv, st.L, st.n):
+                if nc > 1:
+                    turn_of[c] += 1
+                    by_turn.setdefault(int(turn_of[c]), []).append((int(Lc), int(nc), us))
     wall = time.perf_counter() - t_all0
     ctx.close()
     us = np.array([r[0] for r in rec])
@@ -272,7 +279,15 @@ def run_trace(torch, seed, max_steps, pool_gb):
     def dist(x):
         return {"n": int(x.size), "p10": float(np.percentile(x, 10)), "p50": float(np.percentile(x, 50)),
                 "p90": float(np.percentile(x, 90)), "mean": float(x.mean())} if x.size else {"n": 0}
-    return {"steps": len(rec), "pool_pages": num_pages, "pool_GB": num_pages * page_bytes / 1e9,
+    kv_tok_bytes_model = 2 * Hkv * D * 2 * 80       # 80 layers of this 70B-class shape
+    turn_rows = {}
+    for t in sorted(by_turn):
+        a = np.array(by_turn[t], np.float64)
+        ctx_mean = float(a[:, 0].mean())
+        turn_rows[str(t)] = {"append_prefills": int(a.shape[0]), "mean_accumulated_context": ctx_mean,
+                             "mean_new_tokens": float(a[:, 1].mean()), "mean_step_us_one_layer": float(a[:, 2].mean()),
+                             "kv_transfer_ms_of_that_context_at_25GBs": ctx_mean * kv_tok_bytes_model / 25e9 * 1e3}
+    return {"turns": turns, "append_prefill_steps_by_turn": turn_rows, "steps": len(rec), "pool_pages": num_pages, "pool_GB": num_pages * page_bytes / 1e9,
             "total_gpu_ms": float(us.sum() / 1e3), "wall_s_incl_input_generation": wall,
             "decode_only_steps_us": dist(us[dec]), "steps_with_append_prefill_us": dist(us[apm]),
             "first_layer_decode_only_steps_us": dist(np.array(first_us)[dec]),
@@ -507,6 +522,7 @@ def main():
     ap.add_argument("--trace", action="store_true", help="run the multi-turn conversation trace (cfg5) and exit")
     ap.add_argument("--trace-steps", type=int, default=0, help="limit the trace to its first N engine steps")
     ap.add_argument("--trace-pool-gb", type=float, default=200.0)
+    ap.add_argument("--turns", type=int, default=5, help="turns per conversation of the trace (the paper scales 2..16)")
     ap.add_argument("--landing", action="store_true", help="time the multi-layer KV landing of one request and exit")
     ap.add_argument("--route-table", action="store_true",
                     help="measure the routing grid (local append-prefill vs transfer + landing) and build the decision table")
@@ -523,7 +539,7 @@ def main():
     options = {kv.split("=")[0]: int(kv.split("=")[1]) for kv in args.opt}
     if args.trace:
         print(json.dumps({"workload": "cfg5_multi_turn_trace", "trace": run_trace(torch, args.seed, args.trace_steps,
-                                                                                 args.trace_pool_gb)}))
+                                                                                 args.trace_pool_gb, args.turns)}))
         return
     if args.landing:
         print(json.dumps({"workload": "kv_landing_5115_tokens_32_layers", "landing": run_landing(torch, args.seed, args.steps)}))

@@ -10,21 +10,25 @@ from helpers import SENTINEL, bits_to_f32, check_close
 pytestmark = pytest.mark.gpu
 
 
-def test_short_trace_matches_oracle_every_step():
+def _trace_against_oracle(n_conv, turns, prompt_mean, response_mean, sigma, start_spread, len_clip, seed,
+                          sample_ap_rows=False):
+    """Runs a whole trace on one persistent pool, the oracle beside it step by step (its own pool, its own appends);
+    every decode row is compared, append-prefill rows all or -- sample_ap_rows -- first, last, block edges and a few."""
     import torch
     import paper_2603_13358_amd as ppd
     from gpu_helpers import from_dev_u16, to_dev_u16
 
     Hq, Hkv, D, P = 16, 2, 128, 16
-    steps, max_tokens = si.cfg5_trace(seed=3, n_conv=6, turns=3, prompt_mean=40.0, response_mean=6.0, sigma=0.8,
-                                      start_spread=4, len_clip=(1, 200))
+    steps, max_tokens = si.cfg5_trace(seed=seed, n_conv=n_conv, turns=turns, prompt_mean=prompt_mean,
+                                      response_mean=response_mean, sigma=sigma, start_spread=start_spread,
+                                      len_clip=len_clip)
     rng = np.random.default_rng(77)
     need = (max_tokens + P - 1) // P
     num_pages = int(need.sum()) + 5
     perm = rng.permutation(num_pages).astype(np.int32)
-    pt = np.full((6, int(need.max())), -1, np.int32)
+    pt = np.full((n_conv, int(need.max())), -1, np.int32)
     at = 0
-    for c in range(6):
+    for c in range(n_conv):
         pt[c, :need[c]] = perm[at:at + need[c]]
         at += int(need[c])
     dev = torch.device("cuda:0")
@@ -33,8 +37,8 @@ def test_short_trace_matches_oracle_every_step():
     pool_d = torch.full((ctx.pool_elems(),), fill, dtype=torch.int16, device=dev)
     pool_h = np.full(ctx.pool_elems(), SENTINEL, np.uint16)
     scale = 1.0 / np.sqrt(D)
-    n_att = 0
-    for si_, st in enumerate(steps):
+    n_att, longest = 0, 0
+    for st in steps:
         T = int(st.n.sum())
         k = si.normal_bf16(rng, (T, Hkv, D))
         v = si.normal_bf16(rng, (T, Hkv, D))
@@ -48,13 +52,39 @@ def test_short_trace_matches_oracle_every_step():
         sub_pt = np.ascontiguousarray(pt[st.conv])
         out = torch.zeros((T, Hq, D), dtype=torch.int16, device=dev)
         ctx.mixed_attention(to_dev_u16(q, torch, dev), pool_d, torch.from_numpy(sub_pt).to(dev), st.L, st.n, scale, out)
-        ref = oracle.mixed_attention(q, pool_h, sub_pt, st.L, st.n, Hq, Hkv, D, P, num_pages, scale)
-        check_close(bits_to_f32(from_dev_u16(out).reshape(T, Hq, D)), ref)
+        mask = None
+        if sample_ap_rows:
+            mask = np.zeros(T, np.uint8)
+            o = 0
+            for n_i in st.n:
+                mask[o + np.asarray(_sample_rows(int(n_i), 256 // (Hq // Hkv), rng))] = 1
+                o += int(n_i)
+        ref = oracle.mixed_attention(q, pool_h, sub_pt, st.L, st.n, Hq, Hkv, D, P, num_pages, scale, row_mask=mask)
+        got = bits_to_f32(from_dev_u16(out).reshape(T, Hq, D))
+        sel = np.ones(T, bool) if mask is None else mask.astype(bool)
+        check_close(got[sel], ref[sel])
         n_att += 1
+        longest = max(longest, int((st.L + st.n).max()))
     assert ctx.device_error_flags() == 0
     assert np.array_equal(from_dev_u16(pool_d), pool_h), "pools diverged over the trace"
-    assert n_att > 10
     ctx.close()
+    return n_att, longest
+
+
+def test_short_trace_matches_oracle_every_step():
+    n_att, _ = _trace_against_oracle(n_conv=6, turns=3, prompt_mean=40.0, response_mean=6.0, sigma=0.8, start_spread=4,
+                                     len_clip=(1, 200), seed=3)
+    assert n_att > 10
+
+
+def test_sixteen_turn_trace_matches_oracle():
+    """Turn scaling (the paper's scaling-validation appendix runs conversations of 2 to 16 turns): 16 turns of long
+    prompts and short answers, so that the accumulated context passes 16K tokens while the turn's append-prefill
+    still sees all of it from the pages; every decode row and sampled append-prefill rows of every step."""
+    n_att, longest = _trace_against_oracle(n_conv=4, turns=16, prompt_mean=1100.0, response_mean=5.0, sigma=0.5,
+                                           start_spread=3, len_clip=(1, 2500), seed=5, sample_ap_rows=True)
+    print("attention steps", n_att, "longest context", longest, flush=True)
+    assert longest > 16384 and n_att > 60
 
 
 def _sample_rows(n_i, rows_per_block, rng, extra=3):
