@@ -540,13 +540,6 @@ ppd_status ppd_kv_land(ppd_ctx* ctx, const void* k, const void* v, void* kv_page
     return PPD_OK;
 }
 
-double ppd_transfer_delay_s(int64_t n_tokens, int64_t kv_bytes_per_token, double beta_target_bytes_per_s,
-                            double t_fast_s) {
-    if (n_tokens < 0 || kv_bytes_per_token < 0 || !(beta_target_bytes_per_s > 0.0)) return -1.0;
-    const double d = (double)n_tokens * (double)kv_bytes_per_token / beta_target_bytes_per_s - t_fast_s;
-    return d > 0.0 ? d : 0.0;
-}
-
 ppd_status ppd_mixed_attention(ppd_ctx* ctx, const void* q, const void* kv_pages, const int32_t* page_tables,
                                int32_t max_pages, const int32_t* L, const int32_t* n, int32_t B, float scale,
                                void* out, void* stream) {

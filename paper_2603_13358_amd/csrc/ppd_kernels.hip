@@ -123,6 +123,18 @@ __device__ __forceinline__ void lds_direct_load16(const void* gbase, uint32_t la
 // phase -- with S^T of 32 keys and half of the packed probabilities live at a time: 24 registers less per lane,
 // which is what lets two such waves and a stream wave share a SIMD (three waves of 168 registers).  The late waves
 // then take the loop barrier between the second vector phase and the second matrix phase.
+// LDS byte address of p as an opaque 32-bit register value: operand reads then address LDS as this register plus a
+// compile-time offset below 64 KiB, which fits the instruction's offset field (left to itself the compiler folds
+// ring and stage offsets into constants beyond that field and spends one vector add per read).
+__device__ __forceinline__ uint32_t lds_base(const char* p) {
+    uint32_t a = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) const char*)p;
+    asm volatile("" : "+v"(a));
+    return a;
+}
+__device__ __forceinline__ u32x4 lds_read16(uint32_t base, int offset) {
+    return *reinterpret_cast<const __attribute__((address_space(3))) u32x4*>(base + (uint32_t)offset);
+}
+
 template <int HD, bool HALF>
 __device__ __forceinline__ void mfma_item(const KParams& P, const ppd_work_item& it, char* smem) {
     constexpr int PB = kPage * HD * 2;         // bytes of one (page, head) block of K or of V
@@ -247,7 +259,7 @@ __device__ __forceinline__ void mfma_item(const KParams& P, const ppd_work_item&
     const int v_lane_off = VRING + (h * HD + l32) * 16;             // + stage + s*PB + db*512
 
     auto qk_tile = [&](int stage, f32x16 (&sacc)[2]) {
-        const char* kb = smem + stage * KBYTES + k_lane_off;
+        const uint32_t kb = lds_base(smem + stage * KBYTES + k_lane_off);
 #pragma unroll
         for (int tb = 0; tb < 2; ++tb)
 #pragma unroll
@@ -256,7 +268,7 @@ __device__ __forceinline__ void mfma_item(const KParams& P, const ppd_work_item&
         for (int ks = 0; ks < KS; ++ks)
 #pragma unroll
             for (int tb = 0; tb < 2; ++tb) {
-                bf16x8 a = as_bf16x8(*reinterpret_cast<const u32x4*>(kb + tb * 2 * PB + ks * 512));
+                bf16x8 a = as_bf16x8(lds_read16(kb, tb * 2 * PB + ks * 512));
                 sacc[tb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, qreg[ks], sacc[tb], 0, 0, 0);
             }
     };
@@ -380,13 +392,13 @@ __device__ __forceinline__ void mfma_item(const KParams& P, const ppd_work_item&
         if (wave_active) {
             // Matrix phase: O^T += V^T P^T of this tile, then S^T of the next one into the registers the
             // probabilities have left.
-            const char* vb = smem + sv_cur * KBYTES + v_lane_off;
+            const uint32_t vb = lds_base(smem + sv_cur * KBYTES + v_lane_off);
 #pragma unroll
             for (int s = 0; s < 4; ++s) {
                 const bf16x8 pb = as_bf16x8(pw[s]);
 #pragma unroll
                 for (int db = 0; db < DB; ++db) {
-                    bf16x8 a = as_bf16x8(*reinterpret_cast<const u32x4*>(vb + s * PB + db * 512));
+                    bf16x8 a = as_bf16x8(lds_read16(vb, s * PB + db * 512));
                     oacc[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, pb, oacc[db], 0, 0, 0);
                 }
             }
@@ -402,12 +414,12 @@ __device__ __forceinline__ void mfma_item(const KParams& P, const ppd_work_item&
     } else {
     // S^T of 32 keys: the tb-th pair of pages of a K stage
     auto qk_half = [&](int stage, int tb, f32x16& sacc) {
-        const char* kb = smem + stage * KBYTES + k_lane_off + tb * 2 * PB;
+        const uint32_t kb = lds_base(smem + stage * KBYTES + k_lane_off + tb * 2 * PB);
 #pragma unroll
         for (int i = 0; i < 16; ++i) sacc[i] = 0.f;
 #pragma unroll
         for (int ks = 0; ks < KS; ++ks) {
-            bf16x8 a = as_bf16x8(*reinterpret_cast<const u32x4*>(kb + ks * 512));
+            bf16x8 a = as_bf16x8(lds_read16(kb, ks * 512));
             sacc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, qreg[ks], sacc, 0, 0, 0);
         }
     };
@@ -486,13 +498,13 @@ __device__ __forceinline__ void mfma_item(const KParams& P, const ppd_work_item&
             if (hb == 1 && late) close_iteration();
             if (wave_active) {
                 // O^T += V^T P^T of this half, then S^T of the next half into the registers the probabilities left
-                const char* vb = smem + sv_cur * KBYTES + v_lane_off + hb * 2 * PB;
+                const uint32_t vb = lds_base(smem + sv_cur * KBYTES + v_lane_off + hb * 2 * PB);
 #pragma unroll
                 for (int s2 = 0; s2 < 2; ++s2) {
                     const bf16x8 pb = as_bf16x8(pw[s2]);
 #pragma unroll
                     for (int db = 0; db < DB; ++db) {
-                        bf16x8 a = as_bf16x8(*reinterpret_cast<const u32x4*>(vb + s2 * PB + db * 512));
+                        bf16x8 a = as_bf16x8(lds_read16(vb, s2 * PB + db * 512));
                         oacc[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, pb, oacc[db], 0, 0, 0);
                     }
                 }

@@ -1,10 +1,10 @@
 // Host planner of the one-launch mixed step: classifies sequences, splits key ranges, orders tiles.
 //
 // Per sequence (L cached, n new; paper section 4.1 with L = the paper's n and n = its m): n*G <= 16 query
-// columns -> narrow tiles (decode is n = 1), else row blocks of 128/G rows on the MFMA path.  A tile is
-// (sequence, KV head, row block, key range); key ranges are split so that the launch has several tiles per
-// resident workgroup, and tiles run longest-first from one queue so that HBM-bound narrow tiles and
-// MFMA-bound row-block tiles share the compute units.
+// columns -> narrow tiles (decode is n = 1), else row blocks of 256/G rows on the MFMA path.  A tile is
+// (sequence, KV head, row block, key range); key ranges are split only as far as filling and balancing the
+// workgroups needs, and tiles run longest-first from nine queues (one of narrow tiles, eight of row-block tiles,
+// one per XCD) so that HBM-bound narrow tiles and MFMA-bound row-block tiles run side by side on the chip.
 #include <algorithm>
 #include <cmath>
 #include <cstring>
@@ -60,9 +60,8 @@ static void split_range(int64_t len, int64_t chunk, std::vector<int32_t>* bounds
 // ranks the candidates of one batch correctly.
 struct RowBlock { int64_t vis_end; int32_t nrows; };
 
-// Compute units (of the 32 of an XCD) whose workgroups take narrow tiles first.  Two workgroups share a compute
-// unit; an MFMA tile next to a narrow tile on the same unit runs far below half the unit's MFMA rate, so the split
-// is by physical unit.  Narrow tiles are bound by the bytes a unit keeps in flight (about 45 GB/s each), MFMA tiles
+// Compute units (of the 32 of an XCD) whose workgroups take narrow tiles first.  A workgroup of the mixed kernel
+// fills a compute unit (8 waves of up to 256 registers), so the two kinds are split by physical unit.  Narrow tiles are bound by the bytes a unit keeps in flight (about 45 GB/s each), MFMA tiles
 // by compute (about 2.3 us per 64 keys of a row block): the split is sized so that both kinds finish together;
 // whoever finishes first steals from the other anyway.
 static int narrow_units(double narrow_bytes, double mfma_iters) {

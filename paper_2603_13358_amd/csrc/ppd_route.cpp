@@ -1,4 +1,4 @@
-// PPD routing decision (host only): the score of local append-prefill versus the prefill-node path, the offline
+// Host-only arithmetic of the library: the KV-transfer delay model and the PPD routing decision: the score of local append-prefill versus the prefill-node path, the offline
 // table of its sign over a discretised workload grid, and the per-request lookup (paper section 3, the score
 // equation; section 5, algorithm "PPD Dynamic Routing"; appendix "Decision-Engine Discretization").
 #include <cmath>
@@ -37,6 +37,14 @@ int nearest_ratio(const double* centers, double ratio) {
 }  // namespace
 
 extern "C" {
+
+// Injected-delay equation of the appendix "Bandwidth Simulation" (host arithmetic).
+double ppd_transfer_delay_s(int64_t n_tokens, int64_t kv_bytes_per_token, double beta_target_bytes_per_s,
+                            double t_fast_s) {
+    if (n_tokens < 0 || kv_bytes_per_token < 0 || !(beta_target_bytes_per_s > 0.0)) return -1.0;
+    const double d = (double)n_tokens * (double)kv_bytes_per_token / beta_target_bytes_per_s - t_fast_s;
+    return d > 0.0 ? d : 0.0;
+}
 
 double ppd_route_score(double w_ttft, double w_tpot, double delta_ttft, double delta_tpot) {
     return w_ttft * delta_ttft - w_tpot * delta_tpot;
