@@ -84,7 +84,8 @@ typedef struct {
     int32_t kv_begin; /* key range [kv_begin, kv_end) this tile covers; kv_begin is a multiple of 64 */
     int32_t kv_end;
     int32_t group;    /* merge group, or -1 when the tile covers the whole key range and writes `out` */
-    int32_t queue;    /* work queue: 0..7 = MFMA tiles preferred by the workgroups of XCD `queue`, 8 = narrow tiles */
+    int32_t queue;    /* work queue: 0..7 = MFMA tiles preferred by the workgroups of XCD `queue`, 8 = narrow tiles run by a
+                         whole workgroup, 9 = short narrow tiles run one per wave, eight to a claim */
     int64_t part_off; /* float offset of this tile's partial (o, m, l) in the workspace, or -1 */
 } ppd_work_item;
 
@@ -117,7 +118,8 @@ const char *ppd_last_error(const ppd_ctx *ctx);
  * kind of tile a workgroup takes first -- 0 MFMA tiles for all, 1 alternating per group of 8 workgroups,
  * 2 split by physical compute unit (default), 3 narrow tiles for all), "narrow_cus" (pref_mode 2: how many of
  * the 32 compute units of an XCD take narrow tiles first; -1 = sized by the planner's cost model so that both
- * kinds finish together), "launch_mode" (0 = one kernel runs both kinds of tiles on separate compute units,
+ * kinds finish together), "wave_tiles" (-1 = narrow tiles of at most 384 keys run one per wave, eight to a claim, when the launch has at
+ * least six such tiles per workgroup; 0 = never; 1 = whenever there is such a tile), "launch_mode" (0 = one kernel runs both kinds of tiles on separate compute units,
  * 1 = a step that holds both kinds runs as two kernels resident side by side on every compute unit -- row-block
  * tiles on the caller's stream, narrow tiles on a stream of the context's own, joined before the call's work ends
  * -- 2 = the two specialised kernels also for steps of one kind), "timing" (1 = record HIP

@@ -139,8 +139,8 @@ hipError_t static_scratch_address(int device, unsigned char** out) {
 // Zeroes the queue cursors and the finished-workgroup counts of a counter block (not the sticky error flags).  A
 // kernel rather than a memset: a memset node recorded into a captured graph has replayed wrongly on this platform.
 __global__ void ppd_clear_counters_kernel(uint32_t* counters) {
-    const int i = threadIdx.x;
-    if (i == 10 || i == 11 || (i >= ppd::kCursorBase && i < ppd::kCounterWords)) counters[i] = 0u;
+    for (int i = threadIdx.x; i < ppd::kCounterWords; i += blockDim.x)
+        if (i == 10 || i == 11 || i >= ppd::kCursorBase) counters[i] = 0u;
 }
 
 ppd_status mixed_attention_impl(ppd_ctx* ctx, const void* q, const void* kv_pages, const int32_t* page_tables,
@@ -173,7 +173,9 @@ ppd_status mixed_attention_impl(ppd_ctx* ctx, const void* q, const void* kv_page
     const char* msg = "";
     ppd_status st = PPD_OK;
     const int where = use_static ? 2 : 1;
-    const bool same_opts = std::memcmp(&ctx->plan_opts, &ctx->opts, sizeof(ppd::PlanOptions)) == 0;
+    ppd::PlanOptions opts = ctx->opts;
+    if (ctx->launch_mode != 0) opts.wave_tiles = 0;  // the specialised kernels run every narrow tile on four waves
+    const bool same_opts = std::memcmp(&ctx->plan_opts, &opts, sizeof(ppd::PlanOptions)) == 0;
     const bool reuse = ctx->plan_on_device && ctx->plan_where == where && same_opts &&
                        (!use_static || g_scratch_owner[ctx->device] == ctx) && (int32_t)ctx->plan_L.size() == B &&
                        std::memcmp(ctx->plan_L.data(), L, sizeof(int32_t) * B) == 0 &&
@@ -191,7 +193,7 @@ ppd_status mixed_attention_impl(ppd_ctx* ctx, const void* q, const void* kv_page
     const auto t_plan0 = std::chrono::steady_clock::now();
     if (!reuse) {
         ctx->plan_on_device = false;
-        st = ppd::build_plan(ctx->shape, L, n, B, ctx->opts, &ctx->plan, &msg);
+        st = ppd::build_plan(ctx->shape, L, n, B, opts, &ctx->plan, &msg);
         if (st != PPD_OK) return fail(ctx, st, msg);
     }
 
@@ -199,7 +201,8 @@ ppd_status mixed_attention_impl(ppd_ctx* ctx, const void* q, const void* kv_page
     const size_t items_bytes = plan.items.size() * sizeof(ppd_work_item);
     const size_t groups_bytes = plan.groups.size() * sizeof(ppd::MergeGroup);
     const size_t units_bytes = plan.units.size() * sizeof(ppd::MergeUnit);
-    const size_t total = items_bytes + groups_bytes + units_bytes;
+    const size_t bounds_bytes = sizeof plan.queue_begin;  // the queues' bounds travel behind the tables
+    const size_t total = items_bytes + groups_bytes + units_bytes + bounds_bytes;
     unsigned char* sbase = nullptr;
     if (use_static) {
         PPD_HIP(ctx, static_scratch_address(ctx->device, &sbase));
@@ -260,6 +263,7 @@ ppd_status mixed_attention_impl(ppd_ctx* ctx, const void* q, const void* kv_page
             std::memcpy(static_cast<char*>(host) + items_bytes, plan.groups.data(), groups_bytes);
             std::memcpy(static_cast<char*>(host) + items_bytes + groups_bytes, plan.units.data(), units_bytes);
         }
+        std::memcpy(static_cast<char*>(host) + total - bounds_bytes, plan.queue_begin, bounds_bytes);
         PPD_HIP(ctx, hipMemcpyAsync(use_static ? d_plan : ctx->d_items, host, total, hipMemcpyHostToDevice, hs));
         PPD_HIP(ctx, hipEventRecord(done, hs));
         if (use_static) {
@@ -268,7 +272,7 @@ ppd_status mixed_attention_impl(ppd_ctx* ctx, const void* q, const void* kv_page
         }
         ctx->plan_L.assign(L, L + B);
         ctx->plan_n.assign(n, n + B);
-        ctx->plan_opts = ctx->opts;
+        ctx->plan_opts = opts;
         ctx->plan_on_device = true;
         ctx->plan_where = where;
         ctx->plan.stats.plan_host_us = (int32_t)std::chrono::duration_cast<std::chrono::microseconds>(
@@ -296,7 +300,7 @@ ppd_status mixed_attention_impl(ppd_ctx* ctx, const void* q, const void* kv_page
     kp.num_pages = ctx->shape.num_pages;
     kp.page_stride = 2LL * ctx->shape.num_kv_heads * ppd::kPage * ctx->shape.head_dim;
     kp.n_items = (int32_t)plan.items.size();
-    std::memcpy(kp.queue_begin, plan.queue_begin, sizeof kp.queue_begin);
+    kp.queue_begin = reinterpret_cast<const int32_t*>(static_cast<const char*>(d_plan) + total - bounds_bytes);
     kp.pref_mode = ctx->opts.pref_mode;
     kp.narrow_cus = plan.narrow_cus;
     kp.max_pages = max_pages;
@@ -489,6 +493,9 @@ ppd_status ppd_set_option(ppd_ctx* ctx, const char* key, int64_t value) {
     } else if (k == "narrow_cus") {
         if (value < -1 || value > 32) return fail(ctx, PPD_ERR_RANGE, "narrow_cus must be in [-1, 32]");
         ctx->opts.narrow_cus = (int32_t)value;
+    } else if (k == "wave_tiles") {
+        if (value < -1 || value > 1) return fail(ctx, PPD_ERR_RANGE, "wave_tiles must be -1, 0 or 1");
+        ctx->opts.wave_tiles = (int32_t)value;
     } else if (k == "launch_mode") {
         if (value < 0 || value > 2) return fail(ctx, PPD_ERR_RANGE, "launch_mode must be in [0, 2]");
         ctx->launch_mode = (int)value;

@@ -38,13 +38,26 @@ constexpr int kStreamThreads = 64 * kStreamWaves;
 #endif
 constexpr int kStreamKSets = PPD_STREAM_KSETS;
 constexpr int kStreamVSets = PPD_STREAM_VSETS;
+constexpr int kXcds = 8;             // MFMA tile queues, one per XCD (each XCD has its own L2)
+constexpr int kNarrowQueue = kXcds;  // index of the narrow-tile queue
+// Very short narrow tiles of a launch that has very many of them are handed out kWaves at a time (one claim), each
+// wave running one tile on its own: no combine through LDS, no barrier, and the fixed costs of a tile (claim, work
+// item, page ids, first loads) overlap across the eight tiles instead of adding up.  Only worth it while a tile is
+// far shorter than the launch: a wave alone streams slowly, so long tiles would stretch the end of the launch.
+constexpr int kWaveQueue = kXcds + 1;       // index of that queue; a claim covers kWaves consecutive tiles
+constexpr int kQueues = kXcds + 2;
+constexpr int kCursors = kQueues;           // one cursor per queue
+#ifndef PPD_WAVE_TILE_KEYS
+#define PPD_WAVE_TILE_KEYS 384
+#endif
+constexpr int kWaveTileKeys = PPD_WAVE_TILE_KEYS;  // a narrow tile of at most this many keys may run on one wave
 // Device counters of a context: 64 words of flags (word 9: sticky error flags; words 10 and 11: finished
-// workgroups of the mixed / row-block kernel and of the stream kernel), then the nine queue cursors, each in a
+// workgroups of the mixed / row-block kernel and of the stream kernel), then the queue cursors, each in a
 // 128-byte line of its own (claims on different queues then do not queue up behind one another at one address
 // range of the memory side, where device-scope atomics execute).
 constexpr int kCursorBase = 64;    // word index of cursor 0
 constexpr int kCursorStride = 32;  // words between cursors
-constexpr int kCounterWords = kCursorBase + 9 * kCursorStride;
+constexpr int kCounterWords = kCursorBase + kCursors * kCursorStride;
 constexpr int kMergeCols = 16;     // columns of a merge group one block of the merge kernel takes
 
 // One merge group: a row block whose key range was split over `nsplit` tiles with consecutive partials.
@@ -63,11 +76,8 @@ struct MergeUnit {
     int32_t col0;
 };
 
-constexpr int kXcds = 8;             // MFMA tile queues, one per XCD (each XCD has its own L2)
-constexpr int kNarrowQueue = kXcds;  // index of the narrow-tile queue
-
 struct Plan {
-    int32_t queue_begin[kXcds + 2];  // items [queue_begin[q], queue_begin[q+1]) belong to queue q
+    int32_t queue_begin[kQueues + 1];  // items [queue_begin[q], queue_begin[q+1]) belong to queue q
     int32_t narrow_cus = 16;         // of the 32 compute units of an XCD, how many take narrow tiles first
     std::vector<ppd_work_item> items;
     std::vector<MergeGroup> groups;
@@ -83,6 +93,7 @@ struct PlanOptions {
     int32_t num_cus = 256;
     int32_t pref_mode = 2;
     int32_t narrow_cus = -1;  // -1: from the cost model
+    int32_t wave_tiles = -1;  // -1: short narrow tiles run one per wave when the launch has enough of them; 0 never; 1 always
 };
 
 // Returns PPD_OK or an error code with a message in `err` (may be null).
@@ -99,7 +110,7 @@ struct KParams {
     const ppd_work_item* items;
     float* partials;
     uint32_t* counters;   // [9] sticky error flags, [10], [11] finished workgroups; queue cursors from kCursorBase on
-    int32_t queue_begin[kXcds + 2];
+    const int32_t* queue_begin;  // device: kQueues + 1 bounds, uploaded behind the plan's tables
     int64_t num_pages;
     int64_t page_stride;  // elements per page = 2 * Hkv * 16 * D
     int32_t n_items;

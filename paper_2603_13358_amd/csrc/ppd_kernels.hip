@@ -569,8 +569,11 @@ struct NarrowCombine {
     static constexpr size_t bytes(int head_dim) { return (size_t)NW * CB * (head_dim + 2) * sizeof(float); }
 };
 
-template <int HD, int NW, int NK, int NV>
+// SOLO: the calling wave runs the whole tile on its own (NW = 1): no LDS, no barrier, the result is written from the
+// accumulator registers; the other waves of the workgroup run other tiles at the same time.
+template <int HD, int NW, int NK, int NV, bool SOLO = false>
 __device__ __forceinline__ void narrow_item(const KParams& P, const ppd_work_item& it, char* smem) {
+    static_assert(!SOLO || NW == 1, "a solo tile is one wave");
     constexpr int KS = HD / 32;   // k-steps of S^T
     constexpr int DBN = HD / 16;  // 16-row d blocks of O^T
     constexpr int CB = NarrowCombine<NW>::CB;
@@ -579,7 +582,7 @@ __device__ __forceinline__ void narrow_item(const KParams& P, const ppd_work_ite
 
     const int tid = threadIdx.x;
     const int lane = tid & 63;
-    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int wave = SOLO ? 0 : __builtin_amdgcn_readfirstlane(tid >> 6);
     const int c16 = lane & 15;
     const int g4 = lane >> 4;
     const int G = P.G;
@@ -725,6 +728,32 @@ __device__ __forceinline__ void narrow_item(const KParams& P, const ppd_work_ite
     l_run += xor_shuffle(l_run, 16);
     l_run = sum_halves(l_run);
 
+    if constexpr (SOLO) {
+        // O^T register i of block db is d = db*16 + 4*g4 + i of column c16; m and l are the column's in every lane
+        if (c16 < ncols) {
+            if (it.part_off < 0) {
+                const float inv = 1.f / l_run;
+                uint16_t* op = P.out + ((int64_t)(it.grow0 + jrow) * P.Hq + head) * HD + 4 * g4;
+#pragma unroll
+                for (int db = 0; db < DBN; ++db) {
+                    u32x2 w;
+                    w[0] = pack_bf16(oacc[db][0] * inv, oacc[db][1] * inv);
+                    w[1] = pack_bf16(oacc[db][2] * inv, oacc[db][3] * inv);
+                    *reinterpret_cast<u32x2*>(op + db * 16) = w;
+                }
+            } else {
+                float* pp = P.partials + it.part_off;
+#pragma unroll
+                for (int db = 0; db < DBN; ++db)
+                    *reinterpret_cast<f32x4*>(pp + (int64_t)c16 * HD + db * 16 + 4 * g4) = oacc[db];
+                if (g4 == 0) {
+                    pp[(int64_t)ncols * HD + c16 * 2] = m_run;
+                    pp[(int64_t)ncols * HD + c16 * 2 + 1] = l_run;
+                }
+            }
+        }
+        return;
+    }
     // combine the waves, CB columns per pass: O^T register i of block db is d = db*16 + 4*g4 + i of column c16
     float* wbuf = reinterpret_cast<float*>(smem) + wave * WSTRIDE;
     const float* all = reinterpret_cast<const float*>(smem);
@@ -775,9 +804,10 @@ __device__ __forceinline__ void narrow_item(const KParams& P, const ppd_work_ite
     }
 }
 
-// Claims the next tile of queue q: its index in the work list, or -1 when the queue is exhausted.
+// Claims the next tile of queue q: its index in the work list, or -1 when the queue is exhausted.  A claim on the
+// wave-tile queue covers kWaves consecutive tiles and returns the index of the first.
 __device__ __forceinline__ int claim_from(const KParams& P, int q) {
-    const int got = (int)atomicAdd(&P.counters[kCursorBase + q * kCursorStride], 1u);
+    const int got = (int)atomicAdd(&P.counters[kCursorBase + q * kCursorStride], 1u) * (q == kWaveQueue ? kWaves : 1);
     return got < P.queue_begin[q + 1] - P.queue_begin[q] ? P.queue_begin[q] + got : -1;
 }
 
@@ -801,9 +831,10 @@ __global__ __launch_bounds__(kThreads, 2) void ppd_mixed_kernel(const KParams P)
     __shared__ int s_next_slot;
     volatile int* s_next = &s_next_slot;
     const int tid = threadIdx.x;
-    // Nine queues in one list: MFMA row-block tiles in eight queues, one per XCD (tiles that read the same K/V
+    // Ten queues in one list: MFMA row-block tiles in eight queues, one per XCD (tiles that read the same K/V
     // sit in the same queue, next to each other, so the workgroups of one XCD find them in their L2), and one
-    // queue of narrow tiles; each longest tile first.  A workgroup prefers one kind, chosen by the compute
+    // queue of narrow tiles run by the whole workgroup and one of short narrow tiles run one per wave; each longest tile
+    // first.  A workgroup prefers one kind, chosen by the compute
     // unit it runs on (narrow_cus of the 32 units of every XCD take narrow tiles, spread evenly over the shader
     // engines; the planner sizes the split so that both kinds finish together): workgroups that share a unit
     // then run the same kind, and HBM-bound and MFMA-bound tiles run side by side on different units.
@@ -829,16 +860,17 @@ __global__ __launch_bounds__(kThreads, 2) void ppd_mixed_kernel(const KParams P)
     // that chain used to be the last ~10 us of every workgroup, and so of every launch.
     unsigned dry = 0;
 #pragma unroll
-    for (int q = 0; q <= kNarrowQueue; ++q)
+    for (int q = 0; q < kQueues; ++q)
         if (P.queue_begin[q + 1] == P.queue_begin[q]) dry |= 1u << q;
+    constexpr unsigned kAllDry = (1u << kQueues) - 1;
     auto look_at_cursors = [&]() {
-        unsigned cur[kNarrowQueue + 1];
+        unsigned cur[kQueues];
 #pragma unroll
-        for (int q = 0; q <= kNarrowQueue; ++q)
+        for (int q = 0; q < kQueues; ++q)
             cur[q] = __hip_atomic_load(&P.counters[kCursorBase + q * kCursorStride], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 #pragma unroll
-        for (int q = 0; q <= kNarrowQueue; ++q)
-            if ((int)cur[q] >= P.queue_begin[q + 1] - P.queue_begin[q]) dry |= 1u << q;
+        for (int q = 0; q < kQueues; ++q)
+            if ((int)(cur[q] * (q == kWaveQueue ? kWaves : 1)) >= P.queue_begin[q + 1] - P.queue_begin[q]) dry |= 1u << q;
     };
     for (;;) {
         if (tid == 0) {
@@ -847,11 +879,13 @@ __global__ __launch_bounds__(kThreads, 2) void ppd_mixed_kernel(const KParams P)
             for (int attempt = 0; attempt < 2 && idx < 0; ++attempt) {
                 const bool want_narrow = (attempt == 0) == (pref == 1);
                 if (want_narrow) {
-                    if (!(dry & (1u << kNarrowQueue))) {
-                        idx = claim_from(P, kNarrowQueue);
+                    // whole-workgroup tiles first (the long ones), then the very short ones, eight to a claim
+                    for (int q = kNarrowQueue; q <= kWaveQueue && idx < 0; ++q) {
+                        if (dry & (1u << q)) continue;
+                        idx = claim_from(P, q);
                         if (idx < 0) {
-                            dry |= 1u << kNarrowQueue;
-                            if (dry != (2u << kNarrowQueue) - 1) look_at_cursors();
+                            dry |= 1u << q;
+                            if (dry != kAllDry) look_at_cursors();
                         }
                     }
                 } else {
@@ -861,7 +895,7 @@ __global__ __launch_bounds__(kThreads, 2) void ppd_mixed_kernel(const KParams P)
                         idx = claim_from(P, q);
                         if (idx < 0) {
                             dry |= 1u << q;
-                            if (dry != (2u << kNarrowQueue) - 1) look_at_cursors();
+                            if (dry != kAllDry) look_at_cursors();
                         }
                     }
                 }
@@ -872,13 +906,22 @@ __global__ __launch_bounds__(kThreads, 2) void ppd_mixed_kernel(const KParams P)
         const int idx = __builtin_amdgcn_readfirstlane(*s_next);
         __syncthreads();  // everyone has read s_next, and the previous tile's LDS use is over
         if (idx < 0) break;
+        if (idx >= P.queue_begin[kWaveQueue]) {
+            // a claim on the wave-tile queue: wave w runs tile idx + w on its own
+            const int mine = idx + __builtin_amdgcn_readfirstlane(tid >> 6);
+            if (mine < P.queue_begin[kQueues]) {
+                const ppd_work_item it = P.items[mine];
+                narrow_item<HD, 1, 4, 4, true>(P, it, smem);
+            }
+            continue;
+        }
         const ppd_work_item it = P.items[idx];
         if (it.kind == 0)
             narrow_item<HD, kWaves, 4, 4>(P, it, smem);
         else
             mfma_item<HD, false>(P, it, smem);
     }
-    if (tid == 0) rearm_cursors(P, 0, kNarrowQueue + 1, 10);
+    if (tid == 0) rearm_cursors(P, 0, kCursors, 10);
 }
 
 // ---------------------------------------------------------------------------------------------------

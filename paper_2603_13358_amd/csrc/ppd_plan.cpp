@@ -104,13 +104,18 @@ static int64_t choose_mfma_chunk(const std::vector<RowBlock>& blocks, int G, int
         // the workgroups that take MFMA tiles first, as the launch will split them
         const int S = std::max(1, slots - narrow_units(narrow_bytes, iters) * slots / 32);
         std::sort(tiles.begin(), tiles.end(), std::greater<double>());
-        load.assign((size_t)S, 0.0);  // min-heap of workgroup finish times
-        auto later = [](double a, double b) { return a > b; };
+        load.assign((size_t)S, 0.0);  // min-heap of workgroup finish times; the earliest workgroup takes the next tile
         for (double t : tiles)
             for (int h = 0; h < Hkv; ++h) {
-                std::pop_heap(load.begin(), load.end(), later);
-                load.back() += t;
-                std::push_heap(load.begin(), load.end(), later);
+                load[0] += t;
+                for (size_t at = 0;;) {  // sift the grown root down
+                    size_t kid = 2 * at + 1;
+                    if (kid >= (size_t)S) break;
+                    if (kid + 1 < (size_t)S && load[kid + 1] < load[kid]) ++kid;
+                    if (load[at] <= load[kid]) break;
+                    std::swap(load[at], load[kid]);
+                    at = kid;
+                }
             }
         const double makespan = *std::max_element(load.begin(), load.end());
         const double even = std::max((mfma_work + narrow_work) / slots, narrow_floor);
@@ -239,6 +244,7 @@ ppd_status build_plan(const ppd_shape& s, const int32_t* L, const int32_t* n, in
 
     struct Keyed { double cost; ppd_work_item it; };
     std::vector<Keyed> keyed;
+    keyed.reserve((row_blocks.size() + narrow_lengths.size()) * (size_t)Hkv);
     std::vector<int32_t> bounds;
     int64_t part_floats = 0;
     int64_t grow = 0;
@@ -347,12 +353,27 @@ ppd_status build_plan(const ppd_shape& s, const int32_t* L, const int32_t* n, in
         plan->queue_begin[q] = (int32_t)plan->items.size();
         for (auto& it : queues[q]) plan->items.push_back(it);
     }
-    plan->queue_begin[kNarrowQueue] = (int32_t)plan->items.size();
-    for (auto& k : narrow_items) {
-        k.it.queue = kNarrowQueue;
-        plan->items.push_back(k.it);
+    // Narrow tiles, longest first.  The short ones at the end of the list form the wave-tile queue when there are
+    // enough of them to keep the waves of every workgroup busy (then eight tiles share the fixed cost of one); with
+    // fewer, eight waves per tile keep more compute units streaming.
+    size_t wave_from = narrow_items.size();
+    if (o.wave_tiles != 0 && o.force_kind != 1) {
+        size_t first_short = 0;
+        while (first_short < narrow_items.size() &&
+               narrow_items[first_short].it.kv_end - narrow_items[first_short].it.kv_begin > kWaveTileKeys)
+            ++first_short;
+        const size_t n_short = narrow_items.size() - first_short;
+        // (by the chip's workgroup slots, not by a grid override: that option must stay scheduling only)
+        if (n_short > 0 && (o.wave_tiles == 1 || n_short >= (size_t)6 * (size_t)(kWgPerCu * o.num_cus))) wave_from = first_short;
     }
-    plan->queue_begin[kNarrowQueue + 1] = (int32_t)plan->items.size();
+    plan->queue_begin[kNarrowQueue] = (int32_t)plan->items.size();
+    for (size_t k = 0; k < narrow_items.size(); ++k) {
+        if (k == wave_from) plan->queue_begin[kWaveQueue] = (int32_t)plan->items.size();
+        narrow_items[k].it.queue = k < wave_from ? kNarrowQueue : kWaveQueue;
+        plan->items.push_back(narrow_items[k].it);
+    }
+    if (wave_from == narrow_items.size()) plan->queue_begin[kWaveQueue] = (int32_t)plan->items.size();
+    plan->queue_begin[kQueues] = (int32_t)plan->items.size();
 
     // Split of the compute units between the two kinds when both are present (see narrow_units).
     {
@@ -376,7 +397,9 @@ ppd_status build_plan(const ppd_shape& s, const int32_t* L, const int32_t* n, in
     st.flops = flops;
     st.narrow_chunk = (int32_t)narrow_chunk;
     st.mfma_chunk = (int32_t)mfma_chunk;
-    st.grid = (int32_t)std::max<int64_t>(1, std::min<int64_t>(slots, st.n_items));
+    // a workgroup's eight waves take eight wave tiles at a time
+    const int64_t wave_groups = (plan->queue_begin[kQueues] - plan->queue_begin[kWaveQueue] + kWaves - 1) / kWaves;
+    st.grid = (int32_t)std::max<int64_t>(1, std::min<int64_t>(slots, plan->queue_begin[kWaveQueue] + wave_groups));
     return PPD_OK;
 }
 

@@ -91,6 +91,33 @@ def test_resident_pair_of_kernels_matches_oracle(mode, shape):
         assert np.array_equal(out, again), "not deterministic"
 
 
+@pytest.mark.parametrize("shape", [(32, 8, 128), (64, 8, 128), (8, 2, 64), (40, 8, 128), (6, 6, 64)])
+def test_wave_tiles_match_oracle(shape):
+    """Option wave_tiles = 1: narrow tiles of at most 384 keys run one per wave, eight to a claim (no combine through
+    LDS, output straight from the accumulators): decode rows of lengths around page and claim boundaries, multi-row
+    narrow tiles, a count that is no multiple of eight, longer tiles and an append-prefill beside them, and split
+    ranges whose short pieces write partials."""
+    Hq, Hkv, D = shape
+    L = [1, 15, 16, 17, 255, 256, 382, 383, 384, 300, 3, 64, 2000, 5000, 333, 90, 0, 400]
+    n = [1, 1, 1, 1, 1, 1, 1, 1, 1, 2, 1, 1, 1, 1, 1, 1, 1, 70]
+    b = si.make_batch("wave", L=L, n=n, Hq=Hq, Hkv=Hkv, D=D, seed=33, slack_pages=3)
+    out, stats = _compare(b, options={"wave_tiles": 1})
+    base, _ = _compare(b, options={"wave_tiles": 0})
+    check_close(bits_to_f32(out), bits_to_f32(base), max_abs=2e-2, rel=1e-2)
+    again, _ = _compare(b, options={"wave_tiles": 1})
+    assert np.array_equal(out, again), "not deterministic"
+    _compare(b, options={"wave_tiles": 1, "narrow_chunk": 512, "mfma_chunk": 512, "grid": 3})
+
+
+def test_wave_tiles_chosen_automatically_for_large_decode_batches():
+    """2048 short decode tiles (256 sequences x 8 KV heads): the planner picks the wave queue by itself."""
+    rng = np.random.default_rng(8)
+    b = si.make_batch("wave_auto", L=rng.integers(1, 380, size=256), n=np.ones(256, np.int64), Hq=16, Hkv=8, D=128,
+                      seed=34, slack_pages=5)
+    out, stats = _compare(b)
+    assert stats["grid"] == 256 and stats["n_narrow"] == 2048
+
+
 def test_resident_pair_only_one_kind_present():
     """launch_mode 2 with batches of one kind: each specialised kernel alone, no fork to the side stream."""
     dec = si.make_batch("pair_dec", L=[900, 17, 4000, 0, 2047, 2048, 2049], n=[1, 1, 1, 1, 1, 2, 1], Hq=32, Hkv=8,

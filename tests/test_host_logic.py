@@ -104,7 +104,7 @@ def test_plan_covers_every_pair_once(opts):
         # (same sequence, KV head and key range) sit in one queue, next to each other
         queues = [t.queue for t in items]
         assert queues == sorted(queues)
-        assert all((t.kind == 0) == (t.queue == 8) for t in items)
+        assert all((t.kind == 0) == (t.queue in (8, 9)) for t in items)
         lens = [t.kv_end - t.kv_begin for t in items if t.kind == 0]
         assert lens == sorted(lens, reverse=True)
         seen, last = set(), None
@@ -121,6 +121,27 @@ def test_plan_covers_every_pair_once(opts):
         assert abs(st.flops - b.attention_flops()) <= 1e-9 * st.flops
         assert st.kv_bytes_tiles >= st.kv_bytes - 1
         assert 1 <= st.grid <= max(1, st.n_items)
+
+
+def test_short_narrow_tiles_form_the_wave_queue_when_there_are_many():
+    """Narrow tiles of at most 384 keys go to queue 9 (one tile per wave, eight to a claim) once the launch has six
+    of them per workgroup; they stay the tail of the longest-first narrow list, and the rest of the plan is as before."""
+    rng = np.random.default_rng(5)
+    L = np.concatenate([rng.integers(1, 380, size=40), rng.integers(1500, 6000, size=6), [300, 5000]])
+    n = np.concatenate([np.ones(46, np.int64), [70, 200]])
+    for num_cus, expect_wave in ((4, True), (256, False)):
+        items, st = ppd.ppd_plan_build(16, 2, 128, 16, 1 << 20, L, n, num_cus=num_cus)
+        replay(items, L, n, 2, 8, 128)
+        wave = [t for t in items if t.queue == 9]
+        assert bool(wave) == expect_wave
+        assert all(t.kind == 0 and t.kv_end - t.kv_begin <= 384 for t in wave)
+        assert all(t.kv_end - t.kv_begin > 384 for t in items if t.queue == 8) or not wave
+        queues = [t.queue for t in items]
+        assert queues == sorted(queues)
+        lens = [t.kv_end - t.kv_begin for t in items if t.kind == 0]
+        assert lens == sorted(lens, reverse=True)
+        if wave:
+            assert len(wave) >= 80 and st.grid <= 4
 
 
 def test_plan_of_random_batches_covers_every_pair_once():
