@@ -31,6 +31,10 @@
  *    captured into a HIP graph and replayed (the kernels reset their own queue cursors; no memset nodes); with the
  *    option "timing" set, events are recorded as well, so leave it off under capture.
  *  - One context serves one stream at a time.  Calls on a context are not thread-safe.
+ *  - Debugging aids, read from the environment by ppd_create: PPD_LOG=1 prints one line per call on stderr (batch
+ *    size, tiles of each kind, split sizes, grid, whether the plan was reused); PPD_DEBUG_SLOTS=1 makes every append
+ *    look for duplicate slots within the call (two more small launches and a bitmap of one bit per pool slot) and
+ *    raises device error flag bit 2 when it finds one.
  *
  * Page pool layout (bf16 elements; P = 16 tokens per page; D = head_dim; Hkv = KV heads):
  *    page stride          S = 2 * Hkv * P * D
@@ -199,7 +203,8 @@ ppd_status ppd_plan_build(const ppd_shape *shape, const int32_t *L, const int32_
                           int32_t num_cus, ppd_work_item *items, int64_t capacity, ppd_plan_stats *stats);
 
 /* Synchronises `stream`, then returns and clears the sticky device error flags (bit 0: append slot out of
- * range, bit 1: page id out of range) in *flags. */
+ * range, bit 1: page id out of range, bit 2: duplicate slot within an append -- looked for only under
+ * PPD_DEBUG_SLOTS=1) in *flags. */
 ppd_status ppd_device_error_flags(ppd_ctx *ctx, void *stream, uint32_t *flags);
 
 /* With option "timing" set: waits for the mixed-attention kernel of the last ppd_mixed_attention call and

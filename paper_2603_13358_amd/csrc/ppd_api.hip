@@ -6,6 +6,7 @@
 #include <cstdint>
 #include <cstdio>
 #include <algorithm>
+#include <cstdlib>
 #include <cstring>
 #include <mutex>
 #include <string>
@@ -59,6 +60,9 @@ struct ppd_ctx {
     hipStream_t side_stream = nullptr;
     hipEvent_t ev_fork = nullptr, ev_join = nullptr;
     int launch_mode = 0;  // option "launch_mode"
+    // debugging aids switched on by environment variables read in ppd_create
+    bool log_calls = false;          // PPD_LOG=1: one line per call on stderr
+    uint32_t* d_slot_seen = nullptr;  // PPD_DEBUG_SLOTS=1: one bit per pool slot, to find duplicate slots of an append
     // pinned staging of the entry point that allocates nothing (fixed size, allocated with the context)
     void* static_staging = nullptr;
     hipEvent_t static_staging_done = nullptr;
@@ -141,6 +145,32 @@ hipError_t static_scratch_address(int device, unsigned char** out) {
 __global__ void ppd_clear_counters_kernel(uint32_t* counters) {
     for (int i = threadIdx.x; i < ppd::kCounterWords; i += blockDim.x)
         if (i == 10 || i == 11 || i >= ppd::kCursorBase) counters[i] = 0u;
+}
+
+// Debugging aid (PPD_DEBUG_SLOTS=1): marks every slot of an append in a bitmap; a bit found set already is a
+// duplicate slot within the call (error flag bit 2).  The second pass clears the bits again.
+__global__ void ppd_mark_slots_kernel(const int64_t* slots, int64_t T, int64_t pool_slots, uint32_t* seen, uint32_t* flags,
+                                      int clear) {
+    const int64_t t = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (t >= T) return;
+    const int64_t s = slots[t];
+    if (s < 0 || s >= pool_slots) return;
+    const uint32_t bit = 1u << (s & 31);
+    if (clear) {
+        atomicAnd(&seen[s >> 5], ~bit);
+    } else if (atomicOr(&seen[s >> 5], bit) & bit) {
+        atomicOr(flags, 4u);
+    }
+}
+
+// PPD_DEBUG_SLOTS=1: looks for duplicate slots among the T slots of an append (error flag bit 2), on `stream`.
+void check_duplicate_slots(ppd_ctx* ctx, const int64_t* slot_mapping, int64_t T, hipStream_t hs) {
+    if (!ctx->d_slot_seen || T <= 0) return;
+    const int64_t pool_slots = ctx->shape.num_pages * ppd::kPage;
+    const unsigned blocks = (unsigned)((T + 255) / 256);
+    for (int clear = 0; clear < 2; ++clear)
+        hipLaunchKernelGGL(ppd_mark_slots_kernel, dim3(blocks), dim3(256), 0, hs, slot_mapping, T, pool_slots, ctx->d_slot_seen,
+                           ctx->d_counters + 9, clear);
 }
 
 ppd_status mixed_attention_impl(ppd_ctx* ctx, const void* q, const void* kv_pages, const int32_t* page_tables,
@@ -377,6 +407,13 @@ ppd_status mixed_attention_impl(ppd_ctx* ctx, const void* q, const void* kv_page
         rc = ppd::launch_merge(mp, stream);
         if (rc != 0) return hip_fail(ctx, (hipError_t)rc, "launch merge");
     }
+    if (ctx->log_calls)
+        std::fprintf(stderr, "ppd: mixed_attention%s B=%d tiles=%lld (narrow %lld of which one-wave %d, row-block %lld) merge groups=%lld "
+                             "chunks=%d/%d grid=%d launch_mode=%d plan=%s (%d us)\n",
+                     use_static ? "_static" : "", (int)B, (long long)plan.stats.n_items, (long long)plan.stats.n_narrow,
+                     (int)(plan.queue_begin[ppd::kQueues] - plan.queue_begin[ppd::kWaveQueue]), (long long)plan.stats.n_mfma,
+                     (long long)plan.stats.n_groups, (int)plan.stats.narrow_chunk, (int)plan.stats.mfma_chunk, (int)plan.stats.grid,
+                     mode, reuse ? "reused" : "built", (int)plan.stats.plan_host_us);
     return PPD_OK;
 }
 
@@ -440,6 +477,14 @@ ppd_status ppd_create(const ppd_shape* shape, int32_t device, ppd_ctx** out) {
         return bail(e, "hipHostMalloc(static staging)");
     if ((e = hipEventCreateWithFlags(&ctx->static_staging_done, hipEventDisableTiming)) != hipSuccess)
         return bail(e, "hipEventCreate");
+    const char* env = std::getenv("PPD_LOG");
+    ctx->log_calls = env && env[0] == '1';
+    env = std::getenv("PPD_DEBUG_SLOTS");
+    if (env && env[0] == '1') {
+        const size_t words = (size_t)((shape->num_pages * ppd::kPage + 31) / 32);
+        if ((e = hipMalloc((void**)&ctx->d_slot_seen, words * sizeof(uint32_t))) != hipSuccess) return bail(e, "hipMalloc(slot bitmap)");
+        if ((e = hipMemset(ctx->d_slot_seen, 0, words * sizeof(uint32_t))) != hipSuccess) return bail(e, "hipMemset(slot bitmap)");
+    }
     *out = ctx;
     return PPD_OK;
 }
@@ -451,6 +496,7 @@ ppd_status ppd_destroy(ppd_ctx* ctx) {
     if (ctx->d_items) (void)hipFree(ctx->d_items);
     if (ctx->d_partials) (void)hipFree(ctx->d_partials);
     if (ctx->d_counters) (void)hipFree(ctx->d_counters);
+    if (ctx->d_slot_seen) (void)hipFree(ctx->d_slot_seen);
     for (auto& s : ctx->staging) {
         if (s.host) (void)hipHostFree(s.host);
         if (s.done) (void)hipEventDestroy(s.done);
@@ -521,6 +567,8 @@ ppd_status ppd_kv_append(ppd_ctx* ctx, const void* k, const void* v, void* kv_pa
                                    static_cast<uint16_t*>(kv_pages), slot_mapping, T, ctx->shape.num_kv_heads,
                                    ctx->shape.head_dim, ctx->shape.num_pages, 1, 0, ctx->d_counters + 9, stream);
     if (rc != 0) return hip_fail(ctx, (hipError_t)rc, "launch kv_append");
+    check_duplicate_slots(ctx, slot_mapping, T, static_cast<hipStream_t>(stream));
+    if (ctx->log_calls) std::fprintf(stderr, "ppd: kv_append T=%lld\n", (long long)T);
     return PPD_OK;
 }
 
@@ -544,6 +592,8 @@ ppd_status ppd_kv_land(ppd_ctx* ctx, const void* k, const void* v, void* kv_page
                                    ctx->shape.head_dim, ctx->shape.num_pages, num_layers, layer_stride_elems,
                                    ctx->d_counters + 9, stream);
     if (rc != 0) return hip_fail(ctx, (hipError_t)rc, "launch kv_land");
+    check_duplicate_slots(ctx, slot_mapping, T, static_cast<hipStream_t>(stream));
+    if (ctx->log_calls) std::fprintf(stderr, "ppd: kv_land T=%lld layers=%d\n", (long long)T, (int)num_layers);
     return PPD_OK;
 }
 

@@ -617,3 +617,39 @@ def test_measured_route_table_reproduces_the_papers_regime():
     centers = res["ratio_centers"]
     assert ppd.ppd_route_decide(table, centers, 3, 1024, 32, 9000, 8.0) == 1
     assert ppd.ppd_route_decide(table, centers, 1, 1024, 32, 9000, 8.0) == 0
+
+
+def test_debugging_aids_from_the_environment():
+    """PPD_LOG=1 prints one line per call; PPD_DEBUG_SLOTS=1 finds a duplicate slot within an append (flag bit 2) and
+    stays silent on a clean one.  Both are read by ppd_create, so the check runs in a process of its own."""
+    import os
+    import subprocess
+    import sys
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    code = r"""
+import sys
+sys.path.insert(0, %r); sys.path.insert(0, %r)
+import numpy as np, torch
+import paper_2603_13358_amd as ppd
+import synthetic_inputs as si
+from gpu_helpers import gpu_step, to_dev_u16
+b = si.cfg1_tiny(0)
+pool, out, stats, ctx = gpu_step(b, return_ctx=True)          # clean appends + one attention call
+assert ctx.device_error_flags() == 0
+dev = torch.device("cuda:0")
+k, v, slots = b.new_part()
+slots = slots.copy(); slots[5] = slots[9]                      # two tokens into one slot
+pool_d = torch.zeros(ctx.pool_elems(), dtype=torch.int16, device=dev)
+ctx.kv_append(to_dev_u16(k, torch, dev), to_dev_u16(v, torch, dev), pool_d, torch.from_numpy(slots).to(dev))
+flags = ctx.device_error_flags()
+assert flags == 4, flags
+ctx.kv_append(to_dev_u16(k, torch, dev), to_dev_u16(v, torch, dev), pool_d, torch.from_numpy(b.new_part()[2]).to(dev))
+assert ctx.device_error_flags() == 0                           # the bitmap was cleared again
+print("aids ok")
+""" % (root, os.path.join(root, "tests"))
+    env = dict(os.environ, PPD_LOG="1", PPD_DEBUG_SLOTS="1")
+    res = subprocess.run([sys.executable, "-c", code], stdout=subprocess.PIPE, stderr=subprocess.PIPE, text=True, env=env,
+                         timeout=300)
+    assert res.returncode == 0, res.stdout + res.stderr
+    assert "aids ok" in res.stdout
+    assert "ppd: kv_append T=" in res.stderr and "ppd: mixed_attention B=4 tiles=" in res.stderr
