@@ -19,9 +19,18 @@
  * i.e. inside a (page, head) block K keeps 8 consecutive d of one token together and is token-minor over
  * those 16-byte granules; V keeps 8 consecutive tokens of one d together.
  *
+ * FP8 pages (an extension beyond the paper, which keeps KV in 16-bit precision; nothing in the method changes):
+ * the same two layouts with one-byte elements holding OCP FP8 E4M3 codes (1 sign, 4 exponent bits of bias 7, 3
+ * mantissa bits; no infinities; S.1111.111 is NaN; largest finite value 448).  The append stores
+ * code = e4m3(x * (1 / scale)) -- product and reciprocal in binary32, rounded to the nearest code, ties to the
+ * even code, magnitudes beyond 448 saturating to 448 -- with one scale for K and one for V; attention reads
+ * K = value(code) * k_scale, V = value(code) * v_scale and is the definition above on those values.
+ *
  * Pins (tests/test_oracle_*.py): dense brute force from the un-paged token arrays, recompute-prefill
  * equivalence, n=1 == decode, page relabelling, chunking, closed forms, GQA replication, a library
- * softmax-attention routine on a contiguous case, sentinel check of the append.
+ * softmax-attention routine on a contiguous case, sentinel check of the append; for the FP8 codes: the format's
+ * landmark values, round trips of all codes, a library float8 conversion, and attention on a 16-bit pool that
+ * holds the decoded values.
  */
 #include <math.h>
 #include <stdint.h>
@@ -86,13 +95,89 @@ double ppd_oracle_transfer_delay(double n_tokens, double s_kv_bytes, double beta
     return d > 0.0 ? d : 0.0;
 }
 
+/* Value of an E4M3 code: (-1)^s * 2^(e-7) * (1 + m/8) for e > 0, (-1)^s * 2^-6 * (m/8) for e = 0. */
+double ppd_oracle_e4m3_value(uint8_t code) {
+    int sgn = code >> 7, e = (code >> 3) & 15, m = code & 7;
+    double mag;
+    if (e == 15 && m == 7) return NAN;
+    if (e == 0)
+        mag = ldexp((double)m / 8.0, -6);
+    else
+        mag = ldexp(1.0 + (double)m / 8.0, e - 7);
+    return sgn ? -mag : mag;
+}
+
+/* Code of a binary32 value: the finite code whose value is nearest, the even code on a tie, 448 for anything
+ * larger in magnitude (infinities included), the NaN code for NaN.  Plain search over the 127 magnitudes. */
+uint8_t ppd_oracle_e4m3_code(float y) {
+    uint8_t sgn = signbit(y) ? 0x80 : 0x00;
+    if (isnan(y)) return (uint8_t)(sgn | 0x7F);
+    double a = fabs((double)y);
+    int best = 0;
+    double best_err = INFINITY;
+    for (int c = 0; c <= 0x7E; ++c) {
+        double err = fabs(ppd_oracle_e4m3_value((uint8_t)c) - a);
+        if (err < best_err || (err == best_err && (c & 1) == 0)) {
+            best = c;
+            best_err = err;
+        }
+    }
+    return (uint8_t)(sgn | best);
+}
+
+static uint8_t quantise(uint16_t bf16_bits, float scale) {
+    uint32_t u = ((uint32_t)bf16_bits) << 16;
+    float x;
+    memcpy(&x, &u, sizeof x);
+    volatile float inv = 1.0f / scale; /* binary32 reciprocal, then one binary32 product */
+    volatile float y = x * inv;
+    return ppd_oracle_e4m3_code(y);
+}
+
+/* The append into FP8 pages: as ppd_oracle_kv_append, each element stored as its E4M3 code. */
+int ppd_oracle_kv_append_fp8(const uint16_t *k, const uint16_t *v, uint8_t *pool, const int64_t *slot_mapping,
+                             int64_t T, int Hkv, int D, int P, int64_t num_pages, float k_scale, float v_scale) {
+    for (int64_t t = 0; t < T; ++t) {
+        int64_t slot = slot_mapping[t];
+        if (slot < 0) continue;
+        int64_t page = slot / P;
+        int tok = (int)(slot % P);
+        if (page >= num_pages) return -1;
+        for (int h = 0; h < Hkv; ++h)
+            for (int d = 0; d < D; ++d) {
+                int64_t src = (t * Hkv + h) * D + d;
+                pool[k_index(page, h, tok, d, Hkv, D, P)] = quantise(k[src], k_scale);
+                pool[v_index(page, h, tok, d, Hkv, D, P)] = quantise(v[src], v_scale);
+            }
+    }
+    return 0;
+}
+
+int ppd_oracle_kv_land_fp8(const uint16_t *k, const uint16_t *v, uint8_t *pools, int64_t layer_stride, int layers,
+                           const int64_t *slot_mapping, int64_t T, int Hkv, int D, int P, int64_t num_pages,
+                           float k_scale, float v_scale) {
+    for (int l = 0; l < layers; ++l) {
+        int rc = ppd_oracle_kv_append_fp8(k + (int64_t)l * T * Hkv * D, v + (int64_t)l * T * Hkv * D,
+                                          pools + (int64_t)l * layer_stride, slot_mapping, T, Hkv, D, P, num_pages,
+                                          k_scale, v_scale);
+        if (rc != 0) return rc;
+    }
+    return 0;
+}
+
+/* Element `index` of a pool: a bf16 value, or for FP8 pages the code's value times the tensor's scale. */
+static double kv_value(const void *pool, int64_t index, int fp8, double scale) {
+    if (fp8) return ppd_oracle_e4m3_value(((const uint8_t *)pool)[index]) * scale;
+    return bf16_to_double(((const uint16_t *)pool)[index]);
+}
+
 /* Mixed-batch attention.  q, out: [T][Hq][D] with the rows of sequence i starting at sum_{j<i} n_j.
  * row_mask (may be NULL): compute only rows with row_mask[r] != 0, leave the others untouched.
  * out is fp32 (rounded once from the double result).  Returns 0, or a negative code for an invalid
  * page-table entry. */
-int ppd_oracle_mixed_attention(const uint16_t *q, const uint16_t *pool, const int32_t *page_tables,
-                               int max_pages, const int32_t *L, const int32_t *n, int B, int Hq, int Hkv, int D,
-                               int P, int64_t num_pages, float scale, const uint8_t *row_mask, float *out) {
+static int attention(const uint16_t *q, const void *pool, int fp8, double k_scale, double v_scale,
+                     const int32_t *page_tables, int max_pages, const int32_t *L, const int32_t *n, int B, int Hq,
+                     int Hkv, int D, int P, int64_t num_pages, float scale, const uint8_t *row_mask, float *out) {
     int G = Hq / Hkv;
     int64_t T = 0;
     for (int i = 0; i < B; ++i) T += n[i];
@@ -124,7 +209,7 @@ int ppd_oracle_mixed_attention(const uint16_t *q, const uint16_t *pool, const in
                 if (page < 0 || page >= num_pages) { bad = 1; break; }
                 double dot = 0.0;
                 for (int d = 0; d < D; ++d)
-                    dot += bf16_to_double(qv[d]) * bf16_to_double(pool[k_index(page, g, (int)(t % P), d, Hkv, D, P)]);
+                    dot += bf16_to_double(qv[d]) * kv_value(pool, k_index(page, g, (int)(t % P), d, Hkv, D, P), fp8, k_scale);
                 s[t] = (double)scale * dot;
                 if (s[t] > m) m = s[t];
             }
@@ -143,7 +228,7 @@ int ppd_oracle_mixed_attention(const uint16_t *q, const uint16_t *pool, const in
                 double acc = 0.0;
                 for (int64_t t = 0; t < visible; ++t) {
                     int32_t page = page_tables[(int64_t)i * max_pages + t / P];
-                    acc += s[t] * bf16_to_double(pool[v_index(page, g, (int)(t % P), d, Hkv, D, P)]);
+                    acc += s[t] * kv_value(pool, v_index(page, g, (int)(t % P), d, Hkv, D, P), fp8, v_scale);
                 }
                 out[(row * Hq + h) * D + d] = (float)(acc / l);
             }
@@ -152,4 +237,20 @@ int ppd_oracle_mixed_attention(const uint16_t *q, const uint16_t *pool, const in
     free(row_seq);
     free(row_j);
     return status;
+}
+
+int ppd_oracle_mixed_attention(const uint16_t *q, const uint16_t *pool, const int32_t *page_tables,
+                               int max_pages, const int32_t *L, const int32_t *n, int B, int Hq, int Hkv, int D,
+                               int P, int64_t num_pages, float scale, const uint8_t *row_mask, float *out) {
+    return attention(q, pool, 0, 1.0, 1.0, page_tables, max_pages, L, n, B, Hq, Hkv, D, P, num_pages, scale, row_mask,
+                     out);
+}
+
+/* The same on FP8 pages: K = value(code) * k_scale, V = value(code) * v_scale. */
+int ppd_oracle_mixed_attention_fp8(const uint16_t *q, const uint8_t *pool, float k_scale, float v_scale,
+                                   const int32_t *page_tables, int max_pages, const int32_t *L, const int32_t *n,
+                                   int B, int Hq, int Hkv, int D, int P, int64_t num_pages, float scale,
+                                   const uint8_t *row_mask, float *out) {
+    return attention(q, pool, 1, (double)k_scale, (double)v_scale, page_tables, max_pages, L, n, B, Hq, Hkv, D, P,
+                     num_pages, scale, row_mask, out);
 }
