@@ -130,6 +130,21 @@ const char *ppd_last_error(const ppd_ctx *ctx);
  * events on the call's stream right before and after the attention kernel(s), see ppd_last_kernel_ms). */
 ppd_status ppd_set_option(ppd_ctx *ctx, const char *key, int64_t value);
 
+/* Element format of the page pools a context works on.  PPD_KV_BF16 (the default) is the paper's setting: KV in
+ * 16-bit precision.  PPD_KV_FP8_E4M3 is an extension beyond the paper for the HBM-bound decode rows: the same two
+ * layouts with ONE-BYTE elements (every offset above counts elements; a page is Hkv*P*D*2 bytes, 32 KiB at 8 KV
+ * heads and D = 128) holding OCP FP8 E4M3 codes -- 1 sign, 4 exponent bits of bias 7, 3 mantissa bits, no
+ * infinities, S.1111.111 = NaN, largest finite magnitude 448 -- with one scale per tensor:
+ *   ppd_kv_append / ppd_kv_land store   code = e4m3(x * (1 / scale)), the reciprocal and the product in binary32,
+ *       rounded to the nearest code, ties to the even code, magnitudes from 448 on saturating to 448, NaN -> NaN code;
+ *   ppd_mixed_attention(_static) reads  K = value(code) * k_scale, V = value(code) * v_scale (every code's value is a
+ *       bf16 number, so the matrix cores see exact operands; k_scale multiplies the scores, v_scale the output).
+ * k, v, q and out stay bf16.  k_scale, v_scale: finite and > 0 (ignored for PPD_KV_BF16).  Takes effect from the next
+ * call on; pools written in one format must be read in the same.  Option "launch_mode" must be 0 with FP8 pages. */
+#define PPD_KV_BF16 0
+#define PPD_KV_FP8_E4M3 1
+ppd_status ppd_set_kv_format(ppd_ctx *ctx, int32_t format, float k_scale, float v_scale);
+
 /* Paged KV append (the KV-cache write of the step; paper sections 2.1 and 4.1: prefill populates the
  * cache, decode-side KV stays resident and grows with the context).
  *   k, v          device bf16 [T][Hkv][D], token-major, contiguous
@@ -137,7 +152,8 @@ ppd_status ppd_set_option(ppd_ctx *ctx, const char *key, int64_t value);
  *   slot_mapping  device int64 [T]; slot = page*P + offset; a negative slot skips the token; a slot beyond
  *                 the pool is skipped and raises device error flag bit 0; duplicate slots in one call are
  *                 a caller error (which copy wins is unspecified)
- * Pure 16-bit copies: the pool afterwards is bit-identical to the definition.  T = 0 is a no-op. */
+ * Pure 16-bit copies: the pool afterwards is bit-identical to the definition (FP8 pages: the codes are, see
+ * ppd_set_kv_format).  T = 0 is a no-op. */
 ppd_status ppd_kv_append(ppd_ctx *ctx, const void *k, const void *v, void *kv_pages,
                          const int64_t *slot_mapping, int64_t T, void *stream);
 

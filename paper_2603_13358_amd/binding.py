@@ -64,6 +64,7 @@ def load_library():
     lib.ppd_last_error.argtypes = [vp]
     lib.ppd_last_error.restype = ctypes.c_char_p
     lib.ppd_set_option.argtypes = [vp, ctypes.c_char_p, i64]
+    lib.ppd_set_kv_format.argtypes = [vp, i32, ctypes.c_float, ctypes.c_float]
     lib.ppd_kv_append.argtypes = [vp, vp, vp, vp, vp, i64, vp]
     lib.ppd_kv_land.argtypes = [vp, vp, vp, vp, i64, i32, vp, i64, vp]
     lib.ppd_transfer_delay_s.argtypes = [i64, i64, ctypes.c_double, ctypes.c_double]
@@ -131,6 +132,13 @@ def ppd_destroy(ctx):
 
 def ppd_set_option(ctx, key, value):
     _check(load_library().ppd_set_option(ctx, key.encode(), int(value)), ctx)
+
+
+PPD_KV_BF16, PPD_KV_FP8_E4M3 = 0, 1
+
+
+def ppd_set_kv_format(ctx, fmt, k_scale=1.0, v_scale=1.0):
+    _check(load_library().ppd_set_kv_format(ctx, int(fmt), float(k_scale), float(v_scale)), ctx)
 
 
 def ppd_kv_append(ctx, k, v, kv_pages, slot_mapping, T=None, stream=None):
@@ -279,6 +287,9 @@ class Context:
 
     def set_option(self, key, value):
         ppd_set_option(self.handle, key, value)
+
+    def set_kv_format(self, fmt, k_scale=1.0, v_scale=1.0):
+        ppd_set_kv_format(self.handle, fmt, k_scale, v_scale)
 
     def kv_append(self, k, v, kv_pages, slot_mapping, stream=None):
         ppd_kv_append(self.handle, k, v, kv_pages, slot_mapping, stream=stream)

@@ -60,6 +60,9 @@ struct ppd_ctx {
     hipStream_t side_stream = nullptr;
     hipEvent_t ev_fork = nullptr, ev_join = nullptr;
     int launch_mode = 0;  // option "launch_mode"
+    // element format of the pools (ppd_set_kv_format): FP8 E4M3 codes with one scale per tensor, or bf16
+    bool fp8_pages = false;
+    float k_scale = 1.f, v_scale = 1.f;
     // debugging aids switched on by environment variables read in ppd_create
     bool log_calls = false;          // PPD_LOG=1: one line per call on stderr
     uint32_t* d_slot_seen = nullptr;  // PPD_DEBUG_SLOTS=1: one bit per pool slot, to find duplicate slots of an append
@@ -203,8 +206,11 @@ ppd_status mixed_attention_impl(ppd_ctx* ctx, const void* q, const void* kv_page
     const char* msg = "";
     ppd_status st = PPD_OK;
     const int where = use_static ? 2 : 1;
+    if (ctx->fp8_pages && ctx->launch_mode != 0)
+        return fail(ctx, PPD_ERR_RANGE, "FP8 pages are read by the one-launch kernel only: set launch_mode to 0");
     ppd::PlanOptions opts = ctx->opts;
     if (ctx->launch_mode != 0) opts.wave_tiles = 0;  // the specialised kernels run every narrow tile on four waves
+    opts.kv_elem_bytes = ctx->fp8_pages ? 1 : 2;
     const bool same_opts = std::memcmp(&ctx->plan_opts, &opts, sizeof(ppd::PlanOptions)) == 0;
     const bool reuse = ctx->plan_on_device && ctx->plan_where == where && same_opts &&
                        (!use_static || g_scratch_owner[ctx->device] == ctx) && (int32_t)ctx->plan_L.size() == B &&
@@ -318,6 +324,7 @@ ppd_status mixed_attention_impl(ppd_ctx* ctx, const void* q, const void* kv_page
     // Masked scores are -inf and enter the exponent as s*c: keep c strictly positive so that scale = 0 gives
     // 2^(-inf) = 0 for masked keys and 2^(~0) = 1 for visible ones (identical to the exact result in fp32).
     float scale_log2e = scale * 1.4426950408889634f;
+    if (ctx->fp8_pages) scale_log2e = (float)((double)scale * (double)ctx->k_scale * 1.4426950408889634);
     if (scale_log2e < 1e-30f) scale_log2e = 1e-30f;
     ppd::KParams kp;
     kp.q = static_cast<const uint16_t*>(q);
@@ -339,6 +346,7 @@ ppd_status mixed_attention_impl(ppd_ctx* ctx, const void* q, const void* kv_page
     kp.G = G;
     kp.invG = 65536 / G + 1;
     kp.scale_log2e = scale_log2e;
+    kp.v_scale = ctx->fp8_pages ? ctx->v_scale : 1.f;
     // The static array is shared by every context of the process on this GPU and keeps the last call's contents:
     // the cursors and finished counts must start at zero whoever ran before.
     if (use_static)
@@ -359,7 +367,7 @@ ppd_status mixed_attention_impl(ppd_ctx* ctx, const void* q, const void* kv_page
     const int mode = ctx->launch_mode;
     int rc = 0;
     if (mode == 0 || (mode == 1 && !(has_narrow && has_mfma))) {
-        rc = ppd::launch_mixed(kp, D, plan.stats.grid, stream);
+        rc = ppd::launch_mixed(kp, D, plan.stats.grid, stream, ctx->fp8_pages);
         if (rc != 0) return hip_fail(ctx, (hipError_t)rc, "launch mixed attention");
     } else {
         // The co-resident pair: the row-block kernel on the caller's stream, the stream kernel beside it on the
@@ -404,13 +412,14 @@ ppd_status mixed_attention_impl(ppd_ctx* ctx, const void* q, const void* kv_page
         mp.invG = kp.invG;
         mp.D = D;
         mp.scale_log2e = scale_log2e;
+        mp.v_scale = kp.v_scale;
         rc = ppd::launch_merge(mp, stream);
         if (rc != 0) return hip_fail(ctx, (hipError_t)rc, "launch merge");
     }
     if (ctx->log_calls)
-        std::fprintf(stderr, "ppd: mixed_attention%s B=%d tiles=%lld (narrow %lld of which one-wave %d, row-block %lld) merge groups=%lld "
+        std::fprintf(stderr, "ppd: mixed_attention%s%s B=%d tiles=%lld (narrow %lld of which one-wave %d, row-block %lld) merge groups=%lld "
                              "chunks=%d/%d grid=%d launch_mode=%d plan=%s (%d us)\n",
-                     use_static ? "_static" : "", (int)B, (long long)plan.stats.n_items, (long long)plan.stats.n_narrow,
+                     use_static ? "_static" : "", ctx->fp8_pages ? " (FP8 pages)" : "", (int)B, (long long)plan.stats.n_items, (long long)plan.stats.n_narrow,
                      (int)(plan.queue_begin[ppd::kQueues] - plan.queue_begin[ppd::kWaveQueue]), (long long)plan.stats.n_mfma,
                      (long long)plan.stats.n_groups, (int)plan.stats.narrow_chunk, (int)plan.stats.mfma_chunk, (int)plan.stats.grid,
                      mode, reuse ? "reused" : "built", (int)plan.stats.plan_host_us);
@@ -554,6 +563,24 @@ ppd_status ppd_set_option(ppd_ctx* ctx, const char* key, int64_t value) {
     return PPD_OK;
 }
 
+ppd_status ppd_set_kv_format(ppd_ctx* ctx, int32_t format, float k_scale, float v_scale) {
+    if (!ctx) return PPD_ERR_NULL;
+    if (format != PPD_KV_BF16 && format != PPD_KV_FP8_E4M3)
+        return fail(ctx, PPD_ERR_RANGE, "format must be PPD_KV_BF16 or PPD_KV_FP8_E4M3");
+    if (format == PPD_KV_FP8_E4M3) {
+        if (!(k_scale > 0.f) || !(v_scale > 0.f) || !std::isfinite(k_scale) || !std::isfinite(v_scale) ||
+            !std::isfinite(1.0f / k_scale) || !std::isfinite(1.0f / v_scale))
+            return fail(ctx, PPD_ERR_RANGE, "k_scale and v_scale must be finite and > 0, and so must their reciprocals");
+        ctx->fp8_pages = true;
+        ctx->k_scale = k_scale;
+        ctx->v_scale = v_scale;
+    } else {
+        ctx->fp8_pages = false;
+        ctx->k_scale = ctx->v_scale = 1.f;
+    }
+    return PPD_OK;
+}
+
 ppd_status ppd_kv_append(ppd_ctx* ctx, const void* k, const void* v, void* kv_pages, const int64_t* slot_mapping,
                          int64_t T, void* stream) {
     if (!ctx) return PPD_ERR_NULL;
@@ -563,9 +590,10 @@ ppd_status ppd_kv_append(ppd_ctx* ctx, const void* k, const void* v, void* kv_pa
     if (!aligned16(k) || !aligned16(v) || !aligned16(kv_pages) || (reinterpret_cast<uintptr_t>(slot_mapping) & 7u))
         return fail(ctx, PPD_ERR_RANGE, "k / v / kv_pages must be 16-byte aligned, slot_mapping 8-byte aligned");
     PPD_HIP(ctx, hipSetDevice(ctx->device));
-    int rc = ppd::launch_kv_append(static_cast<const uint16_t*>(k), static_cast<const uint16_t*>(v),
-                                   static_cast<uint16_t*>(kv_pages), slot_mapping, T, ctx->shape.num_kv_heads,
-                                   ctx->shape.head_dim, ctx->shape.num_pages, 1, 0, ctx->d_counters + 9, stream);
+    int rc = ppd::launch_kv_append(static_cast<const uint16_t*>(k), static_cast<const uint16_t*>(v), kv_pages,
+                                   slot_mapping, T, ctx->shape.num_kv_heads, ctx->shape.head_dim, ctx->shape.num_pages,
+                                   1, 0, ctx->d_counters + 9, stream, ctx->fp8_pages, 1.0f / ctx->k_scale,
+                                   1.0f / ctx->v_scale);
     if (rc != 0) return hip_fail(ctx, (hipError_t)rc, "launch kv_append");
     check_duplicate_slots(ctx, slot_mapping, T, static_cast<hipStream_t>(stream));
     if (ctx->log_calls) std::fprintf(stderr, "ppd: kv_append T=%lld\n", (long long)T);
@@ -583,14 +611,15 @@ ppd_status ppd_kv_land(ppd_ctx* ctx, const void* k, const void* v, void* kv_page
     if (num_layers > 1 && layer_stride_elems < pool_elems)
         return fail(ctx, PPD_ERR_RANGE, "layer_stride_elems is smaller than one pool: layers would overlap");
     if (!aligned16(k) || !aligned16(v) || !aligned16(kv_pages) || (reinterpret_cast<uintptr_t>(slot_mapping) & 7u) ||
-        (num_layers > 1 && layer_stride_elems % 8 != 0))
+        (num_layers > 1 && layer_stride_elems % (ctx->fp8_pages ? 16 : 8) != 0))
         return fail(ctx, PPD_ERR_RANGE,
-                    "k / v / kv_pages must be 16-byte aligned (layer_stride_elems a multiple of 8), slot_mapping 8-byte aligned");
+                    "k / v / kv_pages must be 16-byte aligned (layer_stride_elems a multiple of 8, of 16 for FP8 pages), "
+                    "slot_mapping 8-byte aligned");
     PPD_HIP(ctx, hipSetDevice(ctx->device));
-    int rc = ppd::launch_kv_append(static_cast<const uint16_t*>(k), static_cast<const uint16_t*>(v),
-                                   static_cast<uint16_t*>(kv_pages), slot_mapping, T, ctx->shape.num_kv_heads,
-                                   ctx->shape.head_dim, ctx->shape.num_pages, num_layers, layer_stride_elems,
-                                   ctx->d_counters + 9, stream);
+    int rc = ppd::launch_kv_append(static_cast<const uint16_t*>(k), static_cast<const uint16_t*>(v), kv_pages,
+                                   slot_mapping, T, ctx->shape.num_kv_heads, ctx->shape.head_dim, ctx->shape.num_pages,
+                                   num_layers, layer_stride_elems, ctx->d_counters + 9, stream, ctx->fp8_pages,
+                                   1.0f / ctx->k_scale, 1.0f / ctx->v_scale);
     if (rc != 0) return hip_fail(ctx, (hipError_t)rc, "launch kv_land");
     check_duplicate_slots(ctx, slot_mapping, T, static_cast<hipStream_t>(stream));
     if (ctx->log_calls) std::fprintf(stderr, "ppd: kv_land T=%lld layers=%d\n", (long long)T, (int)num_layers);

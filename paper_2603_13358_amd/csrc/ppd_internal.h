@@ -94,6 +94,7 @@ struct PlanOptions {
     int32_t pref_mode = 2;
     int32_t narrow_cus = -1;  // -1: from the cost model
     int32_t wave_tiles = -1;  // -1: short narrow tiles run one per wave when the launch has enough of them; 0 never; 1 always
+    int32_t kv_elem_bytes = 2;  // bytes per K/V element in the pool: 2 (bf16 pages) or 1 (FP8 E4M3 pages)
 };
 
 // Returns PPD_OK or an error code with a message in `err` (may be null).
@@ -118,7 +119,8 @@ struct KParams {
     int32_t narrow_cus;   // pref_mode 2: compute units per XCD (of 32) that take narrow tiles first
     int32_t max_pages;
     int32_t Hq, Hkv, G, invG;  // invG = 65536 / G + 1: col / G == (col * invG) >> 16
-    float scale_log2e;
+    float scale_log2e;    // softmax scale * log2(e), times the K scale of FP8 pages
+    float v_scale;        // factor of the final output: the V scale of FP8 pages, 1 for bf16 pages
 };
 
 struct MergeParams {
@@ -130,16 +132,18 @@ struct MergeParams {
     int32_t n_groups;
     int32_t Hq, G, invG, D;
     float scale_log2e;
+    float v_scale;
 };
 
 // Launchers (defined in ppd_kernels.hip); stream is a hipStream_t.
 int prepare_mixed_kernels();
-int launch_mixed(const KParams& p, int head_dim, int grid, void* stream);
+int launch_mixed(const KParams& p, int head_dim, int grid, void* stream, bool fp8_pages);
 int launch_mfma_only(const KParams& p, int head_dim, int grid, void* stream);    // row-block tiles of queues 0..7
 int launch_stream_only(const KParams& p, int head_dim, int grid, void* stream);  // narrow tiles of queue 8
 int launch_merge(const MergeParams& p, void* stream);
-int launch_kv_append(const uint16_t* k, const uint16_t* v, uint16_t* pool, const int64_t* slots, int64_t T,
+// fp8_pages: the pool holds one-byte FP8 E4M3 codes of x * inv_k_scale (K) and x * inv_v_scale (V)
+int launch_kv_append(const uint16_t* k, const uint16_t* v, void* pool, const int64_t* slots, int64_t T,
                      int Hkv, int D, int64_t num_pages, int layers, int64_t pool_layer_stride, uint32_t* err_flags,
-                     void* stream);
+                     void* stream, bool fp8_pages, float inv_k_scale, float inv_v_scale);
 
 }  // namespace ppd

@@ -9,6 +9,8 @@
 // lane that owns the row's column.
 #include <hip/hip_runtime.h>
 
+#include <type_traits>
+
 #include "ppd_internal.h"
 
 #ifndef PPD_PINGPONG
@@ -87,6 +89,42 @@ __device__ __forceinline__ int64_t checked_page(const KParams& P, int page) {
     return page;
 }
 
+// FP8 pages hold OCP FP8 E4M3 codes (1 sign, 4 exponent bits of bias 7, 3 mantissa bits).  Every code's value is a
+// bf16 number, so the tiles turn codes into bf16 MFMA operands exactly; the tensor's scale is applied once, to the
+// scores (K) and to the final output (V).
+// Four codes of a dword -> four bf16, in order (the conversion instruction takes the two codes of one 16-bit half).
+__device__ __forceinline__ u32x2 fp8x4_to_bf16x4(uint32_t w) {
+    const bf16x2 lo = __builtin_amdgcn_cvt_scalef32_pk_bf16_fp8(w, 1.0f, false);
+    const bf16x2 hi = __builtin_amdgcn_cvt_scalef32_pk_bf16_fp8(w, 1.0f, true);
+    return u32x2{__builtin_bit_cast(uint32_t, lo), __builtin_bit_cast(uint32_t, hi)};
+}
+__device__ __forceinline__ u32x4 fp8x8_to_bf16x8(u32x2 w) {
+    const u32x2 a = fp8x4_to_bf16x4(w[0]), b = fp8x4_to_bf16x4(w[1]);
+    return u32x4{a[0], a[1], b[0], b[1]};
+}
+
+// Code of a binary32 value: nearest, ties to the even code, magnitudes from 448 on (infinities included) saturate
+// to 448, NaN gives the NaN code.  Integer arithmetic on the bits, so that the stored byte does not depend on any
+// conversion instruction's treatment of ties, overflow or subnormals.
+__device__ __forceinline__ uint32_t e4m3_code(float y) {
+    const uint32_t u = __builtin_bit_cast(uint32_t, y);
+    const uint32_t sign = (u >> 24) & 0x80u;
+    const uint32_t a = u & 0x7FFFFFFFu;
+    uint32_t code;
+    if (a > 0x7F800000u) {
+        code = 0x7Fu;
+    } else if (a >= 0x43E00000u) {  // 448.0f
+        code = 0x7Eu;
+    } else if (a >= 0x3C800000u) {  // 2^-6, the smallest normal: round the mantissa at bit 20, re-bias 127 -> 7
+        const uint32_t r = a + 0x7FFFFu + ((a >> 20) & 1u);
+        code = (r >> 20) - (120u << 3);
+    } else {                        // subnormal codes are multiples of 2^-9 (8 is the smallest normal's code)
+        code = (uint32_t)__builtin_rintf(__builtin_bit_cast(float, a) * 512.0f);
+    }
+    return sign | code;
+}
+__device__ __forceinline__ float bf16_bits_to_f32(uint32_t bits) { return __builtin_bit_cast(float, bits << 16); }
+
 // Zeroes the bf16 elements e of a granule of 8 tokens whose position first + e is >= kv_total (never written).
 __device__ __forceinline__ u32x4 zero_unwritten(u32x4 v, int first, int kv_total) {
 #pragma unroll
@@ -135,16 +173,33 @@ __device__ __forceinline__ u32x4 lds_read16(uint32_t base, int offset) {
     return *reinterpret_cast<const __attribute__((address_space(3))) u32x4*>(base + (uint32_t)offset);
 }
 
-template <int HD, bool HALF>
+// FP8 (pages of one-byte codes): the loads land the tile's codes in a staging ring of their own (half the bytes, NS - 1
+// stages of K and of V), and at the end of the iteration before a tile is first read every thread turns the 16 codes it
+// loaded itself into bf16 in the operand rings -- once per workgroup, not once per wave and operand read -- so the
+// loop's matrix and vector phases are the ones of bf16 pages.  The operand rings then need three stages each (the tile
+// being written, the one the early waves read and the one the late waves read), which with the staging ring is the same
+// LDS as the four-stage rings of bf16 pages.
+template <int HD, bool HALF, bool FP8 = false>
 __device__ __forceinline__ void mfma_item(const KParams& P, const ppd_work_item& it, char* smem) {
-    constexpr int PB = kPage * HD * 2;         // bytes of one (page, head) block of K or of V
-    constexpr int GPP = PB / 16;               // 16-byte granules per block
+    static_assert(!(FP8 && HALF), "FP8 pages are read by the full-tile loop only");
+    static_assert(!FP8 || kStages == 3, "the staging of FP8 tiles is written for a prefetch distance of 3");
+    constexpr int EB = FP8 ? 1 : 2;            // bytes per pool element
+    constexpr int PB = kPage * HD * 2;         // bytes of one (page, head) block of K or of V as bf16 operands in LDS
+    constexpr int GPP = PB / 16;               // 16-byte granules per such block
     constexpr int KBYTES = 4 * PB;             // one stage: 4 pages of K (or of V)
     constexpr int NS = kStages;
-    constexpr int NSV = kStages + (PPD_PINGPONG ? 1 : 0);  // the late half of the waves reads V one barrier later
-    constexpr int NSK = kStages + (PPD_PINGPONG ? 1 : 0);  // ... and K as well
+    constexpr int NSV = FP8 ? 3 : kStages + (PPD_PINGPONG ? 1 : 0);  // the late half of the waves reads V one barrier later
+    constexpr int NSK = FP8 ? 3 : kStages + (PPD_PINGPONG ? 1 : 0);  // ... and K as well
     constexpr int VRING = NSK * KBYTES;        // LDS: K ring at 0, V ring behind it
-    constexpr int ROUNDS = 4 * GPP / kThreads; // granules of K (and of V) each thread moves per tile
+    constexpr int LPB = PB / 2 * EB;           // bytes of a block as the loads move it
+    constexpr int LGPP = LPB / 16;             // 16-byte granules per loaded block
+    constexpr int LBYTES = 4 * LPB;            // one loaded tile of K (or of V)
+    constexpr int LOADERS = 4 * LGPP < kThreads ? 4 * LGPP : kThreads;  // threads that load (all, or the first waves)
+    constexpr int ROUNDS = 4 * LGPP / LOADERS; // granules of K (and of V) each loading thread moves per tile
+    constexpr int NST = NS - 1;                // FP8: stages of the staging ring of K, and of V
+    constexpr int STAGE_K = (NSK + NSV) * KBYTES, STAGE_V = STAGE_K + NST * LBYTES;
+    constexpr int IDS_AT = (NSK + NSV) * KBYTES + (FP8 ? 2 * NST * LBYTES : 0);
+    static_assert(IDS_AT <= (2 * kStages + 2 * (PPD_PINGPONG ? 1 : 0)) * KBYTES, "the kernel's LDS is sized for the bf16 rings");
     constexpr int KS = HD / 16;                // k-steps of S^T = K Q^T
     constexpr int DB = HD / 32;                // 32-row d blocks of O^T
 
@@ -185,12 +240,14 @@ __device__ __forceinline__ void mfma_item(const KParams& P, const ppd_work_item&
     // 1 KiB contiguous per round, which is what a wave-wide LDS-direct load does.  The page a wave reads in
     // round r is wave-uniform, s = r * (kThreads / GPP) + (wave * 64) / GPP, and the lane's offset inside the
     // page block is the same in every round: the load's address is a scalar base plus a per-lane constant.
-    constexpr int PAGES_PER_ROUND = kThreads / GPP;
-    static_assert(kThreads % GPP == 0 && ROUNDS * PAGES_PER_ROUND == 4, "one round covers whole page blocks");
-    const int page_sel = (wave * 64) / GPP;
-    const uint32_t lane_off = (uint32_t)(tid % GPP) * 16u;
+    constexpr int PAGES_PER_ROUND = LOADERS / LGPP;
+    static_assert(LOADERS % 64 == 0 && LOADERS % LGPP == 0 && ROUNDS * PAGES_PER_ROUND == 4, "one round covers whole page blocks");
+    static_assert(!FP8 || ROUNDS == 1, "a thread stages one granule of codes per tile");
+    const bool loader = LOADERS == kThreads || tid < LOADERS;  // wave-uniform
+    const int page_sel = loader ? (wave * 64) / LGPP : 0;
+    const uint32_t lane_off = (uint32_t)(tid % LGPP) * 16u;
     struct TilePages { int p[ROUNDS]; };  // the pages this wave loads from, one per round
-    int* lds_ids = reinterpret_cast<int*>(smem + (NSK + NSV) * KBYTES);
+    int* lds_ids = reinterpret_cast<int*>(smem + IDS_AT);
     for (int i = tid; i < ntiles * 4; i += kThreads)
         lds_ids[i] = (int)checked_page(P, load_page_id(pt_row, first_page + i, last_page));
     struct RawPages { int p[ROUNDS]; };  // the same ids as they come from LDS (vector registers)
@@ -211,11 +268,30 @@ __device__ __forceinline__ void mfma_item(const KParams& P, const ppd_work_item&
     // LDS-direct loads of later tiles stay in flight across it.
     auto lds_barrier = [&]() { asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory"); };
     auto load_block = [&](const TilePages& t, int lds_byte, int64_t kv_off) {
+        if (!loader) return;
 #pragma unroll
         for (int r = 0; r < ROUNDS; ++r) {
-            const uint16_t* base = P.pool + (int64_t)t.p[r] * P.page_stride + head_off + kv_off;
+            const char* base = reinterpret_cast<const char*>(P.pool) + ((int64_t)t.p[r] * P.page_stride + head_off + kv_off) * EB;
             lds_direct_load16(base, lane_off, smem + lds_byte + r * (kThreads * 16) + wave * 1024);
         }
+    };
+    // FP8: the 16 codes this thread staged at src_byte become two bf16 granules of the operand tile at dst_byte (the
+    // element order of a tile is the same in both); V rows of positions >= kv_total were never written and become 0.
+    auto convert_staged = [&](int src_byte, int dst_byte, bool is_v, int tile) {
+        if (!loader) return;
+        const u32x4 raw = *reinterpret_cast<const u32x4*>(smem + src_byte + tid * 16);
+        u32x4 lo = fp8x8_to_bf16x8(u32x2{raw[0], raw[1]}), hi = fp8x8_to_bf16x8(u32x2{raw[2], raw[3]});
+        if (is_v) {
+            const int tile_base = it.kv_begin + tile * kTileTokens;
+            if (tile_base + kTileTokens > it.kv_total) {
+                const int g0 = 2 * tid, g1 = 2 * tid + 1;  // bf16 granules of the tile: page g / GPP, (octet, d) = g % GPP
+                lo = zero_unwritten(lo, tile_base + (g0 / GPP) * 16 + ((g0 % GPP) / HD) * 8, it.kv_total);
+                hi = zero_unwritten(hi, tile_base + (g1 / GPP) * 16 + ((g1 % GPP) / HD) * 8, it.kv_total);
+            }
+        }
+        u32x4* dst = reinterpret_cast<u32x4*>(smem + dst_byte + tid * 32);
+        dst[0] = lo;
+        dst[1] = hi;
     };
     // V rows of positions >= kv_total were never written: zero them in LDS (each thread fixes the granules it
     // loaded itself, after its own loads have landed).  Only the sequence's last tile needs it.
@@ -275,7 +351,21 @@ __device__ __forceinline__ void mfma_item(const KParams& P, const ppd_work_item&
 
     // prologue: K(0..NS-1) and V(0..NS-2) are issued, K(0), K(1), V(0) must land; S^T of tile 0
     __syncthreads();  // page ids are in LDS
-    {
+    if constexpr (FP8) {
+        // K(0), K(1) and V(0) are staged and converted; K(2) and V(1) are then issued into the slots of K(0) and beside V(0)
+        const TilePages tp0 = tile_pages(0), tp1 = tile_pages(1 < ntiles ? 1 : 0);
+        load_block(tp0, STAGE_K, 0);
+        load_block(tp0, STAGE_V, v_off);
+        if (1 < ntiles) load_block(tp1, STAGE_K + LBYTES, 0);
+        wait_all_loads();
+#pragma unroll
+        for (int ks = 0; ks < KS; ++ks) asm volatile("" ::"v"(qreg[ks]));
+        convert_staged(STAGE_K, 0, false, 0);
+        if (1 < ntiles) convert_staged(STAGE_K + LBYTES, KBYTES, false, 1);
+        convert_staged(STAGE_V, VRING, true, 0);
+        if (2 < ntiles) load_block(tile_pages(2), STAGE_K, 0);
+        if (1 < ntiles) load_block(tp1, STAGE_V + LBYTES, v_off);
+    } else {
 #pragma unroll
         for (int t = 0; t < NS; ++t) {
             if (t < ntiles) {
@@ -284,16 +374,16 @@ __device__ __forceinline__ void mfma_item(const KParams& P, const ppd_work_item&
                 if (t < NS - 1) load_block(tp, VRING + t * KBYTES, v_off);
             }
         }
+        wait_all_loads();
+        // The compiler does not count the asm loads; make it settle its own pending loads (the Q operand) here, or
+        // it would place ever-decreasing memory-counter waits at their first use inside the loop and drain the
+        // LDS-direct loads in flight there.
+#pragma unroll
+        for (int ks = 0; ks < KS; ++ks) asm volatile("" ::"v"(qreg[ks]));
+#pragma unroll
+        for (int t = 0; t < NS - 1; ++t)
+            if (t < ntiles) fix_v_tail(t, VRING + t * KBYTES);
     }
-    wait_all_loads();
-    // The compiler does not count the asm loads; make it settle its own pending loads (the Q operand) here, or
-    // it would place ever-decreasing memory-counter waits at their first use inside the loop and drain the
-    // LDS-direct loads in flight there.
-#pragma unroll
-    for (int ks = 0; ks < KS; ++ks) asm volatile("" ::"v"(qreg[ks]));
-#pragma unroll
-    for (int t = 0; t < NS - 1; ++t)
-        if (t < ntiles) fix_v_tail(t, VRING + t * KBYTES);
     lds_barrier();
     if constexpr (!HALF) {
     f32x16 s_cur[2];
@@ -324,8 +414,13 @@ __device__ __forceinline__ void mfma_item(const KParams& P, const ppd_work_item&
         const int sv_nxt = sv_cur + 1 == NSV ? 0 : sv_cur + 1;           // (ti + 1) % NSV
         const int sv_far = (sv_cur + NS - 1) % NSV;                       // (ti + NS - 1) % NSV
         const bool full_issue = ti + NS < ntiles;
-        if (ti + NS - 1 < ntiles) load_block(tp_v, VRING + sv_far * KBYTES, v_off);
-        if (full_issue) load_block(tp_k, st_far * KBYTES, 0);
+        if constexpr (FP8) {  // tile t of K or of V is staged in slot t % 2
+            if (ti + NS - 1 < ntiles) load_block(tp_v, STAGE_V + (ti & 1) * LBYTES, v_off);
+            if (full_issue) load_block(tp_k, STAGE_K + ((ti + 1) & 1) * LBYTES, 0);
+        } else {
+            if (ti + NS - 1 < ntiles) load_block(tp_v, VRING + sv_far * KBYTES, v_off);
+            if (full_issue) load_block(tp_k, st_far * KBYTES, 0);
+        }
         // The V tile of the next iteration is this iteration's K tile; the ids of its K tile are read from LDS
         // now and turned into scalars at the end of the iteration: under the other waves' operand reads that
         // small LDS read takes hundreds of cycles, which nothing waits for this way.
@@ -338,7 +433,12 @@ __device__ __forceinline__ void mfma_item(const KParams& P, const ppd_work_item&
                 wait_older_loads();
             else
                 wait_all_loads();
-            if (ti + 1 < ntiles) fix_v_tail(ti + 1, VRING + sv_nxt * KBYTES);
+            if constexpr (FP8) {
+                if (ti + 2 < ntiles) convert_staged(STAGE_K + (ti & 1) * LBYTES, ((st_cur + 2) % NSK) * KBYTES, false, ti + 2);
+                if (ti + 1 < ntiles) convert_staged(STAGE_V + ((ti + 1) & 1) * LBYTES, VRING + sv_nxt * KBYTES, true, ti + 1);
+            } else {
+                if (ti + 1 < ntiles) fix_v_tail(ti + 1, VRING + sv_nxt * KBYTES);
+            }
             lds_barrier();
         };
         float mc = 0.f;
@@ -526,7 +626,7 @@ __device__ __forceinline__ void mfma_item(const KParams& P, const ppd_work_item&
     const float l_tot = sum_halves(l_run);
     if (col < ncols) {
         if (it.part_off < 0) {
-            const float inv = 1.f / l_tot;
+            const float inv = P.v_scale / l_tot;
             uint16_t* op = P.out + ((int64_t)(it.grow0 + jrow) * P.Hq + head) * HD + h * 4;
 #pragma unroll
             for (int db = 0; db < DB; ++db)
@@ -571,9 +671,14 @@ struct NarrowCombine {
 
 // SOLO: the calling wave runs the whole tile on its own (NW = 1): no LDS, no barrier, the result is written from the
 // accumulator registers; the other waves of the workgroup run other tiles at the same time.
-template <int HD, int NW, int NK, int NV, bool SOLO = false>
+// FP8: the pool holds one-byte codes in the same element layout; a lane's loads are half as wide and the codes are
+// turned into bf16 operands right before the MFMAs.
+template <int HD, int NW, int NK, int NV, bool SOLO = false, bool FP8 = false>
 __device__ __forceinline__ void narrow_item(const KParams& P, const ppd_work_item& it, char* smem) {
     static_assert(!SOLO || NW == 1, "a solo tile is one wave");
+    constexpr int EB = FP8 ? 1 : 2;  // bytes per pool element
+    using KVec = std::conditional_t<FP8, u32x2, u32x4>;     // 8 elements
+    using VVec = std::conditional_t<FP8, uint32_t, u32x2>;  // 4 elements
     constexpr int KS = HD / 32;   // k-steps of S^T
     constexpr int DBN = HD / 16;  // 16-row d blocks of O^T
     constexpr int CB = NarrowCombine<NW>::CB;
@@ -623,13 +728,13 @@ __device__ __forceinline__ void narrow_item(const KParams& P, const ppd_work_ite
     // and may still be in the batch before (ids_old).
     int ids_old = 0, ids_cur = 0, ids_nxt = 0, k_batch = 0;
     auto load_ids = [&](int batch) { return load_page_id(pt_row, wave_first_page + batch * 64 + lane, last_page); };
-    struct KRegs { u32x4 k[KS]; };   // K operand of the page: 16 tokens x 32 d per k-step
-    struct VRegs { u32x2 v[DBN]; };  // V^T operand: 4 tokens of one d, one per 16-row d block
+    struct KRegs { KVec k[KS]; };   // K operand of the page: 16 tokens x 32 d per k-step
+    struct VRegs { VVec v[DBN]; };  // V^T operand: 4 tokens of one d, one per 16-row d block
     KRegs rk[NK];
     VRegs rv[NV];
     const int my_steps = s_hi - s_lo;
-    const uint32_t k_lane_bytes = (uint32_t)(g4 * 128 + c16 * 8) * 2u;                          // + ks * 1024
-    const uint32_t v_lane_bytes = (uint32_t)(((g4 >> 1) * HD + c16) * 8 + (g4 & 1) * 4) * 2u;  // + db * 256
+    const uint32_t k_lane_bytes = (uint32_t)(g4 * 128 + c16 * 8) * EB;                          // + ks * 512 elements
+    const uint32_t v_lane_bytes = (uint32_t)(((g4 >> 1) * HD + c16) * 8 + (g4 & 1) * 4) * EB;  // + db * 128 elements
     // K and V are read once: non-temporal loads (no reuse to keep in the caches) stream ~12 % faster than plain
     // ones on this pattern.  Address = wave-uniform base of the (page, head) block + one 32-bit byte offset per lane.
     auto issue_k = [&](int k, KRegs& r) {  // k = step index relative to s_lo
@@ -640,24 +745,27 @@ __device__ __forceinline__ void narrow_item(const KParams& P, const ppd_work_ite
             if (k + 64 < my_steps) ids_nxt = load_ids(k_batch + 1);
         }
         const int64_t pa = checked_page(P, __builtin_amdgcn_readlane(ids_cur, k & 63));
-        const char* kb = reinterpret_cast<const char*>(P.pool + pa * P.page_stride + head_off);
+        const char* kb = reinterpret_cast<const char*>(P.pool) + (pa * P.page_stride + head_off) * EB;
 #pragma unroll
         for (int ks = 0; ks < KS; ++ks)
-            r.k[ks] = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(kb + k_lane_bytes + ks * 1024));
+            r.k[ks] = __builtin_nontemporal_load(reinterpret_cast<const KVec*>(kb + k_lane_bytes + ks * (512 * EB)));
     };
     auto issue_v = [&](int k, VRegs& r) {
         const int ids = (k >> 6) == k_batch ? ids_cur : ids_old;
         const int64_t pa = checked_page(P, __builtin_amdgcn_readlane(ids, k & 63));
-        const char* vb = reinterpret_cast<const char*>(P.pool + pa * P.page_stride + head_off + v_off);
+        const char* vb = reinterpret_cast<const char*>(P.pool) + (pa * P.page_stride + head_off + v_off) * EB;
 #pragma unroll
         for (int db = 0; db < DBN; ++db)
-            r.v[db] = __builtin_nontemporal_load(reinterpret_cast<const u32x2*>(vb + v_lane_bytes + db * 256));
+            r.v[db] = __builtin_nontemporal_load(reinterpret_cast<const VVec*>(vb + v_lane_bytes + db * (128 * EB)));
     };
     auto compute_step = [&](int k, KRegs& rs, VRegs& rw) {
         f32x4 sa = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-        for (int ks = 0; ks < KS; ++ks)
-            sa = __builtin_amdgcn_mfma_f32_16x16x32_bf16(as_bf16x8(rs.k[ks]), qreg[ks], sa, 0, 0, 0);
+        for (int ks = 0; ks < KS; ++ks) {
+            bf16x8 ka;
+            if constexpr (FP8) ka = as_bf16x8(fp8x8_to_bf16x8(rs.k[ks])); else ka = as_bf16x8(rs.k[ks]);
+            sa = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ka, qreg[ks], sa, 0, 0, 0);
+        }
         // sa[i]: token 4*g4 + i of the page
         const int t0 = it.kv_begin + (s_lo + k) * kPage;
         const bool masked = t0 + kPage - 1 > min_limit || t0 + kPage > it.kv_end;
@@ -673,7 +781,11 @@ __device__ __forceinline__ void narrow_item(const KParams& P, const ppd_work_ite
 #pragma unroll
                     for (int e = 0; e < 4; ++e) {
                         const int pos = t0 + 4 * g4 + e;
-                        if (pos >= it.kv_total) rw.v[db][e >> 1] &= (e & 1) ? 0x0000FFFFu : 0xFFFF0000u;
+                        if constexpr (FP8) {
+                            if (pos >= it.kv_total) rw.v[db] &= ~(0xFFu << (8 * e));  // code 0 is 0.0
+                        } else {
+                            if (pos >= it.kv_total) rw.v[db][e >> 1] &= (e & 1) ? 0x0000FFFFu : 0xFFFF0000u;
+                        }
                     }
                 }
             }
@@ -698,8 +810,11 @@ __device__ __forceinline__ void narrow_item(const KParams& P, const ppd_work_ite
         const u32x2 pw = {pack_bf16(p[0], p[1]), pack_bf16(p[2], p[3])};
         const s16x4 pb4 = __builtin_bit_cast(s16x4, pw);
 #pragma unroll
-        for (int db = 0; db < DBN; ++db)
-            oacc[db] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(__builtin_bit_cast(s16x4, rw.v[db]), pb4, oacc[db], 0, 0, 0);
+        for (int db = 0; db < DBN; ++db) {
+            s16x4 va;
+            if constexpr (FP8) va = __builtin_bit_cast(s16x4, fp8x4_to_bf16x4(rw.v[db])); else va = __builtin_bit_cast(s16x4, rw.v[db]);
+            oacc[db] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(va, pb4, oacc[db], 0, 0, 0);
+        }
     };
 
     // K of NK - 1 pages and V of NV - 1 pages (4 KiB each at D = 128) are in flight per wave while one page is being
@@ -732,7 +847,7 @@ __device__ __forceinline__ void narrow_item(const KParams& P, const ppd_work_ite
         // O^T register i of block db is d = db*16 + 4*g4 + i of column c16; m and l are the column's in every lane
         if (c16 < ncols) {
             if (it.part_off < 0) {
-                const float inv = 1.f / l_run;
+                const float inv = P.v_scale / l_run;
                 uint16_t* op = P.out + ((int64_t)(it.grow0 + jrow) * P.Hq + head) * HD + 4 * g4;
 #pragma unroll
                 for (int db = 0; db < DBN; ++db) {
@@ -789,7 +904,7 @@ __device__ __forceinline__ void narrow_item(const KParams& P, const ppd_work_ite
             if (it.part_off < 0) {
                 const int crow = col_row(col, P.invG);
                 const int64_t orow = (int64_t)(it.grow0 + crow) * P.Hq + it.kvh * G + (col - crow * G);
-                const float val = o / l;
+                const float val = (o / l) * P.v_scale;
                 const float other = __shfl_xor(val, 1, 64);  // d and d^1 sit in neighbouring lanes
                 if ((d & 1) == 0) *reinterpret_cast<uint32_t*>(P.out + orow * HD + d) = pack_bf16(val, other);
             } else {
@@ -822,8 +937,10 @@ __device__ __forceinline__ void rearm_cursors(const KParams& P, int q0, int q1, 
     }
 }
 
-template <int HD>
+template <int HD, bool FP8>
 __global__ __launch_bounds__(kThreads, 2) void ppd_mixed_kernel(const KParams P) {
+    // register sets of a streaming wave: a page of codes is half the registers, so FP8 pages keep more pages in flight
+    constexpr int NSETS = FP8 ? 6 : 4;
     // Dynamic LDS: rings of kStages + 1 stages of 4 pages of K and as many of V, then the page ids of a tile's key
     // range, for the MFMA path (136 KiB at HD = 128); the narrow path's combine buffer (kWaves * 16 * (HD+2)
     // floats) uses the front of it.
@@ -911,15 +1028,15 @@ __global__ __launch_bounds__(kThreads, 2) void ppd_mixed_kernel(const KParams P)
             const int mine = idx + __builtin_amdgcn_readfirstlane(tid >> 6);
             if (mine < P.queue_begin[kQueues]) {
                 const ppd_work_item it = P.items[mine];
-                narrow_item<HD, 1, 4, 4, true>(P, it, smem);
+                narrow_item<HD, 1, NSETS, NSETS, true, FP8>(P, it, smem);
             }
             continue;
         }
         const ppd_work_item it = P.items[idx];
         if (it.kind == 0)
-            narrow_item<HD, kWaves, 4, 4>(P, it, smem);
+            narrow_item<HD, kWaves, NSETS, NSETS, false, FP8>(P, it, smem);
         else
-            mfma_item<HD, false>(P, it, smem);
+            mfma_item<HD, false, FP8>(P, it, smem);
     }
     if (tid == 0) rearm_cursors(P, 0, kCursors, 10);
 }
@@ -1076,7 +1193,7 @@ __global__ __launch_bounds__(kSmallThreads) void ppd_merge_kernel(const MergePar
         if (live && col < ncols) {
             const int crow = col_row(col, M.invG);
             const int64_t orow = (int64_t)(g.grow0 + crow) * M.Hq + g.kvh * M.G + (col - crow * M.G);
-            *reinterpret_cast<uint32_t*>(M.out + orow * D + d) = pack_bf16(o0[c] / l[c], o1[c] / l[c]);
+            *reinterpret_cast<uint32_t*>(M.out + orow * D + d) = pack_bf16((o0[c] / l[c]) * M.v_scale, (o1[c] / l[c]) * M.v_scale);
         }
     }
 }
@@ -1098,12 +1215,19 @@ __global__ __launch_bounds__(kSmallThreads) void ppd_merge_kernel(const MergePar
 // faster with them)
 #define APPEND_LOAD(p) __builtin_nontemporal_load(p)
 #define APPEND_STORE(v, p) __builtin_nontemporal_store(v, p)
+// FP8: the pool's elements are bytes; element x of K is stored as the code of x * inv_k (of V: x * inv_v), one
+// binary32 product each.
+template <bool FP8>
 __global__ __launch_bounds__(kSmallThreads) void ppd_kv_append_kernel(const uint16_t* __restrict__ k,
                                                                  const uint16_t* __restrict__ v,
-                                                                 uint16_t* __restrict__ pool,
+                                                                 std::conditional_t<FP8, uint8_t, uint16_t>* __restrict__ pool,
                                                                  const int64_t* __restrict__ slots, int64_t T,
                                                                  int Hkv, int D, int64_t num_pages,
-                                                                 int64_t pool_layer_stride, uint32_t* err_flags) {
+                                                                 int64_t pool_layer_stride, uint32_t* err_flags,
+                                                                 float inv_k, float inv_v) {
+    auto code_pair = [](uint32_t two_bf16, float inv) {  // the codes of the two bf16 of a dword, low one first
+        return e4m3_code(bf16_bits_to_f32(two_bf16 & 0xFFFFu) * inv) | (e4m3_code(bf16_bits_to_f32(two_bf16 >> 16) * inv) << 8);
+    };
     // blockIdx.z = layer: source layers are contiguous [layer][T][Hkv][D], pools pool_layer_stride apart
     k += (int64_t)blockIdx.z * T * Hkv * D;
     v += (int64_t)blockIdx.z * T * Hkv * D;
@@ -1151,7 +1275,14 @@ __global__ __launch_bounds__(kSmallThreads) void ppd_kv_append_kernel(const uint
         const int64_t s = __shfl(ws, 7 + tok);  // every lane of the wave is here: D is a multiple of 64
         if (s < 0) continue;
         const u32x4 val = APPEND_LOAD(reinterpret_cast<const u32x4*>(k + (t0 + tok) * HD + hh * D + c * 8));
-        APPEND_STORE(val, reinterpret_cast<u32x4*>(pool + (s >> 4) * S + koff + c * (kPage * 8) + (int)(s & 15) * 8));
+        auto* dst = pool + (s >> 4) * S + koff + c * (kPage * 8) + (int)(s & 15) * 8;
+        if constexpr (FP8) {
+            const u32x2 codes = {code_pair(val[0], inv_k) | (code_pair(val[1], inv_k) << 16),
+                                 code_pair(val[2], inv_k) | (code_pair(val[3], inv_k) << 16)};
+            APPEND_STORE(codes, reinterpret_cast<u32x2*>(dst));
+        } else {
+            APPEND_STORE(val, reinterpret_cast<u32x4*>(dst));
+        }
     }
     // V, whole granules (upper half of the threads, at the same time as K): work unit = d
     if (oct_slot >= 0 && tid >= kHalf) {
@@ -1166,7 +1297,14 @@ __global__ __launch_bounds__(kSmallThreads) void ppd_kv_append_kernel(const uint
                 const uint32_t hi = APPEND_LOAD(src + (2 * e + 1) * HD + d);
                 g[e] = lo | (hi << 16);
             }
-            APPEND_STORE((u32x4{g[0], g[1], g[2], g[3]}), reinterpret_cast<u32x4*>(pool + page * S + voff + half * (D * 8) + d * 8));
+            auto* dst = pool + page * S + voff + half * (D * 8) + d * 8;
+            if constexpr (FP8) {
+                const u32x2 codes = {code_pair(g[0], inv_v) | (code_pair(g[1], inv_v) << 16),
+                                     code_pair(g[2], inv_v) | (code_pair(g[3], inv_v) << 16)};
+                APPEND_STORE(codes, reinterpret_cast<u32x2*>(dst));
+            } else {
+                APPEND_STORE((u32x4{g[0], g[1], g[2], g[3]}), reinterpret_cast<u32x4*>(dst));
+            }
         }
     }
     // V, element by element: work unit = (token, d)
@@ -1176,7 +1314,9 @@ __global__ __launch_bounds__(kSmallThreads) void ppd_kv_append_kernel(const uint
             const int64_t s = __shfl(ws, 7 + tok);  // before any lane drops out
             if (!((single >> tok) & 1u)) continue;
             const int off = (int)(s & 15);
-            pool[(s >> 4) * S + voff + (off >> 3) * (D * 8) + d * 8 + (off & 7)] = v[(t0 + tok) * HD + hh * D + d];
+            const uint16_t x = v[(t0 + tok) * HD + hh * D + d];
+            auto* dst = pool + (s >> 4) * S + voff + (off >> 3) * (D * 8) + d * 8 + (off & 7);
+            if constexpr (FP8) *dst = (uint8_t)e4m3_code(bf16_bits_to_f32(x) * inv_v); else *dst = x;
         }
     }
 }
@@ -1198,19 +1338,25 @@ int prepare_mixed_kernels() {
     auto allow = [&](const void* fn, size_t bytes) {
         if (e == hipSuccess) e = hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, (int)bytes);
     };
-    allow(reinterpret_cast<const void*>(&ppd_mixed_kernel<128>), mixed_lds_bytes(128));
-    allow(reinterpret_cast<const void*>(&ppd_mixed_kernel<64>), mixed_lds_bytes(64));
+    allow(reinterpret_cast<const void*>(&ppd_mixed_kernel<128, false>), mixed_lds_bytes(128));
+    allow(reinterpret_cast<const void*>(&ppd_mixed_kernel<64, false>), mixed_lds_bytes(64));
+    allow(reinterpret_cast<const void*>(&ppd_mixed_kernel<128, true>), mixed_lds_bytes(128));
+    allow(reinterpret_cast<const void*>(&ppd_mixed_kernel<64, true>), mixed_lds_bytes(64));
     allow(reinterpret_cast<const void*>(&ppd_mfma_kernel<128>), ring_lds_bytes(128));
     allow(reinterpret_cast<const void*>(&ppd_mfma_kernel<64>), ring_lds_bytes(64));
     return (int)e;
 }
 
-int launch_mixed(const KParams& p, int head_dim, int grid, void* stream) {
+int launch_mixed(const KParams& p, int head_dim, int grid, void* stream, bool fp8_pages) {
     hipStream_t st = static_cast<hipStream_t>(stream);
-    if (head_dim == 128)
-        hipLaunchKernelGGL(ppd_mixed_kernel<128>, dim3(grid), dim3(kThreads), mixed_lds_bytes(128), st, p);
+    if (head_dim == 128 && !fp8_pages)
+        hipLaunchKernelGGL((ppd_mixed_kernel<128, false>), dim3(grid), dim3(kThreads), mixed_lds_bytes(128), st, p);
+    else if (head_dim == 128)
+        hipLaunchKernelGGL((ppd_mixed_kernel<128, true>), dim3(grid), dim3(kThreads), mixed_lds_bytes(128), st, p);
+    else if (!fp8_pages)
+        hipLaunchKernelGGL((ppd_mixed_kernel<64, false>), dim3(grid), dim3(kThreads), mixed_lds_bytes(64), st, p);
     else
-        hipLaunchKernelGGL(ppd_mixed_kernel<64>, dim3(grid), dim3(kThreads), mixed_lds_bytes(64), st, p);
+        hipLaunchKernelGGL((ppd_mixed_kernel<64, true>), dim3(grid), dim3(kThreads), mixed_lds_bytes(64), st, p);
     return (int)hipGetLastError();
 }
 
@@ -1239,13 +1385,19 @@ int launch_merge(const MergeParams& p, void* stream) {
     return (int)hipGetLastError();
 }
 
-int launch_kv_append(const uint16_t* k, const uint16_t* v, uint16_t* pool, const int64_t* slots, int64_t T, int Hkv,
+int launch_kv_append(const uint16_t* k, const uint16_t* v, void* pool, const int64_t* slots, int64_t T, int Hkv,
                      int D, int64_t num_pages, int layers, int64_t pool_layer_stride, uint32_t* err_flags,
-                     void* stream) {
+                     void* stream, bool fp8_pages, float inv_k_scale, float inv_v_scale) {
     const int64_t blocks = (T + 7) / 8;
-    hipLaunchKernelGGL(ppd_kv_append_kernel, dim3((unsigned)blocks, (unsigned)Hkv, (unsigned)layers),
-                       dim3(kSmallThreads), 0, static_cast<hipStream_t>(stream), k, v, pool, slots, T, Hkv, D, num_pages,
-                       pool_layer_stride, err_flags);
+    const dim3 grid((unsigned)blocks, (unsigned)Hkv, (unsigned)layers);
+    if (fp8_pages)
+        hipLaunchKernelGGL(ppd_kv_append_kernel<true>, grid, dim3(kSmallThreads), 0, static_cast<hipStream_t>(stream), k, v,
+                           static_cast<uint8_t*>(pool), slots, T, Hkv, D, num_pages, pool_layer_stride, err_flags,
+                           inv_k_scale, inv_v_scale);
+    else
+        hipLaunchKernelGGL(ppd_kv_append_kernel<false>, grid, dim3(kSmallThreads), 0, static_cast<hipStream_t>(stream), k, v,
+                           static_cast<uint16_t*>(pool), slots, T, Hkv, D, num_pages, pool_layer_stride, err_flags,
+                           inv_k_scale, inv_v_scale);
     return (int)hipGetLastError();
 }
 

@@ -138,11 +138,11 @@ static int64_t choose_mfma_chunk(const std::vector<RowBlock>& blocks, int G, int
 // (the merge walks the splits of a column one after the other).  Constants fitted to 114 measured launches
 // (1..16 sequences x 4K..256K context x six split sizes; log-error 11 % rms, the pick within 3 % of the best
 // measured size in all 19 batches).
-static int64_t choose_narrow_chunk(const std::vector<int64_t>& lengths, int Hkv, int D, int slots) {
+static int64_t choose_narrow_chunk(const std::vector<int64_t>& lengths, int Hkv, int D, int slots, int elem_bytes) {
     constexpr double kStartUs = 7.0, kUnitBytesPerUs = 55e3, kHbmBytesPerUs = 7.0e6;
     constexpr double kMergeUs = 4.0, kMergeSplitUs = 0.3;
     static const int64_t kCandidates[] = {8192, 6144, 4096, 3072, 2048, 1536, 1024, 768, 512};
-    const double bytes_per_key = 2.0 * D * 2;
+    const double bytes_per_key = 2.0 * D * elem_bytes;
     int64_t best_chunk = kCandidates[0];
     double best = -1.0;
     std::vector<int32_t> tiles, bounds;
@@ -193,7 +193,7 @@ ppd_status build_plan(const ppd_shape& s, const int32_t* L, const int32_t* n, in
         *err = kChunk; return PPD_ERR_RANGE;
     }
     const int D = s.head_dim, Hq = s.num_q_heads, Hkv = s.num_kv_heads, G = Hq / Hkv;
-    const int64_t kv_tok_bytes_head = 2LL * D * 2;  // K and V of one token of one KV head
+    const int64_t kv_tok_bytes_head = 2LL * D * (o.kv_elem_bytes == 1 ? 1 : 2);  // K and V of one token of one KV head
     int64_t rows = 0;
     double flops = 0;
     int64_t kv_tokens = 0;
@@ -236,7 +236,7 @@ ppd_status build_plan(const ppd_shape& s, const int32_t* L, const int32_t* n, in
                                ? o.narrow_chunk
                                : std::min<int64_t>(8192, std::max<int64_t>(512, round_up((int64_t)(narrow_tokens / 96), kTileTokens)));
     if (o.narrow_chunk == 0 && row_blocks.empty() && (int64_t)narrow_lengths.size() * Hkv < 2LL * slots)
-        narrow_chunk = choose_narrow_chunk(narrow_lengths, Hkv, D, slots);
+        narrow_chunk = choose_narrow_chunk(narrow_lengths, Hkv, D, slots, o.kv_elem_bytes == 1 ? 1 : 2);
     int64_t mfma_chunk = o.mfma_chunk;
     if (mfma_chunk == 0 && !row_blocks.empty())
         mfma_chunk = choose_mfma_chunk(row_blocks, G, Hkv, D, slots, narrow_tokens * kv_tok_bytes_head);
