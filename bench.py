@@ -68,19 +68,21 @@ def make_shapes(name, seed):
 
 
 class Runner:
-    def __init__(self, b, torch, seed=0, options=None):
+    def __init__(self, b, torch, seed=0, options=None, fp8=False):
         import paper_2603_13358_amd as ppd
         import synthetic_inputs as si
-        self.torch, self.b = torch, b
+        self.torch, self.b, self.fp8 = torch, b, fp8
         self.dev = torch.device("cuda:0")
         self.ctx = ppd.Context(b.Hq, b.Hkv, b.D, b.num_pages)
+        if fp8:  # FP8 E4M3 pages (an extension beyond the paper's 16-bit KV): half the bytes per cached token
+            self.ctx.set_kv_format(ppd.PPD_KV_FP8_E4M3, si.FP8_BENCH_SCALE, si.FP8_BENCH_SCALE)
         for k, v in (options or {}).items():
             self.ctx.set_option(k, v)
-        self.w = si.device_workload(b, torch, self.dev, seed)
+        self.w = si.device_workload(b, torch, self.dev, seed, fp8=fp8)
         # Consecutive steps read different copies of the page pool, as the layers of a model do: nothing of a
         # step's K/V is left in the 256 MB Infinity Cache (or an L2) by the step before.  Identical contents, so
         # every step computes the same result.
-        copies = POOL_COPIES if self.w["pool"].numel() * 2 * POOL_COPIES <= 64e9 else 1
+        copies = POOL_COPIES if self.w["pool"].numel() * self.w["pool"].element_size() * POOL_COPIES <= 64e9 else 1
         self.pools = [self.w["pool"]] + [self.w["pool"].clone() for _ in range(copies - 1)]
         self.at = 0
         self.stream = torch.cuda.current_stream().cuda_stream
@@ -185,8 +187,13 @@ def cpu_baseline(runner, budget_s=15.0):
         if ap:
             pairs += sum(int(b.L[ap[0]]) + j + 1 for j in range(ap_rows))
         t0 = time.perf_counter()
-        ref = oracle.mixed_attention(sub.q, pool, sub.page_tables, sub.L, sub.n, sub.Hq, sub.Hkv, sub.D, sub.P,
-                                     sub.num_pages, sub.scale, row_mask=mask, threads=cores)
+        if runner.fp8:
+            ref = oracle.mixed_attention_fp8(sub.q, pool, si.FP8_BENCH_SCALE, si.FP8_BENCH_SCALE, sub.page_tables, sub.L,
+                                             sub.n, sub.Hq, sub.Hkv, sub.D, sub.P, sub.num_pages, sub.scale,
+                                             row_mask=mask, threads=cores)
+        else:
+            ref = oracle.mixed_attention(sub.q, pool, sub.page_tables, sub.L, sub.n, sub.Hq, sub.Hkv, sub.D, sub.P,
+                                         sub.num_pages, sub.scale, row_mask=mask, threads=cores)
         dt = time.perf_counter() - t0
         got = runner.w["out"].float().cpu().numpy()[rows]
         sel = mask.astype(bool)
@@ -550,6 +557,8 @@ def main():
     ap.add_argument("--seed", type=int, default=0)
     ap.add_argument("--no-extras", action="store_true", help="time the chosen workload only")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle leg")
+    ap.add_argument("--kv-fp8", action="store_true",
+                    help="run the chosen workload on FP8 E4M3 KV pages (extension beyond the paper; half the KV bytes)")
     ap.add_argument("--opt", action="append", default=[], help="library option key=value (tuning sweeps)")
     ap.add_argument("--trace", action="store_true", help="run the multi-turn conversation trace (cfg5) and exit")
     ap.add_argument("--trace-steps", type=int, default=0, help="limit the trace to its first N engine steps")
@@ -585,9 +594,9 @@ def main():
         print(json.dumps({"workload": "interference_sweeps", "sweeps": run_sweeps(torch, args.seed, max(10, args.steps // 2),
                                                                                   options)}))
         return
-    def run(name, steps, warmup, want_cpu=False):
+    def run(name, steps, warmup, want_cpu=False, fp8=False):
         b = make_shapes(name, args.seed)
-        r = Runner(b, torch, args.seed, options)
+        r = Runner(b, torch, args.seed, options, fp8=fp8)
         r.step()                                   # first call: plans and uploads
         first_plan_us = r.ctx.plan_stats().plan_host_us
         # After an idle gap the chip's power controller needs ~12 back-to-back launches of the MFMA-bound kernel to
@@ -603,14 +612,15 @@ def main():
         st["plan_host_us_first_call"] = first_plan_us
         st["plan_host_us"] = warm_plan_us
         res = {"workload": name, "ms_per_step": ms, "mixed_kernel_ms": kms, "plan": st, "step_us": dist,
-               "kv_bytes": b.kv_read_bytes(), "flops": b.attention_flops(), "rows": b.T, "sequences": b.B,
+               "kv_bytes": b.kv_read_bytes() // (2 if fp8 else 1), "flops": b.attention_flops(), "rows": b.T,
+               "sequences": b.B,
                "seq_roofline_us": per_sequence_roofline_us(b)}
         if want_cpu:
             res["cpu"] = cpu_baseline(r)
         r.close()
         return res
 
-    main_res = run(args.workload, args.steps, args.warmup, want_cpu=not args.no_cpu)
+    main_res = run(args.workload, args.steps, args.warmup, want_cpu=not args.no_cpu, fp8=args.kv_fp8)
     b_bytes, b_flops = main_res["kv_bytes"], main_res["flops"]
     t_hbm = b_bytes / (HBM_PEAK_GBS * 1e9)
     t_mfma = b_flops / (MFMA_BF16_PEAK_TFLOPS * 1e12)
@@ -629,7 +639,7 @@ def main():
     # ... and against the sum over the sequences of the bound that governs each (see per_sequence_roofline_us)
     roofline["per_sequence_bound_us"] = main_res["seq_roofline_us"]
     roofline["frac_of_per_sequence_bounds"] = main_res["seq_roofline_us"] * 1e-6 / kernel_s
-    roofline["traffic"] = measured_traffic(args.workload)
+    roofline["traffic"] = None if args.kv_fp8 else measured_traffic(args.workload)
     roofline["kernel"] = "ppd_mixed_kernel<128>"
     roofline["kernel_ms"] = main_res["mixed_kernel_ms"]
 
@@ -650,6 +660,18 @@ def main():
                             "tiles": r["plan"]["n_items"]}
         extras[args.workload] = {"us_per_step": main_res["ms_per_step"] * 1e3,
                                  "mixed_kernel_us": main_res["mixed_kernel_ms"] * 1e3}
+        # the same batches on FP8 E4M3 pages (extension beyond the paper: half the KV bytes; bf16 q, out, matrix math)
+        fp8_pages = {}
+        for name in ["cfg2_decode", "cfg4_decode_only", "cfg3_ap", "cfg4_mixed_ap"]:
+            r = run(name, few, fw, fp8=True)
+            ks = r["mixed_kernel_ms"] * 1e-3
+            fp8_pages[name] = {"us_per_step": r["ms_per_step"] * 1e3, "mixed_kernel_us": r["mixed_kernel_ms"] * 1e3,
+                               "kv_bytes_per_step": r["kv_bytes"], "hbm_GBs": r["kv_bytes"] / ks / 1e9,
+                               "hbm_frac": r["kv_bytes"] / ks / 1e9 / HBM_PEAK_GBS,
+                               "mfma_frac": r["flops"] / ks / 1e12 / MFMA_BF16_PEAK_TFLOPS,
+                               "speedup_vs_bf16_pages": (extras[name]["us_per_step"] / (r["ms_per_step"] * 1e3)
+                                                         if name in extras else None)}
+        extras["fp8_kv_pages"] = fp8_pages
         if "cfg4_decode_only" in extras and "cfg4_mixed_ap" in extras and "cfg4_mixed_full" in extras:
             base = extras["cfg4_decode_only"]["us_per_step"]
             extras["decode_step_slowdown"] = {
@@ -665,6 +687,7 @@ def main():
         "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
         "config": {"workload": args.workload, "sequences": main_res["sequences"], "new_token_rows": main_res["rows"],
                    "heads": "32q/8kv", "head_dim": 128, "page_size": 16, "seed": args.seed,
+                   "kv_pages": "fp8_e4m3" if args.kv_fp8 else "bf16",
                    "kv_bytes_per_step": b_bytes, "attention_flops_per_step": b_flops,
                    "tiles": main_res["plan"]["n_items"], "grid": main_res["plan"]["grid"],
                    "plan_host_us": main_res["plan"]["plan_host_us"],

@@ -818,7 +818,12 @@ __device__ __forceinline__ void narrow_item(const KParams& P, const ppd_work_ite
     };
 
     // K of NK - 1 pages and V of NV - 1 pages (4 KiB each at D = 128) are in flight per wave while one page is being
-    // computed; the register sets rotate (period = NK * NV steps, unrolled)
+    // computed; the register sets rotate (period = NK * NV steps, unrolled).  The loads sit under conditions, so at
+    // the points where paths meet the compiler's waits on the memory counter assume the path with the fewest loads
+    // issued and mostly drain what was just issued.  That costs nothing here: a loop without any conditional load
+    // (waits of 36..47 outstanding loads in its steady state) was built and measured the same -- a compute unit
+    // pulls at most ~58 GB/s from HBM however much it keeps in flight (a load-only kernel with 4 KiB or 28 KiB in
+    // flight per wave, 8 or 16 waves: 54..60 GB/s per unit), and eight waves with one page each are already there.
     if (my_steps > 0) {
         ids_cur = load_ids(0);
         if (my_steps > 64) ids_nxt = load_ids(1);
@@ -940,7 +945,7 @@ __device__ __forceinline__ void rearm_cursors(const KParams& P, int q0, int q1, 
 template <int HD, bool FP8>
 __global__ __launch_bounds__(kThreads, 2) void ppd_mixed_kernel(const KParams P) {
     // register sets of a streaming wave: a page of codes is half the registers, so FP8 pages keep more pages in flight
-    constexpr int NSETS = FP8 ? 6 : 4;
+    constexpr int NSETS = FP8 ? kFp8StreamSets : 4;
     // Dynamic LDS: rings of kStages + 1 stages of 4 pages of K and as many of V, then the page ids of a tile's key
     // range, for the MFMA path (136 KiB at HD = 128); the narrow path's combine buffer (kWaves * 16 * (HD+2)
     // floats) uses the front of it.

@@ -64,22 +64,27 @@ struct RowBlock { int64_t vis_end; int32_t nrows; };
 // fills a compute unit (8 waves of up to 256 registers), so the two kinds are split by physical unit.  Narrow tiles are bound by the bytes a unit keeps in flight (about 45 GB/s each), MFMA tiles
 // by compute (about 2.3 us per 64 keys of a row block): the split is sized so that both kinds finish together;
 // whoever finishes first steals from the other anyway.
-static int narrow_units(double narrow_bytes, double mfma_iters) {
+// A unit streams FP8 pages at about 28 GB/s: the tile does the same work per key for half the bytes, and is bound by
+// the instructions it issues per key rather than by what the unit can pull from memory (about 58 GB/s).
+static double unit_bytes_per_us(int elem_bytes) { return elem_bytes == 1 ? 28e3 : 45e3; }
+
+static int narrow_units(double narrow_bytes, double mfma_iters, int elem_bytes) {
     if (narrow_bytes == 0) return 0;
     if (mfma_iters == 0) return 32;
-    const double narrow_cu_us = narrow_bytes / 45e3;  // CU-microseconds at 45 GB/s per unit
+    const double narrow_cu_us = narrow_bytes / unit_bytes_per_us(elem_bytes);  // CU-microseconds
     const double mfma_us = mfma_iters * 2.3 / kWgPerCu;
     const int cus = (int)std::lround(32.0 * narrow_cu_us / (narrow_cu_us + mfma_us));
     return std::min(std::max(cus, 2), 20);            // HBM saturates well before all units stream
 }
 
 static int64_t choose_mfma_chunk(const std::vector<RowBlock>& blocks, int G, int Hkv, int D, int slots,
-                                 double narrow_bytes) {
+                                 double narrow_bytes, int elem_bytes) {
     constexpr double kTileStartUs = 16.0;
     // 1.7 us per 64 keys at D = 128; at D = 64 the two products halve and the softmax stays (measured ~0.65x)
     const double kTileIterUs = 1.7 * (0.3 + 0.7 * D / 128.0);
     constexpr double kMergeLaunchUs = 12.0, kPartialBytesPerUs = 2.5e6;
-    constexpr double kUnitBytesPerUs = 45e3, kHbmBytesPerUs = 6.5e6;
+    constexpr double kHbmBytesPerUs = 6.5e6;
+    const double kUnitBytesPerUs = unit_bytes_per_us(elem_bytes);
     static const int64_t kCandidates[] = {32768, 24576, 16384, 12288, 8192, 6144, 4096, 3072, 2048, 1024, 512};
     const double narrow_work = narrow_bytes / kUnitBytesPerUs;  // unit-microseconds
     const double narrow_floor = narrow_bytes / kHbmBytesPerUs;  // however many units stream
@@ -102,7 +107,7 @@ static int64_t choose_mfma_chunk(const std::vector<RowBlock>& blocks, int G, int
             if (nsplit > 1) partial_bytes += (double)rb.nrows * G * (D + 2) * 4.0 * nsplit * Hkv;
         }
         // the workgroups that take MFMA tiles first, as the launch will split them
-        const int S = std::max(1, slots - narrow_units(narrow_bytes, iters) * slots / 32);
+        const int S = std::max(1, slots - narrow_units(narrow_bytes, iters, elem_bytes) * slots / 32);
         std::sort(tiles.begin(), tiles.end(), std::greater<double>());
         load.assign((size_t)S, 0.0);  // min-heap of workgroup finish times; the earliest workgroup takes the next tile
         for (double t : tiles)
@@ -139,7 +144,8 @@ static int64_t choose_mfma_chunk(const std::vector<RowBlock>& blocks, int G, int
 // (1..16 sequences x 4K..256K context x six split sizes; log-error 11 % rms, the pick within 3 % of the best
 // measured size in all 19 batches).
 static int64_t choose_narrow_chunk(const std::vector<int64_t>& lengths, int Hkv, int D, int slots, int elem_bytes) {
-    constexpr double kStartUs = 7.0, kUnitBytesPerUs = 55e3, kHbmBytesPerUs = 7.0e6;
+    constexpr double kStartUs = 7.0, kHbmBytesPerUs = 7.0e6;
+    const double kUnitBytesPerUs = elem_bytes == 1 ? 33e3 : 55e3;
     constexpr double kMergeUs = 4.0, kMergeSplitUs = 0.3;
     static const int64_t kCandidates[] = {8192, 6144, 4096, 3072, 2048, 1536, 1024, 768, 512};
     const double bytes_per_key = 2.0 * D * elem_bytes;
@@ -239,7 +245,7 @@ ppd_status build_plan(const ppd_shape& s, const int32_t* L, const int32_t* n, in
         narrow_chunk = choose_narrow_chunk(narrow_lengths, Hkv, D, slots, o.kv_elem_bytes == 1 ? 1 : 2);
     int64_t mfma_chunk = o.mfma_chunk;
     if (mfma_chunk == 0 && !row_blocks.empty())
-        mfma_chunk = choose_mfma_chunk(row_blocks, G, Hkv, D, slots, narrow_tokens * kv_tok_bytes_head);
+        mfma_chunk = choose_mfma_chunk(row_blocks, G, Hkv, D, slots, narrow_tokens * kv_tok_bytes_head, o.kv_elem_bytes == 1 ? 1 : 2);
     if (mfma_chunk == 0) mfma_chunk = kMaxMfmaChunk;
 
     struct Keyed { double cost; ppd_work_item it; };
@@ -383,7 +389,7 @@ ppd_status build_plan(const ppd_shape& s, const int32_t* L, const int32_t* n, in
             if (k.it.kind == 0) narrow_bytes += toks * kv_tok_bytes_head;
             else mfma_iters += std::ceil(toks / kTileTokens);
         }
-        plan->narrow_cus = o.narrow_cus >= 0 ? std::min(o.narrow_cus, 32) : narrow_units(narrow_bytes, mfma_iters);
+        plan->narrow_cus = o.narrow_cus >= 0 ? std::min(o.narrow_cus, 32) : narrow_units(narrow_bytes, mfma_iters, o.kv_elem_bytes == 1 ? 1 : 2);
     }
 
     ppd_plan_stats& st = plan->stats;

@@ -269,15 +269,28 @@ def new_token_slots(b):
     return b.new_part()[2]
 
 
-def device_workload(b, torch, device, seed=0):
-    """Device tensors of a shapes-only batch b (made with with_data=False)."""
+FP8_BENCH_SCALE = 2.0 ** -5  # K and V scale of the FP8 workloads: N(0,1) values / scale stay far below 448
+
+
+def device_workload(b, torch, device, seed=0, fp8=False):
+    """Device tensors of a shapes-only batch b (made with with_data=False).  fp8: the resident pool holds one-byte
+    FP8 E4M3 codes instead of bf16 values -- the codes of N(0,1) / FP8_BENCH_SCALE numbers through the tensor
+    library's own cast (resident data only: any valid code would do; the new tokens still arrive as bf16)."""
     gen = torch.Generator(device=device)
     gen.manual_seed(10_000 + seed)
     page_elems = 2 * b.Hkv * b.P * b.D
-    pool = torch.empty((b.num_pages * page_elems,), dtype=torch.bfloat16, device=device)
     step = 1 << 28
-    for a in range(0, pool.numel(), step):
-        pool[a:a + step].normal_(generator=gen)
+    if fp8:
+        pool = torch.empty((b.num_pages * page_elems,), dtype=torch.uint8, device=device)
+        for a in range(0, pool.numel(), step):
+            e = min(a + step, pool.numel())
+            x = torch.empty((e - a,), dtype=torch.float32, device=device).normal_(generator=gen)
+            pool[a:e] = (x / FP8_BENCH_SCALE).clamp_(-448.0, 448.0).to(torch.float8_e4m3fn).view(torch.uint8)
+            del x
+    else:
+        pool = torch.empty((b.num_pages * page_elems,), dtype=torch.bfloat16, device=device)
+        for a in range(0, pool.numel(), step):
+            pool[a:a + step].normal_(generator=gen)
     q = torch.empty((b.T, b.Hq, b.D), dtype=torch.bfloat16, device=device).normal_(generator=gen)
     k_new = torch.empty((b.T, b.Hkv, b.D), dtype=torch.bfloat16, device=device).normal_(generator=gen)
     v_new = torch.empty((b.T, b.Hkv, b.D), dtype=torch.bfloat16, device=device).normal_(generator=gen)
@@ -305,9 +318,15 @@ def compact_subbatch(b, seq_ids, pool_dev, q_dev, torch):
     for i, p in enumerate(pts):
         pt[i, :len(p)] = p
     idx = torch.from_numpy(np.concatenate(pages)).to(pool_dev.device)
-    sub_pool = pool_dev.view(torch.int16).view(b.num_pages, page_elems).index_select(0, idx).cpu().numpy()
+    if pool_dev.dtype == torch.uint8:   # FP8 pages: one-byte codes
+        sub_pool8 = pool_dev.view(b.num_pages, page_elems).index_select(0, idx).cpu().numpy().reshape(-1)
+    else:
+        sub_pool8 = None
+        sub_pool = pool_dev.view(torch.int16).view(b.num_pages, page_elems).index_select(0, idx).cpu().numpy()
     rows = np.concatenate([np.arange(b.row_off[s], b.row_off[s + 1]) for s in seq_ids])
     q = q_dev.view(torch.int16)[torch.from_numpy(rows).to(q_dev.device)].cpu().numpy().view(np.uint16)
     sub = MixedBatch(name=b.name + "_sub", Hq=b.Hq, Hkv=b.Hkv, D=b.D, P=b.P, num_pages=at, scale=b.scale,
                      L=b.L[seq_ids], n=b.n[seq_ids], page_tables=pt, q=q)
+    if sub_pool8 is not None:
+        return sub, sub_pool8, rows
     return sub, sub_pool.view(np.uint16).reshape(-1), rows
