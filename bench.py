@@ -220,7 +220,7 @@ def cpu_baseline(runner, budget_s=15.0):
             "max_abs_err_vs_gpu": err}
 
 
-def run_trace(torch, seed, max_steps, pool_gb, turns=5):
+def run_trace(torch, seed, max_steps, pool_gb, turns=5, options=None):
     """Multi-turn trace on a 70B-class GQA layer (64 q / 8 kv heads): every engine step = one KV append plus one
     mixed attention over all active conversations, pages drawn at random from a large shared pool."""
     import paper_2603_13358_amd as ppd
@@ -240,6 +240,8 @@ def run_trace(torch, seed, max_steps, pool_gb, turns=5):
         at += int(need[c])
     dev = torch.device("cuda:0")
     ctx = ppd.Context(Hq, Hkv, D, num_pages)
+    for k_, v_ in (options or {}).items():
+        ctx.set_option(k_, v_)
     pool = torch.empty((num_pages * page_bytes // 2,), dtype=torch.bfloat16, device=dev)   # contents: whatever
     # only the pages in use need defined values
     pool.view(num_pages, -1)[torch.from_numpy(pages.astype(np.int64)).to(dev)] = 0
@@ -580,7 +582,7 @@ def main():
     options = {kv.split("=")[0]: int(kv.split("=")[1]) for kv in args.opt}
     if args.trace:
         print(json.dumps({"workload": "cfg5_multi_turn_trace", "trace": run_trace(torch, args.seed, args.trace_steps,
-                                                                                 args.trace_pool_gb, args.turns)}))
+                                                                                 args.trace_pool_gb, args.turns, options)}))
         return
     if args.landing:
         print(json.dumps({"workload": "kv_landing_5115_tokens_32_layers", "landing": run_landing(torch, args.seed, args.steps)}))
