@@ -22,12 +22,13 @@ def _edge_rows(n_i, rows_per_block, cap=None):
     return sorted(pick)
 
 
-def _run_and_check(name, seq_ids_fn, rows_per_seq=4, edge_rows=False, edge_cap=None):
+def _run_and_check(name, seq_ids_fn, rows_per_seq=4, edge_rows=False, edge_cap=None, fp8=False):
     import torch
     import bench
     b = bench.make_shapes(name, 0) if isinstance(name, str) else name
     print("workload", b.name, "B", b.B, "T", b.T, flush=True)
-    r = bench.Runner(b, torch, 0)
+    r = bench.Runner(b, torch, 0, fp8=fp8)   # fp8: FP8 E4M3 pages, the scale of the benchmark for K and for V
+    sc = si.FP8_BENCH_SCALE
     w = r.w
     seqs = seq_ids_fn(b)
     # pages of the sampled sequences before the append
@@ -43,7 +44,10 @@ def _run_and_check(name, seq_ids_fn, rows_per_seq=4, edge_rows=False, edge_cap=N
     v_new = w["v_new"].view(torch.int16)[idx].cpu().numpy().view(np.uint16)
     slots = np.concatenate([sub.slots(i, int(sub.L[i]), int(sub.L[i] + sub.n[i])) for i in range(sub.B)])
     ref_pool = pool_before.copy()
-    oracle.kv_append(k_new, v_new, ref_pool, slots, sub.Hkv, sub.D, sub.P, sub.num_pages)
+    if fp8:
+        oracle.kv_append_fp8(k_new, v_new, ref_pool, slots, sub.Hkv, sub.D, sub.P, sub.num_pages, sc, sc)
+    else:
+        oracle.kv_append(k_new, v_new, ref_pool, slots, sub.Hkv, sub.D, sub.P, sub.num_pages)
     assert np.array_equal(ref_pool, pool_after), "KV append is not bit-exact at full size"
     # --- attention on sampled rows
     mask = np.zeros(sub.T, np.uint8)
@@ -53,8 +57,12 @@ def _run_and_check(name, seq_ids_fn, rows_per_seq=4, edge_rows=False, edge_cap=N
         if edge_rows:
             pick = sorted(set(pick) | set(_edge_rows(n_i, 256 // (sub.Hq // sub.Hkv), edge_cap)))
         mask[int(sub.row_off[i]) + np.asarray(pick)] = 1
-    ref = oracle.mixed_attention(sub.q, pool_after, sub.page_tables, sub.L, sub.n, sub.Hq, sub.Hkv, sub.D, sub.P,
-                                 sub.num_pages, sub.scale, row_mask=mask)
+    if fp8:
+        ref = oracle.mixed_attention_fp8(sub.q, pool_after, sc, sc, sub.page_tables, sub.L, sub.n, sub.Hq, sub.Hkv, sub.D,
+                                         sub.P, sub.num_pages, sub.scale, row_mask=mask)
+    else:
+        ref = oracle.mixed_attention(sub.q, pool_after, sub.page_tables, sub.L, sub.n, sub.Hq, sub.Hkv, sub.D, sub.P,
+                                     sub.num_pages, sub.scale, row_mask=mask)
     got = out1.float().cpu().numpy()[rows]
     sel = mask.astype(bool)
     worst = check_close(got[sel], ref[sel])
@@ -87,6 +95,18 @@ def test_cfg4_mixed_full_size():
     """Every sequence of the batch: all 128 decode rows; of every append-prefill the first and last row, the rows
     either side of each 64-row block edge and a few in between; KV append bit-exact on every page of the batch."""
     _run_and_check("cfg4_mixed_ap", lambda b: list(range(b.B)), rows_per_seq=4, edge_rows=True)
+
+
+def test_cfg2_decode_full_size_fp8_pages():
+    """The decode batch on FP8 E4M3 pages (extension beyond the paper): every sequence, codes of the append bit for bit."""
+    _run_and_check("cfg2_decode", lambda b: list(range(b.B)), fp8=True)
+
+
+def test_cfg4_mixed_full_size_fp8_pages():
+    """The mixed batch on FP8 pages: every 4th decode sequence and every append-prefill with its block-edge rows."""
+    def pick(b):
+        return [i for i in range(b.B) if b.n[i] > 1] + [i for i in range(b.B) if b.n[i] == 1][::4]
+    _run_and_check("cfg4_mixed_ap", pick, rows_per_seq=4, edge_rows=True, edge_cap=8, fp8=True)
 
 
 def test_cfg4_full_prefill_variant_full_size():
