@@ -64,8 +64,8 @@ struct RowBlock { int64_t vis_end; int32_t nrows; };
 // fills a compute unit (8 waves of up to 256 registers), so the two kinds are split by physical unit.  Narrow tiles are bound by the bytes a unit keeps in flight (about 45 GB/s each), MFMA tiles
 // by compute (about 2.3 us per 64 keys of a row block): the split is sized so that both kinds finish together;
 // whoever finishes first steals from the other anyway.
-// A unit streams FP8 pages at about 28 GB/s: the tile does the same work per key for half the bytes, and is bound by
-// the instructions it issues per key rather than by what the unit can pull from memory (about 58 GB/s).
+// A unit streams FP8 pages at about 28 GB/s: its loads are 8 and 4 bytes per lane instead of 16 and 8, and a unit's
+// memory pipeline moves fewer bytes per second with narrower loads (about 58 GB/s at best, with contiguous 16-byte loads).
 static double unit_bytes_per_us(int elem_bytes) { return elem_bytes == 1 ? 28e3 : 45e3; }
 
 static int narrow_units(double narrow_bytes, double mfma_iters, int elem_bytes) {
