@@ -326,9 +326,11 @@ def run_trace(torch, seed, max_steps, pool_gb, turns=5, options=None):
                     "planning and upload; 70B-class layer 64q/8kv heads, D=128"}
 
 
-def run_landing(torch, seed, steps):
+def run_landing(torch, seed, steps, fp8=False):
     """KV landing of one transferred request: 5115 tokens (the context length the paper quotes for its ~670 MB
-    example) x 32 layers of an 8-KV-head, D=128 model scattered into 32 per-layer page pools in one launch."""
+    example) x 32 layers of an 8-KV-head, D=128 model scattered into 32 per-layer page pools in one launch.
+    fp8: the pools hold FP8 E4M3 pages (extension beyond the paper): the landing quantises on the way."""
+    import synthetic_inputs as si
     import oracle
     import paper_2603_13358_amd as ppd
     layers, T, Hkv, D, P = 32, 5115, 8, 128, 16
@@ -340,9 +342,11 @@ def run_landing(torch, seed, steps):
     dev = torch.device("cuda:0")
     pe = num_pages * 2 * Hkv * P * D
     ctx = ppd.Context(32, Hkv, D, num_pages)
+    if fp8:
+        ctx.set_kv_format(ppd.PPD_KV_FP8_E4M3, si.FP8_BENCH_SCALE, si.FP8_BENCH_SCALE)
     k = torch.empty((layers, T, Hkv, D), dtype=torch.bfloat16, device=dev).normal_()
     v = torch.empty((layers, T, Hkv, D), dtype=torch.bfloat16, device=dev).normal_()
-    pools = torch.zeros((layers * pe,), dtype=torch.bfloat16, device=dev)
+    pools = torch.zeros((layers * pe,), dtype=torch.uint8 if fp8 else torch.bfloat16, device=dev)
     slots_d = torch.from_numpy(slots).to(dev)
     stream = torch.cuda.current_stream().cuda_stream
     for _ in range(3):
@@ -371,15 +375,19 @@ def run_landing(torch, seed, steps):
     # oracle on the host: 4 layers, scaled
     kh = k[:4].view(torch.int16).cpu().numpy().view(np.uint16)
     vh = v[:4].view(torch.int16).cpu().numpy().view(np.uint16)
-    ref = np.zeros(4 * pe, np.uint16)
+    ref = np.zeros(4 * pe, np.uint8 if fp8 else np.uint16)
     t0 = time.perf_counter()
-    oracle.kv_land(kh, vh, ref, pe, 4, slots, Hkv, D, P, num_pages)
+    if fp8:
+        oracle.kv_land_fp8(kh, vh, ref, pe, 4, slots, Hkv, D, P, num_pages, si.FP8_BENCH_SCALE, si.FP8_BENCH_SCALE)
+    else:
+        oracle.kv_land(kh, vh, ref, pe, 4, slots, Hkv, D, P, num_pages)
     cpu_s = (time.perf_counter() - t0) * layers / 4
-    got = pools[:4 * pe].view(torch.int16).cpu().numpy().view(np.uint16)
+    got = pools[:4 * pe].cpu().numpy() if fp8 else pools[:4 * pe].view(torch.int16).cpu().numpy().view(np.uint16)
     ctx.close()
-    return {"tokens": T, "layers": layers, "payload_bytes": moved, "us": us,
-            "achieved_GBs_read_plus_write": 2 * moved / (us * 1e-6) / 1e9,
-            "hbm_frac": 2 * moved / (us * 1e-6) / 1e9 / HBM_PEAK_GBS,
+    rw = moved + moved // 2 if fp8 else 2 * moved   # bytes read + bytes written
+    return {"tokens": T, "layers": layers, "payload_bytes": moved, "kv_pages": "fp8_e4m3" if fp8 else "bf16", "us": us,
+            "achieved_GBs_read_plus_write": rw / (us * 1e-6) / 1e9,
+            "hbm_frac": rw / (us * 1e-6) / 1e9 / HBM_PEAK_GBS,
             "plain_copy_of_same_payload_us": copy_us,
             "plain_copy_GBs_read_plus_write": 2 * moved / (copy_us * 1e-6) / 1e9,
             "frac_of_plain_copy": copy_us / us, "bit_exact_vs_oracle_4_layers": bool(np.array_equal(got, ref)),
@@ -585,7 +593,7 @@ def main():
                                                                                  args.trace_pool_gb, args.turns, options)}))
         return
     if args.landing:
-        print(json.dumps({"workload": "kv_landing_5115_tokens_32_layers", "landing": run_landing(torch, args.seed, args.steps)}))
+        print(json.dumps({"workload": "kv_landing_5115_tokens_32_layers", "landing": run_landing(torch, args.seed, args.steps, fp8=args.kv_fp8)}))
         return
     if args.route_table:
         w = [float(x) for x in args.route_weights.split(",")]
