@@ -43,6 +43,8 @@
  *  A (page, head) block of K or V is P*D*2 bytes contiguous (4 KiB at D = 128); K keeps 8 consecutive d of
  *  a token in one 16-byte granule with the 16 tokens of a page adjacent, V keeps 8 consecutive tokens of
  *  one d in a granule: the two operand shapes the matrix cores consume without a transpose.
+ *  With ppd_set_kv_format(PPD_KV_FP8_E4M3) the same offsets address one-byte elements (FP8 codes): blocks and
+ *  granules are half as many bytes.
  */
 #ifndef PPD_H
 #define PPD_H

@@ -43,7 +43,7 @@ struct ppd_ctx {
     size_t d_items_bytes = 0;
     float* d_partials = nullptr;
     size_t d_partials_floats = 0;
-    uint32_t* d_counters = nullptr;  // kCounterWords words: error flags, finished count, timing sums; queue cursors
+    uint32_t* d_counters = nullptr;  // kCounterWords words: error flags, finished-workgroup counts, queue cursors
     Staging staging[kStagingSlots];
     int next_slot = 0;
     // the plan on the device stays valid while L, n and the planner options do not change (the layers of one
