@@ -39,9 +39,9 @@ constexpr int kStreamThreads = 64 * kStreamWaves;
 constexpr int kStreamKSets = PPD_STREAM_KSETS;
 constexpr int kStreamVSets = PPD_STREAM_VSETS;
 #ifndef PPD_FP8_SETS
-#define PPD_FP8_SETS 6
+#define PPD_FP8_SETS 2
 #endif
-constexpr int kFp8StreamSets = PPD_FP8_SETS;  // rotating register sets of a streaming wave on FP8 pages (a set is half as large)
+constexpr int kFp8StreamSets = PPD_FP8_SETS;  // rotating register sets (one page pair each) of a streaming wave on FP8 pages
 constexpr int kXcds = 8;             // MFMA tile queues, one per XCD (each XCD has its own L2)
 constexpr int kNarrowQueue = kXcds;  // index of the narrow-tile queue
 // Very short narrow tiles of a launch that has very many of them are handed out kWaves at a time (one claim), each

@@ -924,6 +924,276 @@ __device__ __forceinline__ void narrow_item(const KParams& P, const ppd_work_ite
     }
 }
 
+// ---------------------------------------------------------------------------------------------------
+// Narrow tile on the operand shapes of the row-block tile: v_mfma_f32_32x32x16_bf16 for both products, two pages (32
+// keys) per step, operands loaded from the pool straight into registers.  A lane then loads whole granules -- 8 d of one
+// key for K, 8 tokens of one d for V -- in runs of 256 and 512 contiguous bytes per half-wave, where the 16x16 shapes of
+// narrow_item make a lane own 4 tokens of a d (half a granule).  For FP8 pages that is 8 bytes per lane instead of 4 in
+// V, and a compute unit streams a third more (measured with loads alone: 45 against 33 GB/s; bf16 pages 53 against 48).
+// Half of the 32 columns of every product are unused (a narrow tile has at most 16), which costs matrix time the
+// memory-bound tile has to spare.  Used for FP8 pages.
+//   S^T rows: MFMA row r is key (page r >> 4 of the pair, token 8*bit2(r) + 4*bit3(r) + (r & 3)), so that accumulator
+//   registers 0..7 of a lane are tokens 8h..8h+7 of the first page and 8..15 those of the second (h = lane / 32):
+//   the octet the lane's V granules hold.
+// NS register sets of one page pair each rotate: NS - 1 pairs are in flight per wave.
+// ---------------------------------------------------------------------------------------------------
+template <int HD, int NW, int NS, bool SOLO, bool FP8>
+__device__ __forceinline__ void narrow_item_wide(const KParams& P, const ppd_work_item& it, char* smem) {
+    static_assert(!SOLO || NW == 1, "a solo tile is one wave");
+    constexpr int EB = FP8 ? 1 : 2;                       // bytes per pool element
+    using Vec = std::conditional_t<FP8, u32x2, u32x4>;    // a granule: 8 elements
+    constexpr int KS = HD / 16;   // k-steps of S^T
+    constexpr int DB = HD / 32;   // 32-row d blocks of O^T
+    constexpr int CB = NarrowCombine<NW>::CB;
+    constexpr int WSTRIDE = CB * (HD + 2);
+    constexpr int NT = NW * 64;
+
+    const int tid = threadIdx.x;
+    const int lane = tid & 63;
+    const int wave = SOLO ? 0 : __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int r = lane & 31;   // column of the products' B operands and results; key row / d row of the A operands
+    const int h = lane >> 5;
+    const int G = P.G;
+    const int ncols = it.nrows * G;
+    const int colc = r < ncols ? r : ncols - 1;
+    const int jrow = col_row(colc, P.invG);
+    const int head = it.kvh * G + (colc - jrow * G);
+    const int limit = it.L + it.row0 + jrow;
+    const int min_limit = it.L + it.row0;
+
+    bf16x8 qreg[KS];  // Q^T operand: column r, d = ks*16 + h*8 .. +8; zero for the unused columns
+    {
+        const uint16_t* qp = P.q + ((int64_t)(it.grow0 + jrow) * P.Hq + head) * HD + h * 8;
+#pragma unroll
+        for (int ks = 0; ks < KS; ++ks) {
+            u32x4 w = *reinterpret_cast<const u32x4*>(qp + ks * 16);
+            if (r >= ncols) w = u32x4{0, 0, 0, 0};
+            qreg[ks] = as_bf16x8(w);
+        }
+    }
+
+    const int32_t* pt_row = P.page_tables + (int64_t)it.seq * P.max_pages;
+    const int last_page = (it.kv_total - 1) >> 4;
+    const int npages = (it.kv_end - it.kv_begin + kPage - 1) >> 4;
+    const int s_lo = wave * npages / NW, s_hi = (wave + 1) * npages / NW;
+    const int my_pages = s_hi - s_lo;
+    const int my_steps = (my_pages + 1) >> 1;  // page pairs; the last may lack its second page
+    const int wave_first_page = (it.kv_begin >> 4) + s_lo;
+    const int64_t head_off = (int64_t)it.kvh * (kPage * HD);
+    const int64_t v_off = (int64_t)P.Hkv * (kPage * HD);
+
+    f32x16 oacc[DB];
+#pragma unroll
+    for (int db = 0; db < DB; ++db)
+#pragma unroll
+        for (int i = 0; i < 16; ++i) oacc[db][i] = 0.f;
+    float m_run = NEG_INF, l_run = 0.f;
+    const float c = P.scale_log2e;
+
+    // lane i of ids_cur holds the page of logical page (batch*64 + i) of this wave's range; a pair never straddles batches
+    int ids_cur = 0, ids_nxt = 0;
+    auto load_ids = [&](int batch) { return load_page_id(pt_row, wave_first_page + batch * 64 + lane, last_page); };
+    struct Set {
+        Vec k[KS];      // K operand of the pair: 32 keys x 16 d per k-step
+        Vec v[2][DB];   // V^T operand of each page: 32 d x 8 tokens (the lane's octet) per d block
+    };
+    Set rs[NS];
+    const int k_tok = ((r >> 2) & 1) * 8 + ((r >> 3) & 1) * 4 + (r & 3);
+    const uint32_t k_lane_bytes = (uint32_t)(h * 128 + k_tok * 8) * EB;   // + ks * 256 elements
+    const uint32_t v_lane_bytes = (uint32_t)((h * HD + r) * 8) * EB;      // + db * 256 elements
+    auto issue = [&](int j, Set& s) {  // j = pair index relative to s_lo
+        const int pg0 = 2 * j;
+        if ((pg0 & 63) == 0 && pg0 > 0) {
+            ids_cur = ids_nxt;
+            if (pg0 + 64 < my_pages) ids_nxt = load_ids((pg0 >> 6) + 1);
+        }
+        const int id_a = __builtin_amdgcn_readlane(ids_cur, pg0 & 63);
+        const int id_b = pg0 + 1 < my_pages ? __builtin_amdgcn_readlane(ids_cur, (pg0 + 1) & 63) : id_a;  // absent: re-read the first
+        const char* base_a = reinterpret_cast<const char*>(P.pool) + (checked_page(P, id_a) * P.page_stride + head_off) * EB;
+        const char* base_b = reinterpret_cast<const char*>(P.pool) + (checked_page(P, id_b) * P.page_stride + head_off) * EB;
+        const char* kb = ((r & 16) ? base_b : base_a) + k_lane_bytes;
+#pragma unroll
+        for (int ks = 0; ks < KS; ++ks) s.k[ks] = __builtin_nontemporal_load(reinterpret_cast<const Vec*>(kb + ks * (256 * EB)));
+        const char* va = base_a + v_off * EB + v_lane_bytes;
+        const char* vb = base_b + v_off * EB + v_lane_bytes;
+#pragma unroll
+        for (int db = 0; db < DB; ++db) s.v[0][db] = __builtin_nontemporal_load(reinterpret_cast<const Vec*>(va + db * (256 * EB)));
+#pragma unroll
+        for (int db = 0; db < DB; ++db) s.v[1][db] = __builtin_nontemporal_load(reinterpret_cast<const Vec*>(vb + db * (256 * EB)));
+    };
+    auto operand = [&](Vec v) {
+        if constexpr (FP8) return as_bf16x8(fp8x8_to_bf16x8(v)); else return as_bf16x8(v);
+    };
+    auto compute_step = [&](int j, Set& s) {
+        f32x16 sa;
+#pragma unroll
+        for (int i = 0; i < 16; ++i) sa[i] = 0.f;
+#pragma unroll
+        for (int ks = 0; ks < KS; ++ks) sa = __builtin_amdgcn_mfma_f32_32x32x16_bf16(operand(s.k[ks]), qreg[ks], sa, 0, 0, 0);
+        // sa[i]: token 8*h + (i & 7) of page i >> 3 of the pair
+        const int t0 = it.kv_begin + (s_lo + 2 * j) * kPage;
+        const bool has_b = 2 * j + 1 < my_pages;
+        if (t0 + 2 * kPage - 1 > min_limit || t0 + 2 * kPage > it.kv_end || !has_b) {
+#pragma unroll
+            for (int i = 0; i < 16; ++i) {
+                const int pos = t0 + (i >> 3) * kPage + h * 8 + (i & 7);
+                if (pos > limit || pos >= it.kv_end || ((i >> 3) && !has_b)) sa[i] = NEG_INF;
+            }
+            if (t0 + 2 * kPage > it.kv_total || !has_b) {  // rows never written, or the page that is not there
+#pragma unroll
+                for (int pg = 0; pg < 2; ++pg)
+#pragma unroll
+                    for (int db = 0; db < DB; ++db)
+#pragma unroll
+                        for (int e = 0; e < 8; ++e) {
+                            const int pos = t0 + pg * kPage + h * 8 + e;
+                            if (pos >= it.kv_total || (pg && !has_b)) {
+                                if constexpr (FP8) s.v[pg][db][e >> 2] &= ~(0xFFu << (8 * (e & 3)));  // code 0 is 0.0
+                                else s.v[pg][db][e >> 1] &= (e & 1) ? 0x0000FFFFu : 0xFFFF0000u;
+                            }
+                        }
+            }
+        }
+        float mx = sa[0];
+#pragma unroll
+        for (int i = 1; i < 16; ++i) mx = fmaxf(mx, sa[i]);
+        mx = max_halves(mx);
+        const float m_new = fmaxf(m_run, mx);
+        if (__any((m_new - m_run) * c > kLazyRescale)) {
+            const float m_use = m_new == NEG_INF ? 0.f : m_new;
+            const float alpha = fast_exp2(m_run * c - m_use * c);
+            l_run *= alpha;
+#pragma unroll
+            for (int db = 0; db < DB; ++db)
+#pragma unroll
+                for (int i = 0; i < 16; ++i) oacc[db][i] *= alpha;
+            m_run = m_new;
+        }
+        const float mc = m_run == NEG_INF ? 0.f : m_run * c;
+        u32x4 pw[2];
+        float psum = 0.f;
+#pragma unroll
+        for (int pg = 0; pg < 2; ++pg)
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                const float p0 = fast_exp2(__builtin_fmaf(sa[pg * 8 + 2 * e], c, -mc));
+                const float p1 = fast_exp2(__builtin_fmaf(sa[pg * 8 + 2 * e + 1], c, -mc));
+                psum += p0 + p1;
+                pw[pg][e] = pack_bf16(p0, p1);
+            }
+        l_run += psum;
+#pragma unroll
+        for (int pg = 0; pg < 2; ++pg)
+#pragma unroll
+            for (int db = 0; db < DB; ++db)
+                oacc[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(operand(s.v[pg][db]), as_bf16x8(pw[pg]), oacc[db], 0, 0, 0);
+    };
+
+    if (my_steps > 0) {
+        ids_cur = load_ids(0);
+        if (my_pages > 64) ids_nxt = load_ids(1);
+#pragma unroll
+        for (int j = 0; j < NS - 1; ++j)
+            if (j < my_steps) issue(j, rs[j]);
+    }
+    for (int k = 0; k < my_steps; k += NS) {
+#pragma unroll
+        for (int j = 0; j < NS; ++j) {
+            if (k + j < my_steps) {
+                if (k + j + NS - 1 < my_steps) issue(k + j + NS - 1, rs[(j + NS - 1) % NS]);
+                compute_step(k + j, rs[j]);
+            }
+        }
+    }
+    const float l_tot = sum_halves(l_run);
+
+    // O^T register i of block db is d = db*32 + (i/4)*8 + h*4 + i%4 of column r; m and l_tot are the column's in both halves
+    if constexpr (SOLO) {
+        if (r < ncols) {
+            if (it.part_off < 0) {
+                const float inv = P.v_scale / l_tot;
+                uint16_t* op = P.out + ((int64_t)(it.grow0 + jrow) * P.Hq + head) * HD + h * 4;
+#pragma unroll
+                for (int db = 0; db < DB; ++db)
+#pragma unroll
+                    for (int i4 = 0; i4 < 4; ++i4) {
+                        u32x2 w;
+                        w[0] = pack_bf16(oacc[db][i4 * 4 + 0] * inv, oacc[db][i4 * 4 + 1] * inv);
+                        w[1] = pack_bf16(oacc[db][i4 * 4 + 2] * inv, oacc[db][i4 * 4 + 3] * inv);
+                        *reinterpret_cast<u32x2*>(op + db * 32 + i4 * 8) = w;
+                    }
+            } else {
+                float* pp = P.partials + it.part_off;
+                float* po = pp + (int64_t)r * HD + h * 4;
+#pragma unroll
+                for (int db = 0; db < DB; ++db)
+#pragma unroll
+                    for (int i4 = 0; i4 < 4; ++i4) {
+                        const f32x4 w = {oacc[db][i4 * 4 + 0], oacc[db][i4 * 4 + 1], oacc[db][i4 * 4 + 2], oacc[db][i4 * 4 + 3]};
+                        *reinterpret_cast<f32x4*>(po + db * 32 + i4 * 8) = w;
+                    }
+                if (h == 0) {
+                    pp[(int64_t)ncols * HD + r * 2] = m_run;
+                    pp[(int64_t)ncols * HD + r * 2 + 1] = l_tot;
+                }
+            }
+        }
+        return;
+    }
+    // combine the waves through LDS, CB columns per pass (the buffer and the second half are those of narrow_item)
+    float* wbuf = reinterpret_cast<float*>(smem) + wave * WSTRIDE;
+    const float* all = reinterpret_cast<const float*>(smem);
+    for (int c0 = 0; c0 < ncols; c0 += CB) {
+        if (c0 > 0) __syncthreads();  // the previous pass has been read
+        if (r >= c0 && r < c0 + CB && r < ncols) {
+#pragma unroll
+            for (int db = 0; db < DB; ++db)
+#pragma unroll
+                for (int i4 = 0; i4 < 4; ++i4) {
+                    const f32x4 w = {oacc[db][i4 * 4 + 0], oacc[db][i4 * 4 + 1], oacc[db][i4 * 4 + 2], oacc[db][i4 * 4 + 3]};
+                    *reinterpret_cast<f32x4*>(wbuf + (r - c0) * HD + db * 32 + i4 * 8 + h * 4) = w;
+                }
+            if (h == 0) {
+                wbuf[CB * HD + (r - c0) * 2] = m_run;
+                wbuf[CB * HD + (r - c0) * 2 + 1] = l_tot;
+            }
+        }
+        __syncthreads();
+        const int nc = ncols - c0 < CB ? ncols - c0 : CB;
+        for (int idx = tid; idx < nc * HD; idx += NT) {
+            const int cl = idx / HD, d = idx % HD;
+            const int col = c0 + cl;
+            float mw[NW], mm = NEG_INF;
+#pragma unroll
+            for (int w = 0; w < NW; ++w) {
+                mw[w] = all[w * WSTRIDE + CB * HD + cl * 2];
+                mm = fmaxf(mm, mw[w]);
+            }
+            float o = 0.f, l = 0.f;
+#pragma unroll
+            for (int w = 0; w < NW; ++w) {
+                const float f = mw[w] == NEG_INF ? 0.f : fast_exp2((mw[w] - mm) * c);
+                o += f * all[w * WSTRIDE + cl * HD + d];
+                l += f * all[w * WSTRIDE + CB * HD + cl * 2 + 1];
+            }
+            if (it.part_off < 0) {
+                const int crow = col_row(col, P.invG);
+                const int64_t orow = (int64_t)(it.grow0 + crow) * P.Hq + it.kvh * G + (col - crow * G);
+                const float val = (o / l) * P.v_scale;
+                const float other = __shfl_xor(val, 1, 64);  // d and d^1 sit in neighbouring lanes
+                if ((d & 1) == 0) *reinterpret_cast<uint32_t*>(P.out + orow * HD + d) = pack_bf16(val, other);
+            } else {
+                float* pp = P.partials + it.part_off;
+                pp[(int64_t)col * HD + d] = o;
+                if (d == 0) {
+                    pp[(int64_t)ncols * HD + col * 2] = mm;
+                    pp[(int64_t)ncols * HD + col * 2 + 1] = l;
+                }
+            }
+        }
+    }
+}
+
 // Claims the next tile of queue q: its index in the work list, or -1 when the queue is exhausted.  A claim on the
 // wave-tile queue covers kWaves consecutive tiles and returns the index of the first.
 __device__ __forceinline__ int claim_from(const KParams& P, int q) {
@@ -1033,15 +1303,18 @@ __global__ __launch_bounds__(kThreads, 2) void ppd_mixed_kernel(const KParams P)
             const int mine = idx + __builtin_amdgcn_readfirstlane(tid >> 6);
             if (mine < P.queue_begin[kQueues]) {
                 const ppd_work_item it = P.items[mine];
-                narrow_item<HD, 1, NSETS, NSETS, true, FP8>(P, it, smem);
+                if constexpr (FP8) narrow_item_wide<HD, 1, kFp8StreamSets, true, true>(P, it, smem);
+                else narrow_item<HD, 1, NSETS, NSETS, true, FP8>(P, it, smem);
             }
             continue;
         }
         const ppd_work_item it = P.items[idx];
-        if (it.kind == 0)
-            narrow_item<HD, kWaves, NSETS, NSETS, false, FP8>(P, it, smem);
-        else
+        if (it.kind == 0) {
+            if constexpr (FP8) narrow_item_wide<HD, kWaves, kFp8StreamSets, false, true>(P, it, smem);
+            else narrow_item<HD, kWaves, NSETS, NSETS, false, FP8>(P, it, smem);
+        } else {
             mfma_item<HD, false, FP8>(P, it, smem);
+        }
     }
     if (tid == 0) rearm_cursors(P, 0, kCursors, 10);
 }

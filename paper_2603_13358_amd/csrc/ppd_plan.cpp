@@ -64,9 +64,9 @@ struct RowBlock { int64_t vis_end; int32_t nrows; };
 // fills a compute unit (8 waves of up to 256 registers), so the two kinds are split by physical unit.  Narrow tiles are bound by the bytes a unit keeps in flight (about 45 GB/s each), MFMA tiles
 // by compute (about 2.3 us per 64 keys of a row block): the split is sized so that both kinds finish together;
 // whoever finishes first steals from the other anyway.
-// A unit streams FP8 pages at about 28 GB/s: its loads are 8 and 4 bytes per lane instead of 16 and 8, and a unit's
-// memory pipeline moves fewer bytes per second with narrower loads (about 58 GB/s at best, with contiguous 16-byte loads).
-static double unit_bytes_per_us(int elem_bytes) { return elem_bytes == 1 ? 28e3 : 45e3; }
+// A unit streams FP8 pages at about 38 GB/s: its loads are 8 bytes per lane instead of 16 and 8, and a unit's memory
+// pipeline moves fewer bytes per second with narrower loads (about 58 GB/s at best, with contiguous 16-byte loads).
+static double unit_bytes_per_us(int elem_bytes) { return elem_bytes == 1 ? 38e3 : 45e3; }
 
 static int narrow_units(double narrow_bytes, double mfma_iters, int elem_bytes) {
     if (narrow_bytes == 0) return 0;
@@ -145,7 +145,7 @@ static int64_t choose_mfma_chunk(const std::vector<RowBlock>& blocks, int G, int
 // measured size in all 19 batches).
 static int64_t choose_narrow_chunk(const std::vector<int64_t>& lengths, int Hkv, int D, int slots, int elem_bytes) {
     constexpr double kStartUs = 7.0, kHbmBytesPerUs = 7.0e6;
-    const double kUnitBytesPerUs = elem_bytes == 1 ? 33e3 : 55e3;
+    const double kUnitBytesPerUs = elem_bytes == 1 ? 44e3 : 55e3;
     constexpr double kMergeUs = 4.0, kMergeSplitUs = 0.3;
     static const int64_t kCandidates[] = {8192, 6144, 4096, 3072, 2048, 1536, 1024, 768, 512};
     const double bytes_per_key = 2.0 * D * elem_bytes;
