@@ -671,14 +671,13 @@ struct NarrowCombine {
 
 // SOLO: the calling wave runs the whole tile on its own (NW = 1): no LDS, no barrier, the result is written from the
 // accumulator registers; the other waves of the workgroup run other tiles at the same time.
-// FP8: the pool holds one-byte codes in the same element layout; a lane's loads are half as wide and the codes are
-// turned into bf16 operands right before the MFMAs.
-template <int HD, int NW, int NK, int NV, bool SOLO = false, bool FP8 = false>
+// (bf16 pages; FP8 pages are read by narrow_item_wide.)
+template <int HD, int NW, int NK, int NV, bool SOLO = false>
 __device__ __forceinline__ void narrow_item(const KParams& P, const ppd_work_item& it, char* smem) {
     static_assert(!SOLO || NW == 1, "a solo tile is one wave");
-    constexpr int EB = FP8 ? 1 : 2;  // bytes per pool element
-    using KVec = std::conditional_t<FP8, u32x2, u32x4>;     // 8 elements
-    using VVec = std::conditional_t<FP8, uint32_t, u32x2>;  // 4 elements
+    constexpr int EB = 2;  // bytes per pool element
+    using KVec = u32x4;    // 8 elements
+    using VVec = u32x2;    // 4 elements
     constexpr int KS = HD / 32;   // k-steps of S^T
     constexpr int DBN = HD / 16;  // 16-row d blocks of O^T
     constexpr int CB = NarrowCombine<NW>::CB;
@@ -761,11 +760,8 @@ __device__ __forceinline__ void narrow_item(const KParams& P, const ppd_work_ite
     auto compute_step = [&](int k, KRegs& rs, VRegs& rw) {
         f32x4 sa = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-        for (int ks = 0; ks < KS; ++ks) {
-            bf16x8 ka;
-            if constexpr (FP8) ka = as_bf16x8(fp8x8_to_bf16x8(rs.k[ks])); else ka = as_bf16x8(rs.k[ks]);
-            sa = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ka, qreg[ks], sa, 0, 0, 0);
-        }
+        for (int ks = 0; ks < KS; ++ks)
+            sa = __builtin_amdgcn_mfma_f32_16x16x32_bf16(as_bf16x8(rs.k[ks]), qreg[ks], sa, 0, 0, 0);
         // sa[i]: token 4*g4 + i of the page
         const int t0 = it.kv_begin + (s_lo + k) * kPage;
         const bool masked = t0 + kPage - 1 > min_limit || t0 + kPage > it.kv_end;
@@ -781,11 +777,7 @@ __device__ __forceinline__ void narrow_item(const KParams& P, const ppd_work_ite
 #pragma unroll
                     for (int e = 0; e < 4; ++e) {
                         const int pos = t0 + 4 * g4 + e;
-                        if constexpr (FP8) {
-                            if (pos >= it.kv_total) rw.v[db] &= ~(0xFFu << (8 * e));  // code 0 is 0.0
-                        } else {
-                            if (pos >= it.kv_total) rw.v[db][e >> 1] &= (e & 1) ? 0x0000FFFFu : 0xFFFF0000u;
-                        }
+                        if (pos >= it.kv_total) rw.v[db][e >> 1] &= (e & 1) ? 0x0000FFFFu : 0xFFFF0000u;
                     }
                 }
             }
@@ -810,11 +802,8 @@ __device__ __forceinline__ void narrow_item(const KParams& P, const ppd_work_ite
         const u32x2 pw = {pack_bf16(p[0], p[1]), pack_bf16(p[2], p[3])};
         const s16x4 pb4 = __builtin_bit_cast(s16x4, pw);
 #pragma unroll
-        for (int db = 0; db < DBN; ++db) {
-            s16x4 va;
-            if constexpr (FP8) va = __builtin_bit_cast(s16x4, fp8x4_to_bf16x4(rw.v[db])); else va = __builtin_bit_cast(s16x4, rw.v[db]);
-            oacc[db] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(va, pb4, oacc[db], 0, 0, 0);
-        }
+        for (int db = 0; db < DBN; ++db)
+            oacc[db] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(__builtin_bit_cast(s16x4, rw.v[db]), pb4, oacc[db], 0, 0, 0);
     };
 
     // K of NK - 1 pages and V of NV - 1 pages (4 KiB each at D = 128) are in flight per wave while one page is being
@@ -1214,8 +1203,7 @@ __device__ __forceinline__ void rearm_cursors(const KParams& P, int q0, int q1, 
 
 template <int HD, bool FP8>
 __global__ __launch_bounds__(kThreads, 2) void ppd_mixed_kernel(const KParams P) {
-    // register sets of a streaming wave: a page of codes is half the registers, so FP8 pages keep more pages in flight
-    constexpr int NSETS = FP8 ? kFp8StreamSets : 4;
+    constexpr int NSETS = 4;  // rotating register sets (one page each) of a streaming wave on bf16 pages
     // Dynamic LDS: rings of kStages + 1 stages of 4 pages of K and as many of V, then the page ids of a tile's key
     // range, for the MFMA path (136 KiB at HD = 128); the narrow path's combine buffer (kWaves * 16 * (HD+2)
     // floats) uses the front of it.
@@ -1304,14 +1292,14 @@ __global__ __launch_bounds__(kThreads, 2) void ppd_mixed_kernel(const KParams P)
             if (mine < P.queue_begin[kQueues]) {
                 const ppd_work_item it = P.items[mine];
                 if constexpr (FP8) narrow_item_wide<HD, 1, kFp8StreamSets, true, true>(P, it, smem);
-                else narrow_item<HD, 1, NSETS, NSETS, true, FP8>(P, it, smem);
+                else narrow_item<HD, 1, NSETS, NSETS, true>(P, it, smem);
             }
             continue;
         }
         const ppd_work_item it = P.items[idx];
         if (it.kind == 0) {
             if constexpr (FP8) narrow_item_wide<HD, kWaves, kFp8StreamSets, false, true>(P, it, smem);
-            else narrow_item<HD, kWaves, NSETS, NSETS, false, FP8>(P, it, smem);
+            else narrow_item<HD, kWaves, NSETS, NSETS, false>(P, it, smem);
         } else {
             mfma_item<HD, false, FP8>(P, it, smem);
         }
