@@ -135,3 +135,35 @@ def test_fp8_needs_the_one_launch_kernel_and_valid_scales():
     from gpu_helpers import gpu_step_fp8
     with pytest.raises(ppd.PPDError):
         gpu_step_fp8(b, 0.02, 0.02, options={"launch_mode": 1})
+
+
+@pytest.mark.parametrize("k_scale,v_scale", [(1.0, 0.0173), (2.0 ** -9, 9.0), (448.0, 1.0 / 448.0), (3.0e-5, 2.0 ** -120)])
+def test_append_codes_of_every_bf16_value(k_scale, v_scale):
+    """All 65 536 bf16 bit patterns (zeros, subnormals, ties, the saturation range, infinities, NaNs) through the
+    quantising append, for K and for V, against the oracle's codes: bit for bit."""
+    import torch
+    import paper_2603_13358_amd as ppd
+    from gpu_helpers import to_dev_u16
+    Hkv, D, P = 2, 64, 16
+    T = 65536 // (Hkv * D)
+    allbits = np.arange(65536, dtype=np.uint16)
+    k = allbits.reshape(T, Hkv, D)
+    v = allbits[::-1].copy().reshape(T, Hkv, D)
+    num_pages = T // P + 3
+    rng = np.random.default_rng(5)
+    pages = rng.permutation(num_pages)[:T // P]
+    t = np.arange(T)
+    slots = pages[t // P].astype(np.int64) * P + t % P
+    ref = np.full(oracle.pool_elems(num_pages, Hkv, D, P), NAN_CODE, np.uint8)
+    oracle.kv_append_fp8(k, v, ref, slots, Hkv, D, P, num_pages, k_scale, v_scale)
+    dev = torch.device("cuda:0")
+    ctx = ppd.Context(2 * Hkv, Hkv, D, num_pages)
+    ctx.set_kv_format(ppd.PPD_KV_FP8_E4M3, k_scale, v_scale)
+    pool = torch.full((ref.size,), NAN_CODE, dtype=torch.uint8, device=dev)
+    ctx.kv_append(to_dev_u16(k, torch, dev), to_dev_u16(v, torch, dev), pool, torch.from_numpy(slots).to(dev))
+    torch.cuda.synchronize()
+    assert ctx.device_error_flags() == 0
+    got = pool.cpu().numpy()
+    bad = np.argwhere(got != ref)
+    assert bad.size == 0, "%d codes differ, first at %s: got %s want %s" % (len(bad), bad[:3].ravel(), got[bad[:3].ravel()], ref[bad[:3].ravel()])
+    ctx.close()
