@@ -167,3 +167,24 @@ def test_append_codes_of_every_bf16_value(k_scale, v_scale):
     bad = np.argwhere(got != ref)
     assert bad.size == 0, "%d codes differ, first at %s: got %s want %s" % (len(bad), bad[:3].ravel(), got[bad[:3].ravel()], ref[bad[:3].ravel()])
     ctx.close()
+
+
+def test_single_key_is_exact_fp8():
+    """L = 0, n = 1: softmax over one key is 1, so out = value(code) * v_scale rounded once to bf16 -- exactly."""
+    from gpu_helpers import gpu_step_fp8
+    b = si.make_batch("one8", L=[0, 0, 0], n=[1, 1, 1], Hq=8, Hkv=2, D=128, seed=49, slack_pages=2)
+    v_scale = 0.0421
+    pool, out, _ = gpu_step_fp8(b, 0.0173, v_scale)
+    ref_pool = _oracle_fp8(b, 0.0173, v_scale)
+    assert np.array_equal(pool, ref_pool)
+    table = np.array([oracle.e4m3_value(c) for c in range(256)], np.float64)
+    G = b.Hq // b.Hkv
+    for i in range(b.B):
+        page = int(b.page_tables[i, 0])
+        for hq in range(b.Hq):
+            g = hq // G
+            S = 2 * b.Hkv * b.P * b.D
+            base = page * S + b.Hkv * b.P * b.D + g * b.P * b.D      # V block of the head; token 0: octet 0, slot 0
+            codes = ref_pool[base + np.arange(b.D) * 8]
+            want = si.f32_to_bf16_bits((table[codes].astype(np.float32) * np.float32(v_scale)).astype(np.float32))
+            assert np.array_equal(out[i, hq], want), (i, hq)
