@@ -8,7 +8,7 @@ import pytest
 
 import oracle
 import synthetic_inputs as si
-from helpers import bits_to_f32, check_close
+from helpers import bits_to_f32, check_close, random_mixed_batch
 
 pytestmark = pytest.mark.gpu
 
@@ -55,6 +55,14 @@ def test_shapes_and_ragged_lengths_fp8(Hq, Hkv, D):
     L = [0, 0, 1, 15, 16, 17, 63, 64, 65, 300, 1000, 129, 191, 0]
     n = [1, 130, 1, 1, 3, 40, 2, 1, 70, 5, 1, 260, 66, 64]
     _compare(si.make_batch("ragged8", L=L, n=n, Hq=Hq, Hkv=Hkv, D=D, seed=41, slack_pages=7))
+
+
+@pytest.mark.parametrize("seed", range(8))
+def test_random_mixed_batches_fp8(seed):
+    """The random batches of the 16-bit parity tests (shapes, row mix, lengths and split sizes drawn from the seed) on
+    FP8 pages."""
+    b, opts = random_mixed_batch(seed)
+    _compare(b, options=opts)
 
 
 def test_scales_that_saturate_and_underflow_fp8():

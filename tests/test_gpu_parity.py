@@ -7,7 +7,7 @@ import numpy as np
 import pytest
 
 import synthetic_inputs as si
-from helpers import bits_to_f32, check_close, oracle_out, oracle_pool
+from helpers import bits_to_f32, check_close, oracle_out, oracle_pool, random_mixed_batch
 
 pytestmark = pytest.mark.gpu
 
@@ -132,38 +132,8 @@ def test_resident_pair_only_one_kind_present():
 def test_random_mixed_batches(seed):
     """Random batches: sequence count, head shape, the mix of decode / append-prefill / full-prefill rows, lengths
     around page, tile and row-block boundaries, and split sizes all drawn from the seed."""
-    rng = np.random.default_rng(7000 + seed)
-    Hkv = int(rng.choice([1, 2, 4, 8]))
-    G = int(rng.integers(1, 9))
-    D = int(rng.choice([64, 128]))
-    B = int(rng.integers(1, 25))
-    L, n = [], []
-    budget = 4e6 / (G * Hkv / 8.0)                 # visible (row, key) pairs: keeps the oracle to a few seconds
-    for _ in range(B):
-        kind = rng.integers(0, 4)
-        if kind == 0:                              # decode
-            Li, ni = int(rng.integers(0, 5000)), 1
-        elif kind == 1:                            # a few new tokens (still a narrow tile for small G)
-            Li, ni = int(rng.integers(0, 3000)), int(rng.integers(2, 8))
-        elif kind == 2:                            # append-prefill, lengths near multiples of 64
-            Li = int(rng.integers(1, 40)) * 64 + int(rng.integers(-2, 3))
-            ni = int(rng.integers(1, 6)) * 64 // max(1, G // 2) + int(rng.integers(-2, 3))
-        else:                                      # full prefill
-            Li, ni = 0, int(rng.integers(1, 400))
-        ni = max(1, ni)
-        cost = ni * (Li + (ni + 1) / 2)
-        if cost > budget:
-            continue
-        budget -= cost
-        L.append(max(0, Li))
-        n.append(ni)
-    if not L:
-        L, n = [5], [1]
-    opts = {}
-    if rng.integers(0, 2):
-        opts = {"narrow_chunk": int(rng.choice([64, 256, 1024])), "mfma_chunk": int(rng.choice([64, 192, 512, 2048]))}
-    _compare(si.make_batch("random%d" % seed, L=L, n=n, Hq=G * Hkv, Hkv=Hkv, D=D, seed=7100 + seed,
-                           slack_pages=int(rng.integers(0, 9))), options=opts)
+    b, opts = random_mixed_batch(seed)
+    _compare(b, options=opts)
 
 
 def test_decode_batch_scaled():
