@@ -164,6 +164,20 @@ __device__ __forceinline__ void lds_direct_load16(const void* gbase, uint32_t la
 // LDS byte address of p as an opaque 32-bit register value: operand reads then address LDS as this register plus a
 // compile-time offset below 64 KiB, which fits the instruction's offset field (left to itself the compiler folds
 // ring and stage offsets into constants beyond that field and spends one vector add per read).
+// (x + k) mod N for 0 <= x, k < N
+template <int N>
+__device__ __forceinline__ int ring_add(int x, int k) {
+    if constexpr ((N & (N - 1)) == 0) return (x + k) & (N - 1);
+    const int y = x + k;
+    return y >= N ? y - N : y;
+}
+// The same with the LDS byte address given as a wave-uniform integer (no pointer cast per load).
+__device__ __forceinline__ void lds_direct_load16_at(const void* gbase, uint32_t lane_off, uint32_t lds_addr) {
+    asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1"
+                 :
+                 : "v"(lane_off), "s"(gbase), "s"(lds_addr)
+                 : "memory", "m0");
+}
 __device__ __forceinline__ uint32_t lds_base(const char* p) {
     uint32_t a = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) const char*)p;
     asm volatile("" : "+v"(a));
@@ -246,11 +260,16 @@ __device__ __forceinline__ void mfma_item(const KParams& P, const ppd_work_item&
     const bool loader = LOADERS == kThreads || tid < LOADERS;  // wave-uniform
     const int page_sel = loader ? (wave * 64) / LGPP : 0;
     const uint32_t lane_off = (uint32_t)(tid % LGPP) * 16u;
-    struct TilePages { int p[ROUNDS]; };  // the pages this wave loads from, one per round
+    // The pages this wave loads from, one per round, as byte offsets of the page in the pool: the id read from LDS
+    // becomes a scalar and the 64-bit product is made once per tile on the scalar unit (a page is at most 8 MiB, so
+    // its size fits 32 bits); a load then costs two scalar additions for its global address and two for its LDS
+    // address.
+    struct TilePages { uint32_t lo[ROUNDS], hi[ROUNDS]; };
     int* lds_ids = reinterpret_cast<int*>(smem + IDS_AT);
     for (int i = tid; i < ntiles * 4; i += kThreads)
         lds_ids[i] = (int)checked_page(P, load_page_id(pt_row, first_page + i, last_page));
-    struct RawPages { int p[ROUNDS]; };  // the same ids as they come from LDS (vector registers)
+    struct RawPages { int p[ROUNDS]; };  // the ids as they come from LDS (vector registers)
+    const uint32_t page_bytes = (uint32_t)P.page_stride * EB;
     auto tile_pages_raw = [&](int ti) {
         RawPages t;
 #pragma unroll
@@ -260,19 +279,33 @@ __device__ __forceinline__ void mfma_item(const KParams& P, const ppd_work_item&
     auto to_scalar = [&](const RawPages& v) {
         TilePages t;
 #pragma unroll
-        for (int r = 0; r < ROUNDS; ++r) t.p[r] = __builtin_amdgcn_readfirstlane(v.p[r]);
+        for (int r = 0; r < ROUNDS; ++r) {
+            const uint32_t id = (uint32_t)__builtin_amdgcn_readfirstlane(v.p[r]);
+            if constexpr (FP8) {  // this kernel has no scalar registers to spare for the pair: the product is made at the load
+                t.lo[r] = id;
+                t.hi[r] = 0;
+            } else {
+                const uint64_t off = (uint64_t)id * page_bytes;
+                t.lo[r] = (uint32_t)off;
+                t.hi[r] = (uint32_t)(off >> 32);
+            }
+        }
         return t;
     };
     auto tile_pages = [&](int ti) { return to_scalar(tile_pages_raw(ti)); };
     // Workgroup barrier for LDS traffic only: unlike __syncthreads() it does not drain the memory counter, so
     // LDS-direct loads of later tiles stay in flight across it.
     auto lds_barrier = [&]() { asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory"); };
-    auto load_block = [&](const TilePages& t, int lds_byte, int64_t kv_off) {
+    const char* const pool_k = reinterpret_cast<const char*>(P.pool) + head_off * EB;  // this KV head's K block of page 0
+    const char* const pool_v = pool_k + v_off * EB;                                    // ... and its V block
+    const uint32_t smem_addr = __builtin_amdgcn_readfirstlane((uint32_t)(uintptr_t)(__attribute__((address_space(3))) const char*)smem) + (uint32_t)wave * 1024u;
+    auto load_block = [&](const TilePages& t, int lds_byte, bool is_v) {
         if (!loader) return;
 #pragma unroll
         for (int r = 0; r < ROUNDS; ++r) {
-            const char* base = reinterpret_cast<const char*>(P.pool) + ((int64_t)t.p[r] * P.page_stride + head_off + kv_off) * EB;
-            lds_direct_load16(base, lane_off, smem + lds_byte + r * (kThreads * 16) + wave * 1024);
+            const uint64_t off = FP8 ? (uint64_t)t.lo[r] * page_bytes : (((uint64_t)t.hi[r] << 32) | t.lo[r]);
+            const char* base = (is_v ? pool_v : pool_k) + off;
+            lds_direct_load16_at(base, lane_off, smem_addr + (uint32_t)(lds_byte + r * (kThreads * 16)));
         }
     };
     // FP8: the 16 codes this thread staged at src_byte become two bf16 granules of the operand tile at dst_byte (the
@@ -354,24 +387,24 @@ __device__ __forceinline__ void mfma_item(const KParams& P, const ppd_work_item&
     if constexpr (FP8) {
         // K(0), K(1) and V(0) are staged and converted; K(2) and V(1) are then issued into the slots of K(0) and beside V(0)
         const TilePages tp0 = tile_pages(0), tp1 = tile_pages(1 < ntiles ? 1 : 0);
-        load_block(tp0, STAGE_K, 0);
-        load_block(tp0, STAGE_V, v_off);
-        if (1 < ntiles) load_block(tp1, STAGE_K + LBYTES, 0);
+        load_block(tp0, STAGE_K, false);
+        load_block(tp0, STAGE_V, true);
+        if (1 < ntiles) load_block(tp1, STAGE_K + LBYTES, false);
         wait_all_loads();
 #pragma unroll
         for (int ks = 0; ks < KS; ++ks) asm volatile("" ::"v"(qreg[ks]));
         convert_staged(STAGE_K, 0, false, 0);
         if (1 < ntiles) convert_staged(STAGE_K + LBYTES, KBYTES, false, 1);
         convert_staged(STAGE_V, VRING, true, 0);
-        if (2 < ntiles) load_block(tile_pages(2), STAGE_K, 0);
-        if (1 < ntiles) load_block(tp1, STAGE_V + LBYTES, v_off);
+        if (2 < ntiles) load_block(tile_pages(2), STAGE_K, false);
+        if (1 < ntiles) load_block(tp1, STAGE_V + LBYTES, true);
     } else {
 #pragma unroll
         for (int t = 0; t < NS; ++t) {
             if (t < ntiles) {
                 const TilePages tp = tile_pages(t);
-                load_block(tp, t * KBYTES, 0);
-                if (t < NS - 1) load_block(tp, VRING + t * KBYTES, v_off);
+                load_block(tp, t * KBYTES, false);
+                if (t < NS - 1) load_block(tp, VRING + t * KBYTES, true);
             }
         }
         wait_all_loads();
@@ -410,16 +443,16 @@ __device__ __forceinline__ void mfma_item(const KParams& P, const ppd_work_item&
     TilePages tp_k = tile_pages(NS < ntiles ? NS : ntiles - 1);
     for (int ti = 0; ti < ntiles; ++ti) {
         const int st_nxt = st_cur + 1 == NSK ? 0 : st_cur + 1;           // (ti + 1) % NSK
-        const int st_far = (st_cur + NS) % NSK;                           // (ti + NS) % NSK
+        const int st_far = ring_add<NSK>(st_cur, NS % NSK);                           // (ti + NS) % NSK
         const int sv_nxt = sv_cur + 1 == NSV ? 0 : sv_cur + 1;           // (ti + 1) % NSV
-        const int sv_far = (sv_cur + NS - 1) % NSV;                       // (ti + NS - 1) % NSV
+        const int sv_far = ring_add<NSV>(sv_cur, (NS - 1) % NSV);                       // (ti + NS - 1) % NSV
         const bool full_issue = ti + NS < ntiles;
         if constexpr (FP8) {  // tile t of K or of V is staged in slot t % 2
-            if (ti + NS - 1 < ntiles) load_block(tp_v, STAGE_V + (ti & 1) * LBYTES, v_off);
-            if (full_issue) load_block(tp_k, STAGE_K + ((ti + 1) & 1) * LBYTES, 0);
+            if (ti + NS - 1 < ntiles) load_block(tp_v, STAGE_V + (ti & 1) * LBYTES, true);
+            if (full_issue) load_block(tp_k, STAGE_K + ((ti + 1) & 1) * LBYTES, false);
         } else {
-            if (ti + NS - 1 < ntiles) load_block(tp_v, VRING + sv_far * KBYTES, v_off);
-            if (full_issue) load_block(tp_k, st_far * KBYTES, 0);
+            if (ti + NS - 1 < ntiles) load_block(tp_v, VRING + sv_far * KBYTES, true);
+            if (full_issue) load_block(tp_k, st_far * KBYTES, false);
         }
         // The V tile of the next iteration is this iteration's K tile; the ids of its K tile are read from LDS
         // now and turned into scalars at the end of the iteration: under the other waves' operand reads that
@@ -434,7 +467,7 @@ __device__ __forceinline__ void mfma_item(const KParams& P, const ppd_work_item&
             else
                 wait_all_loads();
             if constexpr (FP8) {
-                if (ti + 2 < ntiles) convert_staged(STAGE_K + (ti & 1) * LBYTES, ((st_cur + 2) % NSK) * KBYTES, false, ti + 2);
+                if (ti + 2 < ntiles) convert_staged(STAGE_K + (ti & 1) * LBYTES, ring_add<NSK>(st_cur, 2 % NSK) * KBYTES, false, ti + 2);
                 if (ti + 1 < ntiles) convert_staged(STAGE_V + ((ti + 1) & 1) * LBYTES, VRING + sv_nxt * KBYTES, true, ti + 1);
             } else {
                 if (ti + 1 < ntiles) fix_v_tail(ti + 1, VRING + sv_nxt * KBYTES);
@@ -537,12 +570,12 @@ __device__ __forceinline__ void mfma_item(const KParams& P, const ppd_work_item&
     TilePages tp_k = tile_pages(NS < ntiles ? NS : ntiles - 1);
     for (int ti = 0; ti < ntiles; ++ti) {
         const int st_nxt = st_cur + 1 == NSK ? 0 : st_cur + 1;           // (ti + 1) % NSK
-        const int st_far = (st_cur + NS) % NSK;                           // (ti + NS) % NSK
+        const int st_far = ring_add<NSK>(st_cur, NS % NSK);                           // (ti + NS) % NSK
         const int sv_nxt = sv_cur + 1 == NSV ? 0 : sv_cur + 1;           // (ti + 1) % NSV
-        const int sv_far = (sv_cur + NS - 1) % NSV;                       // (ti + NS - 1) % NSV
+        const int sv_far = ring_add<NSV>(sv_cur, (NS - 1) % NSV);                       // (ti + NS - 1) % NSV
         const bool full_issue = ti + NS < ntiles;
-        if (ti + NS - 1 < ntiles) load_block(tp_v, VRING + sv_far * KBYTES, v_off);
-        if (full_issue) load_block(tp_k, st_far * KBYTES, 0);
+        if (ti + NS - 1 < ntiles) load_block(tp_v, VRING + sv_far * KBYTES, true);
+        if (full_issue) load_block(tp_k, st_far * KBYTES, false);
         tp_v = tp_k;
         const RawPages tp_raw = tile_pages_raw(ti + 1 + NS < ntiles ? ti + 1 + NS : ntiles - 1);
         auto close_iteration = [&]() {
