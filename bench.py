@@ -650,7 +650,11 @@ def main():
     roofline["per_sequence_bound_us"] = main_res["seq_roofline_us"]
     roofline["frac_of_per_sequence_bounds"] = main_res["seq_roofline_us"] * 1e-6 / kernel_s
     roofline["traffic"] = None if args.kv_fp8 else measured_traffic(args.workload)
-    roofline["kernel"] = "ppd_mixed_kernel<128, %s>" % ("true" if args.kv_fp8 else "false")  # <head_dim, FP8 pages>
+    fp8_s = "true" if args.kv_fp8 else "false"
+    if main_res["plan"]["n_mfma"] == 0 and options.get("narrow_kernel", 1) and not options.get("launch_mode", 0):
+        roofline["kernel"] = "ppd_narrow_kernel<128, %s, 8>" % fp8_s  # a step without row-block tiles: <head_dim, FP8 pages, waves>
+    else:
+        roofline["kernel"] = "ppd_mixed_kernel<128, %s>" % fp8_s  # <head_dim, FP8 pages>
     roofline["kernel_ms"] = main_res["mixed_kernel_ms"]
 
     extras = {}

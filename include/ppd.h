@@ -128,7 +128,9 @@ const char *ppd_last_error(const ppd_ctx *ctx);
  * least six such tiles per workgroup; 0 = never; 1 = whenever there is such a tile), "launch_mode" (0 = one kernel runs both kinds of tiles on separate compute units,
  * 1 = a step that holds both kinds runs as two kernels resident side by side on every compute unit -- row-block
  * tiles on the caller's stream, narrow tiles on a stream of the context's own, joined before the call's work ends
- * -- 2 = the two specialised kernels also for steps of one kind), "timing" (1 = record HIP
+ * -- 2 = the two specialised kernels also for steps of one kind), "narrow_kernel" (1, the default = with launch_mode 0 a step
+ * without row-block tiles, i.e. a decode-only step, runs a kernel of its own that hands the first tiles out by
+ * workgroup index instead of by atomic claims; same tiles, bit-identical results; 0 = always the one kernel), "timing" (1 = record HIP
  * events on the call's stream right before and after the attention kernel(s), see ppd_last_kernel_ms). */
 ppd_status ppd_set_option(ppd_ctx *ctx, const char *key, int64_t value);
 

@@ -60,6 +60,7 @@ struct ppd_ctx {
     hipStream_t side_stream = nullptr;
     hipEvent_t ev_fork = nullptr, ev_join = nullptr;
     int launch_mode = 0;  // option "launch_mode"
+    bool narrow_kernel = true;  // option "narrow_kernel": launches without row-block tiles run ppd_narrow_kernel
     // element format of the pools (ppd_set_kv_format): FP8 E4M3 codes with one scale per tensor, or bf16
     bool fp8_pages = false;
     float k_scale = 1.f, v_scale = 1.f;
@@ -366,7 +367,15 @@ ppd_status mixed_attention_impl(ppd_ctx* ctx, const void* q, const void* kv_page
     const bool has_narrow = plan.stats.n_narrow > 0, has_mfma = plan.stats.n_mfma > 0;
     const int mode = ctx->launch_mode;
     int rc = 0;
-    if (mode == 0 || (mode == 1 && !(has_narrow && has_mfma))) {
+    if (mode == 0 && has_narrow && !has_mfma && ctx->narrow_kernel) {
+        // a decode-only step: the first tiles are handed out by workgroup index, no more workgroups than there are slots
+        const int64_t n_wave = plan.queue_begin[ppd::kQueues] - plan.queue_begin[ppd::kWaveQueue];
+        constexpr int NW = ppd::kNarrowKernelWaves;
+        const int64_t slots = (plan.queue_begin[ppd::kWaveQueue] - plan.queue_begin[ppd::kNarrowQueue]) + (n_wave + NW - 1) / NW;
+        const int64_t wgs = (int64_t)plan.stats.grid * (ppd::kWaves / NW);  // as many waves on a unit as the planned grid has
+        rc = ppd::launch_narrow(kp, D, (int)std::max<int64_t>(1, std::min<int64_t>(wgs, slots)), stream, ctx->fp8_pages);
+        if (rc != 0) return hip_fail(ctx, (hipError_t)rc, "launch narrow-tile kernel");
+    } else if (mode == 0 || (mode == 1 && !(has_narrow && has_mfma))) {
         rc = ppd::launch_mixed(kp, D, plan.stats.grid, stream, ctx->fp8_pages);
         if (rc != 0) return hip_fail(ctx, (hipError_t)rc, "launch mixed attention");
     } else {
@@ -554,6 +563,9 @@ ppd_status ppd_set_option(ppd_ctx* ctx, const char* key, int64_t value) {
     } else if (k == "launch_mode") {
         if (value < 0 || value > 2) return fail(ctx, PPD_ERR_RANGE, "launch_mode must be in [0, 2]");
         ctx->launch_mode = (int)value;
+    } else if (k == "narrow_kernel") {
+        if (value < 0 || value > 1) return fail(ctx, PPD_ERR_RANGE, "narrow_kernel must be 0 or 1");
+        ctx->narrow_kernel = value != 0;
     } else if (k == "timing") {
         ctx->timing = value != 0;
         ctx->ev_used = 0;

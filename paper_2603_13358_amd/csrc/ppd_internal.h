@@ -42,6 +42,9 @@ constexpr int kStreamVSets = PPD_STREAM_VSETS;
 #define PPD_FP8_SETS 2
 #endif
 constexpr int kFp8StreamSets = PPD_FP8_SETS;  // rotating register sets (one page pair each) of a streaming wave on FP8 pages
+// Waves per workgroup of ppd_narrow_kernel.  Two workgroups of four waves per unit (two tiles in flight there) measured
+// the same on short tiles and 10 % slower on cfg2, so it runs its tiles exactly as ppd_mixed_kernel does.
+constexpr int kNarrowKernelWaves = kWaves;
 constexpr int kXcds = 8;             // MFMA tile queues, one per XCD (each XCD has its own L2)
 constexpr int kNarrowQueue = kXcds;  // index of the narrow-tile queue
 // Very short narrow tiles of a launch that has very many of them are handed out kWaves at a time (one claim), each
@@ -142,6 +145,8 @@ struct MergeParams {
 // Launchers (defined in ppd_kernels.hip); stream is a hipStream_t.
 int prepare_mixed_kernels();
 int launch_mixed(const KParams& p, int head_dim, int grid, void* stream, bool fp8_pages);
+// a launch without row-block tiles: grid <= slots, slots = whole-workgroup tiles + ceil(one-wave tiles / kNarrowKernelWaves)
+int launch_narrow(const KParams& p, int head_dim, int grid, void* stream, bool fp8_pages);
 int launch_mfma_only(const KParams& p, int head_dim, int grid, void* stream);    // row-block tiles of queues 0..7
 int launch_stream_only(const KParams& p, int head_dim, int grid, void* stream);  // narrow tiles of queue 8
 int launch_merge(const MergeParams& p, void* stream);

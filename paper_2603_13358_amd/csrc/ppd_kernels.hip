@@ -1341,6 +1341,52 @@ __global__ __launch_bounds__(kThreads, 2) void ppd_mixed_kernel(const KParams P)
 }
 
 // ---------------------------------------------------------------------------------------------------
+// A launch that holds narrow tiles only (a decode-only step).  Same tile code as in ppd_mixed_kernel, handed out
+// differently: a small launch of the mixed kernel spends 1.7 us on its first claim and ~5 us finding out, claim by
+// failing claim, that nothing is left, which is a quarter of a 25 us decode step.  Here the whole-workgroup tiles
+// (longest first) and then the one-wave tiles, NW to a slot, form one row of slots; workgroup b takes slot b
+// without asking, and only a launch with more slots than workgroups claims further ones (from gridDim.x on) with the
+// cursor of the narrow queue, which the last workgroup to finish re-arms.  The host launches no more workgroups than
+// there are slots.  Measured and not kept: claiming the next slot before running the current one (hides the round
+// trip but holds a slot that an idle workgroup could have run: cfg2 186 -> 206 us), and handing out all slots by
+// index, rounds running alternately up and down the workgroups (no atomics at all: same step time on short tiles,
+// +3 % on long ones).
+// ---------------------------------------------------------------------------------------------------
+template <int HD, bool FP8, int NW>
+__global__ __launch_bounds__(64 * NW, 2) void ppd_narrow_kernel(const KParams P) {
+    constexpr int NSETS = 4;  // rotating register sets (one page each) of a streaming wave on bf16 pages
+    extern __shared__ __attribute__((aligned(16))) char smem[];  // the combine buffer
+    __shared__ int s_next_slot;
+    volatile int* s_next = &s_next_slot;
+    const int tid = threadIdx.x;
+    const int wg_begin = P.queue_begin[kNarrowQueue], wave_begin = P.queue_begin[kWaveQueue], end = P.queue_begin[kQueues];
+    const int n_wg = wave_begin - wg_begin;
+    const int slots = n_wg + (end - wave_begin + NW - 1) / NW;
+    const bool claims = slots > (int)gridDim.x;  // the same for every workgroup of the launch
+    int slot = blockIdx.x;
+    while (slot < slots) {
+        if (slot < n_wg) {
+            const ppd_work_item it = P.items[wg_begin + slot];
+            if constexpr (FP8) narrow_item_wide<HD, NW, kFp8StreamSets, false, true>(P, it, smem);
+            else narrow_item<HD, NW, NSETS, NSETS, false>(P, it, smem);
+        } else {
+            const int mine = wave_begin + (slot - n_wg) * NW + __builtin_amdgcn_readfirstlane(tid >> 6);
+            if (mine < end) {
+                const ppd_work_item it = P.items[mine];
+                if constexpr (FP8) narrow_item_wide<HD, 1, kFp8StreamSets, true, true>(P, it, smem);
+                else narrow_item<HD, 1, NSETS, NSETS, true>(P, it, smem);
+            }
+        }
+        if (!claims) break;
+        if (tid == 0) *s_next = (int)gridDim.x + (int)atomicAdd(&P.counters[kCursorBase + kNarrowQueue * kCursorStride], 1u);
+        __syncthreads();
+        slot = __builtin_amdgcn_readfirstlane(*s_next);
+        __syncthreads();  // everyone has read s_next, and the previous tile's combine is over
+    }
+    if (claims && tid == 0) rearm_cursors(P, kNarrowQueue, kNarrowQueue + 1, 10);
+}
+
+// ---------------------------------------------------------------------------------------------------
 // The co-resident pair.  A step that holds both kinds of tiles is launched as two kernels on two streams, sized so
 // that one workgroup of each fits on every compute unit at the same time: the row-block kernel (8 waves, two per
 // SIMD, 168 registers each, the K/V rings in LDS) keeps the matrix cores busy while the stream kernel (4 waves, one
@@ -1641,6 +1687,10 @@ int prepare_mixed_kernels() {
     allow(reinterpret_cast<const void*>(&ppd_mixed_kernel<64, false>), mixed_lds_bytes(64));
     allow(reinterpret_cast<const void*>(&ppd_mixed_kernel<128, true>), mixed_lds_bytes(128));
     allow(reinterpret_cast<const void*>(&ppd_mixed_kernel<64, true>), mixed_lds_bytes(64));
+    allow(reinterpret_cast<const void*>(&ppd_narrow_kernel<128, false, kNarrowKernelWaves>), NarrowCombine<kNarrowKernelWaves>::bytes(128));
+    allow(reinterpret_cast<const void*>(&ppd_narrow_kernel<64, false, kNarrowKernelWaves>), NarrowCombine<kNarrowKernelWaves>::bytes(64));
+    allow(reinterpret_cast<const void*>(&ppd_narrow_kernel<128, true, kNarrowKernelWaves>), NarrowCombine<kNarrowKernelWaves>::bytes(128));
+    allow(reinterpret_cast<const void*>(&ppd_narrow_kernel<64, true, kNarrowKernelWaves>), NarrowCombine<kNarrowKernelWaves>::bytes(64));
     allow(reinterpret_cast<const void*>(&ppd_mfma_kernel<128>), ring_lds_bytes(128));
     allow(reinterpret_cast<const void*>(&ppd_mfma_kernel<64>), ring_lds_bytes(64));
     return (int)e;
@@ -1656,6 +1706,21 @@ int launch_mixed(const KParams& p, int head_dim, int grid, void* stream, bool fp
         hipLaunchKernelGGL((ppd_mixed_kernel<64, false>), dim3(grid), dim3(kThreads), mixed_lds_bytes(64), st, p);
     else
         hipLaunchKernelGGL((ppd_mixed_kernel<64, true>), dim3(grid), dim3(kThreads), mixed_lds_bytes(64), st, p);
+    return (int)hipGetLastError();
+}
+
+int launch_narrow(const KParams& p, int head_dim, int grid, void* stream, bool fp8_pages) {
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    constexpr int NW = kNarrowKernelWaves;
+    const size_t lds128 = NarrowCombine<NW>::bytes(128), lds64 = NarrowCombine<NW>::bytes(64);
+    if (head_dim == 128 && !fp8_pages)
+        hipLaunchKernelGGL((ppd_narrow_kernel<128, false, NW>), dim3(grid), dim3(64 * NW), lds128, st, p);
+    else if (head_dim == 128)
+        hipLaunchKernelGGL((ppd_narrow_kernel<128, true, NW>), dim3(grid), dim3(64 * NW), lds128, st, p);
+    else if (!fp8_pages)
+        hipLaunchKernelGGL((ppd_narrow_kernel<64, false, NW>), dim3(grid), dim3(64 * NW), lds64, st, p);
+    else
+        hipLaunchKernelGGL((ppd_narrow_kernel<64, true, NW>), dim3(grid), dim3(64 * NW), lds64, st, p);
     return (int)hipGetLastError();
 }
 

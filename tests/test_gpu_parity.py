@@ -118,6 +118,50 @@ def test_wave_tiles_chosen_automatically_for_large_decode_batches():
     assert stats["grid"] == 256 and stats["n_narrow"] == 2048
 
 
+def test_decode_only_kernel_is_the_mixed_kernel_bit_for_bit():
+    """A step without row-block tiles runs ppd_narrow_kernel (first tiles by workgroup index): against the oracle, and
+    bit for bit against the one-launch kernel (option narrow_kernel = 0), with fewer slots than workgroups, with more
+    (claims through the cursor), with one-wave tiles, with split ranges, and twice in a row on one context."""
+    rng = np.random.default_rng(9)
+    few = si.make_batch("dec_few", L=[900, 17, 4000, 0, 2047], n=[1, 1, 1, 3, 1], Hq=32, Hkv=8, D=128, seed=35, slack_pages=3)
+    many = si.make_batch("dec_many", L=rng.integers(1, 700, size=300), n=np.ones(300, np.int64), Hq=16, Hkv=8, D=128,
+                         seed=36, slack_pages=5)
+    small_heads = si.make_batch("dec_d64", L=rng.integers(0, 3000, size=40), n=np.ones(40, np.int64), Hq=8, Hkv=2, D=64,
+                                seed=37, slack_pages=2)
+    for b, extra in ((few, {}), (few, {"narrow_chunk": 256}), (few, {"grid": 3}), (many, {}), (many, {"wave_tiles": 0}),
+                     (many, {"grid": 7, "wave_tiles": 1}), (small_heads, {})):
+        out, stats = _compare(b, options=dict(extra))
+        assert stats["n_mfma"] == 0
+        base, _ = _compare(b, options=dict(extra, narrow_kernel=0))
+        assert np.array_equal(out, base), "the two kernels disagree"
+    # the cursor is left re-armed: one context runs a claiming launch three times, then the one-launch kernel (which
+    # claims from the same cursor) on the same batch
+    import torch
+    import paper_2603_13358_amd as ppd
+    from gpu_helpers import to_dev_u16, from_dev_u16
+    dev = torch.device("cuda:0")
+    ctx = ppd.Context(many.Hq, many.Hkv, many.D, many.num_pages)
+    ctx.set_option("grid", 16)
+    pool = torch.zeros(ctx.pool_elems(), dtype=torch.int16, device=dev)
+    for k, v, slots in (many.cached_part(), many.new_part()):
+        if len(slots):
+            ctx.kv_append(to_dev_u16(k, torch, dev), to_dev_u16(v, torch, dev), pool, torch.from_numpy(slots.astype(np.int64)).to(dev))
+    q = to_dev_u16(many.q, torch, dev)
+    pt = torch.from_numpy(many.page_tables).to(dev)
+    outs = []
+    for call in range(4):
+        if call == 3:
+            ctx.set_option("narrow_kernel", 0)
+        out = torch.zeros((many.T, many.Hq, many.D), dtype=torch.int16, device=dev)
+        ctx.mixed_attention(q, pool, pt, many.L, many.n, many.scale, out)
+        torch.cuda.synchronize()
+        outs.append(from_dev_u16(out))
+    assert ctx.device_error_flags() == 0
+    assert all(np.array_equal(outs[0], o) for o in outs[1:])
+    check_close(bits_to_f32(outs[0]).reshape(many.T, many.Hq, many.D), oracle_out(many, oracle_pool(many, fill=0)))
+    ctx.close()
+
+
 def test_resident_pair_only_one_kind_present():
     """launch_mode 2 with batches of one kind: each specialised kernel alone, no fork to the side stream."""
     dec = si.make_batch("pair_dec", L=[900, 17, 4000, 0, 2047, 2048, 2049], n=[1, 1, 1, 1, 1, 2, 1], Hq=32, Hkv=8,
