@@ -475,6 +475,35 @@ def test_step_replays_from_a_hip_graph():
     ctx.close()
 
 
+def test_decode_only_step_replays_from_a_hip_graph():
+    """The same for a step without row-block tiles (the decode-only kernel), with more slots than workgroups so that
+    every replay claims from the cursor the replay before it has re-armed."""
+    import torch
+    from gpu_helpers import from_dev_u16, to_dev_u16
+    rng = np.random.default_rng(63)
+    b = si.make_batch("graph_dec", L=rng.integers(1, 900, size=60), n=np.ones(60, np.int64), Hq=32, Hkv=8, D=128, seed=63,
+                      slack_pages=3)
+    pool_ref, out_ref, stats, ctx = _step(b, return_ctx=True, options={"grid": 16})
+    assert stats["n_mfma"] == 0 and stats["n_narrow"] > 16
+    dev = torch.device("cuda:0")
+    pool = to_dev_u16(pool_ref, torch, dev)
+    q = to_dev_u16(b.q, torch, dev)
+    pt = torch.from_numpy(b.page_tables).to(dev)
+    out = torch.zeros((b.T, b.Hq, b.D), dtype=torch.int16, device=dev)
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        ctx.mixed_attention(q, pool, pt, b.L, b.n, b.scale, out, stream=torch.cuda.current_stream().cuda_stream)
+    for rep in range(4):
+        out.fill_(7)
+        scratch = torch.randn(1 << 20, device=dev).sum().item()      # eager work and a synchronisation in between
+        graph.replay()
+        torch.cuda.synchronize()
+        assert np.array_equal(from_dev_u16(out).reshape(out_ref.shape), out_ref), "replay %d differs" % rep
+    assert ctx.device_error_flags() == 0
+    del graph
+    ctx.close()
+
+
 def test_plan_change_under_capture_is_refused():
     """A call whose plan is not on the device yet would have to synchronise and allocate: under stream capture it is
     refused on the host, with nothing enqueued, and the capture stays valid."""
