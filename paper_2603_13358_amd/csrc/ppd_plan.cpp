@@ -89,7 +89,7 @@ static int64_t choose_mfma_chunk(const std::vector<RowBlock>& blocks, int G, int
     const double narrow_work = narrow_bytes / kUnitBytesPerUs;  // unit-microseconds
     const double narrow_floor = narrow_bytes / kHbmBytesPerUs;  // however many units stream
     int64_t best_chunk = kCandidates[0];
-    double best = -1.0;
+    double best = -1.0, even_first = -1.0;
     std::vector<double> tiles, load;
     std::vector<int32_t> bounds;
     for (int64_t c : kCandidates) {
@@ -131,6 +131,10 @@ static int64_t choose_mfma_chunk(const std::vector<RowBlock>& blocks, int G, int
             best_chunk = c;
         }
         if ((int64_t)tiles.size() * Hkv > 16LL * S) break;  // plenty of tiles already: smaller pieces only add partials
+        // Smaller pieces only add tiles, so `even` never falls below what the first candidate gives, and no later
+        // estimate can be below it: once the best estimate is within 1 % of that bound nothing can still win.
+        if (even_first < 0) even_first = even;
+        if (0.99 * best <= even_first) break;
     }
     return best_chunk;
 }
